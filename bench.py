@@ -1,0 +1,235 @@
+#!/usr/bin/env python3
+"""Benchmark of the ZSMerge budgeted KV-cache step on one MI355X.
+
+Workload (the benchmark definition's headline one): Llama2-7B shape, 32 layers x 32 KV heads
+= 1024 units, head_dim 128, fp16, a 54 000-token prompt compressed per head to 5 %
+(B = 2700 slots), then decode steps.  A "step" is one fused decode step of all 1024 units
+(all layers in one launch).  The prefill compression of the 32 layers runs on the device
+before the timed region and is reported beside it.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload 2] [--no-cpu-baseline]
+
+Prints one JSON line (rank 0).  Inputs are seeded synthetic data generated on the device
+before the timed region; everything the timed region reads is already resident in HBM.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import re
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0     # MI355X HBM3E, published peak
+
+
+def algorithmic_bytes_per_unit_step(B_tok: int, B_r: int, d: int, e: int, G: int) -> int:
+    """HBM bytes one unit must move in one decode step when every byte moves once.
+
+    token K and V rows once; residual K and V rows (fp32) once; per slot: score read + score
+    write + position read (12 B); q, k_new, v_new in; out (fp32) out; the evicted row re-read
+    and the incoming row written (K and V each); the merged residual row written back;
+    a few header words.
+    """
+    B = B_tok + B_r
+    kv = 2 * B_tok * d * e + 2 * B_r * d * 4
+    meta = 12 * B
+    io = (G + 2) * d * e + 4 * G * d
+    evict = 2 * d * e + 2 * d * e + 2 * d * 4
+    return kv + meta + io + evict + 40
+
+
+def read_traffic_from_profiles(name: str):
+    """HBM bytes per launch measured with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE), as recorded
+    in profiles/<name>.  Returns None when no such summary has been committed."""
+    p = os.path.join(ROOT, "profiles", name)
+    if not os.path.exists(p):
+        return None
+    m = re.search(r"traffic_bytes_per_launch:\s*([0-9.eE+]+)", open(p).read())
+    return float(m.group(1)) if m else None
+
+
+def cpu_baseline(wl, n_units: int, n_steps: int):
+    """The CPU oracle, as it stands, on a bounded sample of the same workload: `n_units`
+    units (layer 0, heads 0..) through their own prefill, then `n_steps` timed decode steps."""
+    import numpy as np
+    import torch
+    from oracle.zsmerge_oracle import UnitCache
+    from paper_2503_10714_amd import synth
+    try:
+        from threadpoolctl import threadpool_info
+        threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        threads = 1
+    sub = wl.sliced(n_layers=1, n_kv_heads=n_units)
+    dev = "cuda:0" if torch.cuda.is_available() else "cpu"
+    Q, K, V, lens = synth.prompt(sub, 0, device=dev)
+    f = lambda t: t.detach().to("cpu").to(torch.float64).numpy()
+    bp, bc, br = sub.budgets()
+    units = []
+    t0 = time.perf_counter()
+    for h in range(n_units):
+        u = UnitCache(sub.head_dim, sub.q_per_kv, bp[0], bc[0], br, lam=float(np.float32(sub.lam)), alpha=sub.alpha)
+        u.prefill_compress(f(Q[0, h]), f(K[0, h, :lens[0]]), f(V[0, h, :lens[0]]))
+        units.append(u)
+    t_prefill = time.perf_counter() - t0
+    q, k, v = synth.decode_inputs_uniform(sub, [0], list(range(n_steps)), device=dev)
+    q, k, v = f(q), f(k), f(v)
+    t0 = time.perf_counter()
+    for s in range(n_steps):
+        for h, u in enumerate(units):
+            u.decode_step(q[s, 0, 0, h], k[s, 0, 0, h], v[s, 0, 0, h])
+    t_decode = time.perf_counter() - t0
+    return {
+        "value": n_units * n_steps / t_decode, "unit": "unit-steps/s", "cores": int(threads), "kind": "oracle",
+        "sample": f"{n_units} units of layer 0 (T={lens[0]}, B={sub.slot_capacity}) x {n_steps} decode steps, NumPy fp64; "
+                  f"their oracle prefill took {t_prefill / n_units:.2f} s per unit (not in value)",
+    }
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=512)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", type=int, default=2)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-units", type=int, default=4)
+    ap.add_argument("--cpu-steps", type=int, default=512)
+    ap.add_argument("--skip-prefill", action="store_true",
+                    help="fill the cache by import of synthetic rows instead of running the prefill (profiling runs)")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on ONE GPU only (units are independent and would shard with no "
+              "exchange; no multi-GPU path is built). Use --gpus 1.", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2503_10714_amd import synth
+    from paper_2503_10714_amd import binding as zb
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    zb.lib()
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    wl = synth.workload(args.workload)
+    if wl.ragged is not None:
+        print("bench.py: ragged workloads are parity-test cases, not bench lines", file=sys.stderr)
+        sys.exit(2)
+    L, S, H, G, d = wl.n_layers, wl.n_seqs, wl.n_kv_heads, wl.q_per_kv, wl.head_dim
+    bp, bc, br = wl.budgets()
+    cache = zb.Cache(L, S, H, G, d, bp, bc, br, wl.dtype, lam=wl.lam, alpha=wl.alpha, slot_capacity=wl.slot_capacity, device=dev)
+    e = 4 if wl.dtype == "f32" else 2
+
+    # ---- prefill compression of every layer (device-generated prompts) -------------------
+    prefill_ms = None
+    t_setup = time.perf_counter()
+    if not args.skip_prefill:
+        ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        tot = 0.0
+        for l in range(L):
+            Q, K, V, lens = synth.prompt(wl, l, device=dev)
+            lens_t = torch.tensor(lens, dtype=torch.int32, device=dev)
+            torch.cuda.synchronize()
+            ev0.record()
+            cache.prefill_compress(l, Q, K, V, lens_t)
+            ev1.record()
+            torch.cuda.synchronize()
+            tot += ev0.elapsed_time(ev1)
+            del Q, K, V
+        prefill_ms = tot
+        cache.release_workspace()
+    else:
+        # every slot filled with synthetic rows: the decode kernel's traffic does not depend on how
+        for l in range(L):
+            K, V = synth.kv_rows(wl, l, torch.arange(wl.slot_capacity - br), device=dev)
+            n = wl.slot_capacity - br
+            pos = torch.full((S, H, wl.slot_capacity), -1, dtype=torch.int32, device=dev)
+            pos[..., br:] = torch.arange(n, dtype=torch.int32, device=dev) + (wl.prompt_len - n)
+            w = torch.zeros(S, H, wl.slot_capacity, dtype=torch.int32, device=dev)
+            w[..., br:] = 1
+            s = torch.rand(S, H, wl.slot_capacity, device=dev) * 0.01
+            cache.import_layer(l, K=K, V=V, s=s, pos=pos, w=w,
+                               n_seen=torch.full((S, H), wl.prompt_len, dtype=torch.int64, device=dev))
+    torch.cuda.empty_cache()
+
+    # ---- decode inputs for all steps, resident before the timed region -------------------
+    n_total = args.warmup + args.steps
+    q_all, k_all, v_all = synth.decode_inputs_uniform(wl, list(range(L)), list(range(n_total)), device=dev)
+    out = torch.empty(L, S, H, G, d, dtype=torch.float32, device=dev)
+    info = tuple(torch.empty(L, S, H, dtype=torch.int32, device=dev) for _ in range(3))
+    torch.cuda.synchronize()
+    setup_s = time.perf_counter() - t_setup
+
+    def step(i):
+        zb.zsm_decode_step(cache.handle, 0, L, q_all[i], k_all[i], v_all[i], out, info[0], info[1], info[2])
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    evs = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]
+    t0 = time.perf_counter()
+    evs[0].record()
+    for i in range(args.steps):
+        step(args.warmup + i)
+        evs[i + 1].record()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    gpu_ms = evs[0].elapsed_time(evs[-1])
+    per = sorted(evs[i].elapsed_time(evs[i + 1]) for i in range(args.steps))
+    ms_per_step = wall * 1e3 / args.steps
+    kernel_ms = gpu_ms / args.steps            # average launch duration over the timed region (HIP events)
+    units = wl.n_units
+    value = units * args.steps / wall
+
+    bytes_unit = algorithmic_bytes_per_unit_step(bp[0] + bc[0], br, d, e, G)
+    bytes_launch = bytes_unit * units
+    achieved = bytes_launch / (kernel_ms * 1e-3) / 1e9
+    traffic = read_traffic_from_profiles(f"decode_step_cfg{args.workload}_pmc.md")
+
+    # achievable read rate on this machine: plain streaming read of the cache buffer
+    sink = torch.zeros(4, dtype=torch.float32, device=dev)
+    nb = (cache.buf.numel() // 16) * 16
+    for _ in range(3):
+        zb.zsm_stream_read(cache.buf[:nb], sink)
+    torch.cuda.synchronize()
+    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    a.record()
+    for _ in range(10):
+        zb.zsm_stream_read(cache.buf[:nb], sink)
+    b.record()
+    torch.cuda.synchronize()
+    read_ceiling = nb * 10 / (a.elapsed_time(b) * 1e-3) / 1e9
+
+    res = {
+        "metric": "decode unit-steps/s (layer x head x batch units per second, fused ZSMerge decode step)",
+        "value": value, "unit": "unit-steps/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": wl.dtype, "data": "synthetic",
+        "config": {"workload": f"cfg{args.workload} {wl.name}: {L} layers x {S} seq x {H} KV heads = {units} units, G={G}, d={d}, "
+                               f"{wl.dtype} KV, prompt {wl.prompt_len} tokens -> B={wl.slot_capacity} slots "
+                               f"(B_p={bp[0]}, B_c={bc[0]}, B_r={br}), all layers in one launch",
+                   "units": units, "slots_per_unit": wl.slot_capacity},
+        "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
+                     "traffic": traffic, "kernel": "zsm::decode_kernel", "kernel_ms": kernel_ms,
+                     "algorithmic_bytes_per_launch": bytes_launch},
+        "step_ms_p10_p50_p90": [per[len(per) // 10], per[len(per) // 2], per[(9 * len(per)) // 10]],
+        "tokens_per_s_cache_step_only": value / (L * H) if S == 1 else None,
+        "hbm_read_ceiling_GBs": read_ceiling,
+        "prefill_compress_ms_all_layers": prefill_ms,
+        "setup_s": setup_s,
+    }
+    if not args.no_cpu_baseline:
+        res["cpu_baseline"] = cpu_baseline(wl, args.cpu_units, args.cpu_steps)
+    print(json.dumps(res))
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,170 @@
+/*
+ * zsm.h - C ABI of the ZSMerge budgeted KV-cache step for MI355X (gfx950).
+ *
+ * One "unit" is one (layer, sequence, KV head).  A unit owns B = B_r + B_c + B_p cache
+ * slots (budget split of Sec. 3.2, Eq. 2): slots [0, B_r) are residual slots that hold
+ * incremental means of evicted tokens, slots [B_r, B) hold single tokens.  All units are
+ * independent; every entry point works on many units per launch.
+ *
+ * Conventions
+ *   - Every pointer named "device" is HIP device memory owned by the caller (the Python
+ *     binding passes torch tensors' data pointers).  Host pointers are read during the
+ *     call only.  The library owns nothing but the small host descriptor zsm_cache_t.
+ *   - Device tensors are contiguous, row-major in the index order written next to them,
+ *     and 16-byte aligned.  Q/K/V inputs and token slots use the cache's kv_dtype;
+ *     residual slots, scores and attention outputs are fp32; counts and positions int32.
+ *   - `stream` is a hipStream_t (NULL = the default stream).  Calls only enqueue work;
+ *     they never synchronise, allocate or free device memory.
+ *   - Return value: ZSM_OK or a negative zsm_status.  Arguments are validated on the
+ *     host before anything is enqueued, so a failed call leaves the cache untouched.
+ *   - One stream per cache at a time; calls on one cache must not overlap.
+ */
+#ifndef ZSM_H
+#define ZSM_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct zsm_cache zsm_cache_t;
+
+enum zsm_dtype { ZSM_F32 = 0, ZSM_F16 = 1, ZSM_BF16 = 2 };
+
+enum zsm_status {
+    ZSM_OK = 0,
+    ZSM_E_NULL = -1,   /* a required pointer is NULL                                  */
+    ZSM_E_SHAPE = -2,  /* unsupported or inconsistent sizes                            */
+    ZSM_E_DTYPE = -3,  /* unknown kv_dtype                                             */
+    ZSM_E_ALIGN = -4,  /* a device pointer is not 16-byte aligned                      */
+    ZSM_E_NOMEM = -5,  /* caller's buffer or workspace is too small                    */
+    ZSM_E_RANGE = -6,  /* layer index / range outside the cache                        */
+    ZSM_E_HIP = -7     /* the HIP runtime refused a launch (text via zsm_strerror)     */
+};
+
+typedef struct {
+    int32_t n_layers;       /* L                                                        */
+    int32_t n_seqs;         /* S: sequences in the batch                                */
+    int32_t n_kv_heads;     /* H: KV heads per layer                                    */
+    int32_t q_per_kv;       /* G: query heads sharing one KV head (1, 2, 4 or 8)        */
+    int32_t head_dim;       /* d: 64 or 128                                             */
+    int32_t slot_capacity;  /* slot stride: max over sequences of B_r + B_c + B_p       */
+    int32_t n_residual;     /* B_r (0 = pure eviction, Sec. 3.2)                        */
+    int32_t kv_dtype;       /* enum zsm_dtype                                           */
+    float lambda;           /* score decay of Eq. 3 (paper: 0.98)                       */
+    float alpha;            /* weight of log w in Eq. 4, in [0, 1] (paper: 1)           */
+    float scale;            /* logit scale; 0 selects 1/sqrt(d) (Eq. 1)                 */
+} zsm_config_t;
+
+/* Bytes of device memory a cache of this shape needs (0 if the config is invalid). */
+size_t zsm_cache_bytes(const zsm_config_t* cfg);
+
+/*
+ * zsm_cache_alloc - lay a cache out in the caller's device buffer and empty it
+ * (Alg. 1 "Init": all three regions empty, no token seen).
+ *   B_p, B_c   host arrays [n_seqs]: proximity and context budgets of each sequence
+ *              (Eq. 2); B_p >= 1, B_c >= 0, B_r + B_c + B_p <= slot_capacity.
+ *   dev_buf    device, 256-byte aligned, dev_bytes >= zsm_cache_bytes(cfg).
+ *   out        receives the descriptor; release it with zsm_cache_free (the device
+ *              buffer stays the caller's).
+ */
+int zsm_cache_alloc(const zsm_config_t* cfg, const int32_t* B_p, const int32_t* B_c,
+                    void* dev_buf, size_t dev_bytes, void* stream, zsm_cache_t** out);
+int zsm_cache_free(zsm_cache_t* cache);
+
+/* Bytes of device workspace zsm_prefill_compress needs for prompts of up to T_max
+ * tokens scored from W query rows (0 on invalid arguments). */
+size_t zsm_prefill_workspace_bytes(const zsm_cache_t* cache, int32_t T_max, int32_t W);
+
+/*
+ * zsm_prefill_compress - one-shot compression of one layer's prompts into the (empty)
+ * cache of that layer.
+ *   Scores: Eq. 3 unrolled over the last n_b = min(W, T_b) prompt queries, each query a
+ *   causal softmax row (Eq. 1), grouped query heads pooled by their mean (appendix, GQA
+ *   adaptation); W >= T_max is the full-history initialisation, a smaller W the
+ *   windowed one (appendix "Implementation Details").
+ *   Selection: the latest B_p tokens plus the top-B_c of the others by score (Sec. 3.2);
+ *   equal scores keep the earlier position.  A prompt with T_b <= B_p + B_c is kept whole.
+ *   Residual: every token not kept is absorbed in position order as in Alg. 1's
+ *   residual branch (Eq. 5, Eq. 6).
+ *   Slot order afterwards: residual slots, context tokens by position, proximity tokens
+ *   by position.
+ *   Q          device [S, H, G, W, d]; row r of sequence b is the query at position
+ *              T_b - n_b + r; rows r >= n_b are ignored.
+ *   K, V       device [S, H, T_max, d]; rows >= T_b are ignored.
+ *   seq_lens   device int32 [S]: T_b, 0 <= T_b <= T_max.
+ *   workspace  device, 256-byte aligned, ws_bytes >= zsm_prefill_workspace_bytes().
+ * The layer's cache must be empty (freshly allocated or re-imported empty).
+ * B_r > 1 is accepted by the decode step; this call currently supports B_r <= 1 and
+ * returns ZSM_E_SHAPE otherwise.
+ */
+int zsm_prefill_compress(zsm_cache_t* cache, int32_t layer, const void* Q, int32_t W,
+                         const void* K, const void* V, const int32_t* seq_lens,
+                         int32_t T_max, void* workspace, size_t ws_bytes, void* stream);
+
+/*
+ * zsm_decode_step - one fused decode step (the loop body of Alg. 1 with the attention
+ * of Eq. 4) for every unit of layers [layer_begin, layer_end).  Per unit, with T tokens
+ * seen so far:
+ *   1. logits q.k/sqrt(d) + alpha*log(w) over the occupied slots and the incoming token
+ *      itself, softmax, output (Eq. 4); one softmax per query head;
+ *   2. scores s <- lambda*s + mean over the group of the probabilities; the incoming
+ *      token starts at its own probability (Eq. 3);
+ *   3. if a token slot is free the incoming token takes the lowest free one; otherwise
+ *      the token with the lowest (score, position) among those outside the latest B_p
+ *      positions (incoming token counted) is evicted (Alg. 1, context overflow);
+ *   4. the evicted key/value opens the lowest unused residual slot, or is merged into
+ *      the residual slot with the largest key dot product (lowest index on ties) by the
+ *      incremental mean, whose count grows by one (Eq. 5, Eq. 6); B_r = 0 drops it;
+ *   5. the incoming token is written to the freed slot with position T.
+ *   q            device [Ln, S, H, G, d], Ln = layer_end - layer_begin
+ *   k_new,v_new  device [Ln, S, H, d]
+ *   out          device fp32 [Ln, S, H, G, d]
+ *   write_slot   device int32 [Ln, S, H] or NULL: slot that received the token
+ *   evicted_pos  device int32 [Ln, S, H] or NULL: position of the evicted token, -1 if none
+ *   merged_slot  device int32 [Ln, S, H] or NULL: residual slot that absorbed it, -1 if none
+ * Limit: (slot_capacity + 1) * G * 8 bytes of per-unit logits must fit the 160 KB LDS
+ * together with ~24 KB of staging, else ZSM_E_SHAPE.
+ */
+int zsm_decode_step(zsm_cache_t* cache, int32_t layer_begin, int32_t layer_end,
+                    const void* q, const void* k_new, const void* v_new, float* out,
+                    int32_t* write_slot, int32_t* evicted_pos, int32_t* merged_slot,
+                    void* stream);
+
+/*
+ * zsm_cache_export / zsm_cache_import - copy one layer's state out of / into the cache
+ * (checkpointing and test hook).  All arrays are device memory; any may be NULL to skip.
+ *   K, V    kv_dtype [S, H, slot_capacity - B_r, d]   token slots
+ *   Kr, Vr  fp32     [S, H, B_r, d]                    residual slots
+ *   s       fp32     [S, H, slot_capacity]             scores, slot order (residual first)
+ *   pos     int32    [S, H, slot_capacity]             original position, -1 = empty
+ *   w       int32    [S, H, slot_capacity]             fusion count, 0 = empty
+ *   n_seen  int64    [S, H]                            tokens seen (T)
+ * Import trusts the caller: token slots must have w in {0,1} with w = 0 exactly where
+ * pos = -1, and positions below n_seen.
+ */
+int zsm_cache_export(const zsm_cache_t* cache, int32_t layer, void* K, void* V, float* Kr,
+                     float* Vr, float* s, int32_t* pos, int32_t* w, int64_t* n_seen,
+                     void* stream);
+int zsm_cache_import(zsm_cache_t* cache, int32_t layer, const void* K, const void* V,
+                     const float* Kr, const float* Vr, const float* s, const int32_t* pos,
+                     const int32_t* w, const int64_t* n_seen, void* stream);
+
+/*
+ * zsm_stream_read / zsm_stream_copy - plain streaming kernels of known size, used to
+ * calibrate hardware counters and to measure the achievable HBM rate next to the decode
+ * step.  `src`/`dst` device, 16-byte aligned, `bytes` a multiple of 16.  zsm_stream_read
+ * sums the buffer into sink[0] (fp32, device) so the reads cannot be elided.
+ */
+int zsm_stream_read(const void* src, size_t bytes, float* sink, void* stream);
+int zsm_stream_copy(void* dst, const void* src, size_t bytes, void* stream);
+
+/* Text for a status code; for ZSM_E_HIP the last HIP error text of this thread. */
+const char* zsm_strerror(int status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ZSM_H */

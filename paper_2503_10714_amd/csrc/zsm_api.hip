@@ -1,0 +1,353 @@
+// Host side of the C ABI declared in include/zsm.h: argument checks, cache layout,
+// launches.  No device memory is allocated or freed here.
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <vector>
+
+#include "../../include/zsm.h"
+#include "zsm_common.hpp"
+#include "zsm_decode.hpp"
+#include "zsm_prefill.hpp"
+
+using namespace zsm;
+
+struct zsm_cache {
+    zsm_config_t cfg;
+    CacheView cv;
+    std::vector<int32_t> Bp, Bc;
+    size_t bytes;
+    int max_btok;   // max over sequences of B_p + B_c
+};
+
+namespace {
+
+thread_local char g_hip_msg[256] = "no HIP error recorded";
+
+int hip_fail(hipError_t e, const char* what) {
+    std::snprintf(g_hip_msg, sizeof(g_hip_msg), "%s: %s", what, hipGetErrorString(e));
+    return ZSM_E_HIP;
+}
+
+size_t esize(int dtype) { return dtype == ZSM_F32 ? 4 : 2; }
+size_t up256(size_t x) { return (x + 255) & ~(size_t)255; }
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }
+
+bool config_ok(const zsm_config_t* c) {
+    if (!c) return false;
+    if (c->n_layers < 1 || c->n_seqs < 1 || c->n_kv_heads < 1) return false;
+    if (!(c->q_per_kv == 1 || c->q_per_kv == 2 || c->q_per_kv == 4 || c->q_per_kv == 8)) return false;
+    if (!(c->head_dim == 64 || c->head_dim == 128)) return false;
+    if (c->n_residual < 0 || c->slot_capacity < c->n_residual + 1) return false;
+    if (!(c->lambda >= 0.f && c->lambda <= 1.f) || !(c->alpha >= 0.f && c->alpha <= 1.f)) return false;
+    if (!(c->scale >= 0.f)) return false;
+    if ((int64_t)c->n_layers * c->n_seqs * c->n_kv_heads > (int64_t)0x7fffffff) return false;
+    return true;
+}
+
+// Section offsets inside the caller's buffer.
+struct Layout {
+    size_t Bp, Bc, n_seen, n_occ, s, pos, w, Kr, Vr, Kt, Vt, total;
+};
+
+Layout make_layout(const zsm_config_t& c) {
+    const size_t units = (size_t)c.n_layers * c.n_seqs * c.n_kv_heads;
+    const size_t cap = c.slot_capacity, Br = c.n_residual, D = c.head_dim;
+    Layout l{};
+    size_t o = 0;
+    l.Bp = o; o += up256(sizeof(int32_t) * c.n_seqs);
+    l.Bc = o; o += up256(sizeof(int32_t) * c.n_seqs);
+    l.n_seen = o; o += up256(sizeof(int64_t) * units);
+    l.n_occ = o; o += up256(sizeof(int32_t) * units);
+    l.s = o; o += up256(sizeof(float) * units * cap);
+    l.pos = o; o += up256(sizeof(int32_t) * units * cap);
+    l.w = o; o += up256(sizeof(int32_t) * units * cap);
+    l.Kr = o; o += up256(sizeof(float) * units * Br * D);
+    l.Vr = o; o += up256(sizeof(float) * units * Br * D);
+    l.Kt = o; o += up256(esize(c.kv_dtype) * units * (cap - Br) * D);
+    l.Vt = o; o += up256(esize(c.kv_dtype) * units * (cap - Br) * D);
+    l.total = o;
+    return l;
+}
+
+// ---- small kernels ---------------------------------------------------------------------
+
+__global__ void fill_i32_kernel(int32_t* p, size_t n, int32_t v) {
+    for (size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x) p[i] = v;
+}
+
+// after an import: count the occupied token slots of every unit of one layer
+__global__ void recount_kernel(CacheView cv, int unit0) {
+    const int ug = unit0 + blockIdx.x;
+    const int b = (ug / cv.H) % cv.S;
+    const int ntok = cv.Bp[b] + cv.Bc[b];
+    const int32_t* pos = cv.pos + (size_t)ug * cv.cap + cv.Br;
+    int n = 0;
+    for (int j = threadIdx.x; j < ntok; j += blockDim.x) n += pos[j] >= 0;
+    __shared__ int red[4];
+    for (int o = 32; o > 0; o >>= 1) n += __shfl_xor(n, o, 64);
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = n;
+    __syncthreads();
+    if (threadIdx.x == 0) cv.n_occ[ug] = red[0] + red[1] + red[2] + red[3];
+}
+
+__global__ __launch_bounds__(256) void stream_read_kernel(const uint4* __restrict__ src, size_t n16, float* sink) {
+    float acc = 0.f;
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x; i < n16; i += stride) {
+        const uint4 v = src[i];
+        acc += __uint_as_float(v.x ^ v.y ^ v.z ^ v.w);
+    }
+    acc = wave_sum(acc);
+    if ((threadIdx.x & 63) == 0 && acc == 123.456f) sink[0] = acc;   // practically never taken; keeps the loads live
+}
+
+__global__ __launch_bounds__(256) void stream_copy_kernel(uint4* __restrict__ dst, const uint4* __restrict__ src, size_t n16) {
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x; i < n16; i += stride) dst[i] = src[i];
+}
+
+int check_layer(const zsm_cache_t* c, int layer) {
+    if (!c) return ZSM_E_NULL;
+    if (layer < 0 || layer >= c->cfg.n_layers) return ZSM_E_RANGE;
+    return ZSM_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+size_t zsm_cache_bytes(const zsm_config_t* cfg) {
+    if (!config_ok(cfg) || cfg->kv_dtype < ZSM_F32 || cfg->kv_dtype > ZSM_BF16) return 0;
+    return make_layout(*cfg).total;
+}
+
+int zsm_cache_alloc(const zsm_config_t* cfg, const int32_t* B_p, const int32_t* B_c, void* dev_buf,
+                    size_t dev_bytes, void* stream, zsm_cache_t** out) {
+    if (!cfg || !B_p || !B_c || !dev_buf || !out) return ZSM_E_NULL;
+    if (cfg->kv_dtype < ZSM_F32 || cfg->kv_dtype > ZSM_BF16) return ZSM_E_DTYPE;
+    if (!config_ok(cfg)) return ZSM_E_SHAPE;
+    int max_btok = 0;
+    for (int b = 0; b < cfg->n_seqs; ++b) {
+        if (B_p[b] < 1 || B_c[b] < 0) return ZSM_E_SHAPE;
+        if ((int64_t)B_p[b] + B_c[b] + cfg->n_residual > cfg->slot_capacity) return ZSM_E_SHAPE;
+        max_btok = B_p[b] + B_c[b] > max_btok ? B_p[b] + B_c[b] : max_btok;
+    }
+    if ((reinterpret_cast<uintptr_t>(dev_buf) & 255) != 0) return ZSM_E_ALIGN;
+    const Layout lay = make_layout(*cfg);
+    if (dev_bytes < lay.total) return ZSM_E_NOMEM;
+
+    zsm_cache_t* c = new (std::nothrow) zsm_cache_t();
+    if (!c) return ZSM_E_NOMEM;
+    c->cfg = *cfg;
+    c->Bp.assign(B_p, B_p + cfg->n_seqs);
+    c->Bc.assign(B_c, B_c + cfg->n_seqs);
+    c->bytes = lay.total;
+    c->max_btok = max_btok;
+    char* base = static_cast<char*>(dev_buf);
+    CacheView& v = c->cv;
+    v.L = cfg->n_layers; v.S = cfg->n_seqs; v.H = cfg->n_kv_heads; v.G = cfg->q_per_kv; v.D = cfg->head_dim;
+    v.cap = cfg->slot_capacity; v.Br = cfg->n_residual; v.cap_tok = v.cap - v.Br; v.dtype = cfg->kv_dtype;
+    v.lambda = cfg->lambda; v.alpha = cfg->alpha;
+    v.scale = cfg->scale > 0.f ? (double)cfg->scale : 1.0 / std::sqrt((double)cfg->head_dim);
+    v.Bp = reinterpret_cast<int32_t*>(base + lay.Bp);
+    v.Bc = reinterpret_cast<int32_t*>(base + lay.Bc);
+    v.n_seen = reinterpret_cast<int64_t*>(base + lay.n_seen);
+    v.n_occ = reinterpret_cast<int32_t*>(base + lay.n_occ);
+    v.s = reinterpret_cast<float*>(base + lay.s);
+    v.pos = reinterpret_cast<int32_t*>(base + lay.pos);
+    v.w = reinterpret_cast<int32_t*>(base + lay.w);
+    v.Kr = reinterpret_cast<float*>(base + lay.Kr);
+    v.Vr = reinterpret_cast<float*>(base + lay.Vr);
+    v.Kt = base + lay.Kt;
+    v.Vt = base + lay.Vt;
+
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const size_t units = (size_t)v.L * v.S * v.H;
+    hipError_t e;
+    // budgets: pageable host -> device copies are staged by the runtime before the call returns
+    e = hipMemcpyAsync(v.Bp, c->Bp.data(), sizeof(int32_t) * v.S, hipMemcpyHostToDevice, st);
+    if (e == hipSuccess) e = hipMemcpyAsync(v.Bc, c->Bc.data(), sizeof(int32_t) * v.S, hipMemcpyHostToDevice, st);
+    if (e != hipSuccess) { delete c; return hip_fail(e, "zsm_cache_alloc budgets"); }
+    // empty state: pos = -1, everything else 0 (fill kernels, no memset nodes)
+    const size_t n_zero_words = (lay.pos - lay.n_seen) / 4;   // n_seen, n_occ, s
+    hipLaunchKernelGGL(fill_i32_kernel, dim3(1024), dim3(256), 0, st, reinterpret_cast<int32_t*>(base + lay.n_seen), n_zero_words, 0);
+    hipLaunchKernelGGL(fill_i32_kernel, dim3(1024), dim3(256), 0, st, v.pos, units * v.cap, -1);
+    const size_t n_rest_words = (lay.total - lay.w) / 4;      // w, Kr, Vr, Kt, Vt
+    hipLaunchKernelGGL(fill_i32_kernel, dim3(1024), dim3(256), 0, st, v.w, n_rest_words, 0);
+    e = hipGetLastError();
+    if (e != hipSuccess) { delete c; return hip_fail(e, "zsm_cache_alloc init"); }
+    *out = c;
+    return ZSM_OK;
+}
+
+int zsm_cache_free(zsm_cache_t* cache) {
+    if (!cache) return ZSM_E_NULL;
+    delete cache;
+    return ZSM_OK;
+}
+
+int zsm_decode_step(zsm_cache_t* cache, int32_t layer_begin, int32_t layer_end, const void* q,
+                    const void* k_new, const void* v_new, float* out, int32_t* write_slot,
+                    int32_t* evicted_pos, int32_t* merged_slot, void* stream) {
+    if (!cache || !q || !k_new || !v_new || !out) return ZSM_E_NULL;
+    if (layer_begin < 0 || layer_end > cache->cfg.n_layers || layer_begin >= layer_end) return ZSM_E_RANGE;
+    if (!aligned16(q) || !aligned16(k_new) || !aligned16(v_new) || !aligned16(out)) return ZSM_E_ALIGN;
+    const CacheView& v = cache->cv;
+    size_t lds;
+    switch (v.dtype) {
+        case ZSM_F32: lds = decode_lds_f32(v.D, v.G, v.cap); break;
+        case ZSM_F16: lds = decode_lds_f16(v.D, v.G, v.cap); break;
+        default: lds = decode_lds_bf16(v.D, v.G, v.cap); break;
+    }
+    if (lds > 160 * 1024) return ZSM_E_SHAPE;
+    DecodeArgs a;
+    a.cv = v;
+    a.unit0 = layer_begin * v.S * v.H;
+    a.n_units = (layer_end - layer_begin) * v.S * v.H;
+    a.q = q; a.k_new = k_new; a.v_new = v_new; a.out = out;
+    a.write_slot = write_slot; a.evicted_pos = evicted_pos; a.merged_slot = merged_slot;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    hipError_t e;
+    switch (v.dtype) {
+        case ZSM_F32: e = launch_decode_f32(a, st); break;
+        case ZSM_F16: e = launch_decode_f16(a, st); break;
+        default: e = launch_decode_bf16(a, st); break;
+    }
+    if (e != hipSuccess) return hip_fail(e, "zsm_decode_step launch");
+    return ZSM_OK;
+}
+
+size_t zsm_prefill_workspace_bytes(const zsm_cache_t* cache, int32_t T_max, int32_t W) {
+    if (!cache || T_max < 1 || W < 1) return 0;
+    return prefill_workspace_bytes(cache->cv, T_max, W);
+}
+
+int zsm_prefill_compress(zsm_cache_t* cache, int32_t layer, const void* Q, int32_t W, const void* K,
+                         const void* V, const int32_t* seq_lens, int32_t T_max, void* workspace,
+                         size_t ws_bytes, void* stream) {
+    if (!cache || !Q || !K || !V || !seq_lens || !workspace) return ZSM_E_NULL;
+    int rc = check_layer(cache, layer);
+    if (rc) return rc;
+    if (T_max < 1 || W < 1) return ZSM_E_SHAPE;
+    if (cache->cfg.n_residual > 1) return ZSM_E_SHAPE;
+    if (!aligned16(Q) || !aligned16(K) || !aligned16(V)) return ZSM_E_ALIGN;
+    if ((reinterpret_cast<uintptr_t>(workspace) & 255) != 0) return ZSM_E_ALIGN;
+    if (ws_bytes < prefill_workspace_bytes(cache->cv, T_max, W)) return ZSM_E_NOMEM;
+    PrefillArgs a;
+    a.cv = cache->cv;
+    a.unit0 = layer * cache->cv.S * cache->cv.H;
+    a.n_units = cache->cv.S * cache->cv.H;
+    a.Q = Q; a.K = K; a.V = V; a.seq_lens = seq_lens; a.W = W; a.T_max = T_max;
+    a.ws = static_cast<char*>(workspace);
+    hipError_t e = launch_prefill(a, static_cast<hipStream_t>(stream));
+    if (e != hipSuccess) return hip_fail(e, "zsm_prefill_compress launch");
+    return ZSM_OK;
+}
+
+static int xfer(const zsm_cache_t* c, int layer, void* K, void* V, float* Kr, float* Vr, float* s,
+                int32_t* pos, int32_t* w, int64_t* n_seen, hipStream_t st, bool to_cache) {
+    const CacheView& v = c->cv;
+    const size_t lu = (size_t)v.S * v.H, u0 = (size_t)layer * lu;
+    const size_t es = esize(v.dtype);
+    struct Seg { void* user; char* mine; size_t bytes; };
+    const Seg segs[] = {
+        {K, static_cast<char*>(v.Kt) + u0 * v.cap_tok * v.D * es, lu * v.cap_tok * v.D * es},
+        {V, static_cast<char*>(v.Vt) + u0 * v.cap_tok * v.D * es, lu * v.cap_tok * v.D * es},
+        {Kr, reinterpret_cast<char*>(v.Kr + u0 * v.Br * v.D), lu * v.Br * v.D * sizeof(float)},
+        {Vr, reinterpret_cast<char*>(v.Vr + u0 * v.Br * v.D), lu * v.Br * v.D * sizeof(float)},
+        {s, reinterpret_cast<char*>(v.s + u0 * v.cap), lu * v.cap * sizeof(float)},
+        {pos, reinterpret_cast<char*>(v.pos + u0 * v.cap), lu * v.cap * sizeof(int32_t)},
+        {w, reinterpret_cast<char*>(v.w + u0 * v.cap), lu * v.cap * sizeof(int32_t)},
+        {n_seen, reinterpret_cast<char*>(v.n_seen + u0), lu * sizeof(int64_t)},
+    };
+    for (const Seg& g : segs) {
+        if (!g.user || g.bytes == 0) continue;
+        if (!aligned16(g.user)) return ZSM_E_ALIGN;
+    }
+    for (const Seg& g : segs) {
+        if (!g.user || g.bytes == 0) continue;
+        const size_t n16 = g.bytes / 16, rem = g.bytes % 16;
+        char* dst = to_cache ? g.mine : static_cast<char*>(g.user);
+        const char* src = to_cache ? static_cast<const char*>(g.user) : g.mine;
+        if (n16) {
+            const int blocks = (int)((n16 + 255) / 256 > 4096 ? 4096 : (n16 + 255) / 256);
+            hipLaunchKernelGGL(stream_copy_kernel, dim3(blocks), dim3(256), 0, st, reinterpret_cast<uint4*>(dst),
+                               reinterpret_cast<const uint4*>(src), n16);
+        }
+        if (rem) {
+            hipError_t e = hipMemcpyAsync(dst + n16 * 16, src + n16 * 16, rem, hipMemcpyDeviceToDevice, st);
+            if (e != hipSuccess) return hip_fail(e, "zsm_cache transfer tail");
+        }
+    }
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return hip_fail(e, "zsm_cache transfer");
+    return ZSM_OK;
+}
+
+int zsm_cache_export(const zsm_cache_t* cache, int32_t layer, void* K, void* V, float* Kr, float* Vr,
+                     float* s, int32_t* pos, int32_t* w, int64_t* n_seen, void* stream) {
+    int rc = check_layer(cache, layer);
+    if (rc) return rc;
+    return xfer(cache, layer, K, V, Kr, Vr, s, pos, w, n_seen, static_cast<hipStream_t>(stream), false);
+}
+
+int zsm_cache_import(zsm_cache_t* cache, int32_t layer, const void* K, const void* V, const float* Kr,
+                     const float* Vr, const float* s, const int32_t* pos, const int32_t* w,
+                     const int64_t* n_seen, void* stream) {
+    int rc = check_layer(cache, layer);
+    if (rc) return rc;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    rc = xfer(cache, layer, const_cast<void*>(K), const_cast<void*>(V), const_cast<float*>(Kr),
+              const_cast<float*>(Vr), const_cast<float*>(s), const_cast<int32_t*>(pos),
+              const_cast<int32_t*>(w), const_cast<int64_t*>(n_seen), st, true);
+    if (rc) return rc;
+    const int lu = cache->cv.S * cache->cv.H;
+    hipLaunchKernelGGL(recount_kernel, dim3(lu), dim3(256), 0, st, cache->cv, layer * lu);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return hip_fail(e, "zsm_cache_import recount");
+    return ZSM_OK;
+}
+
+int zsm_stream_read(const void* src, size_t bytes, float* sink, void* stream) {
+    if (!src || !sink) return ZSM_E_NULL;
+    if (!aligned16(src)) return ZSM_E_ALIGN;
+    if (bytes % 16) return ZSM_E_SHAPE;
+    if (bytes == 0) return ZSM_OK;
+    hipLaunchKernelGGL(stream_read_kernel, dim3(256 * 16), dim3(256), 0, static_cast<hipStream_t>(stream),
+                       static_cast<const uint4*>(src), bytes / 16, sink);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return hip_fail(e, "zsm_stream_read");
+    return ZSM_OK;
+}
+
+int zsm_stream_copy(void* dst, const void* src, size_t bytes, void* stream) {
+    if (!src || !dst) return ZSM_E_NULL;
+    if (!aligned16(src) || !aligned16(dst)) return ZSM_E_ALIGN;
+    if (bytes % 16) return ZSM_E_SHAPE;
+    if (bytes == 0) return ZSM_OK;
+    hipLaunchKernelGGL(stream_copy_kernel, dim3(256 * 16), dim3(256), 0, static_cast<hipStream_t>(stream),
+                       static_cast<uint4*>(dst), static_cast<const uint4*>(src), bytes / 16);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return hip_fail(e, "zsm_stream_copy");
+    return ZSM_OK;
+}
+
+const char* zsm_strerror(int status) {
+    switch (status) {
+        case ZSM_OK: return "ok";
+        case ZSM_E_NULL: return "a required pointer is NULL";
+        case ZSM_E_SHAPE: return "unsupported or inconsistent sizes";
+        case ZSM_E_DTYPE: return "unknown kv_dtype";
+        case ZSM_E_ALIGN: return "device pointer not sufficiently aligned";
+        case ZSM_E_NOMEM: return "buffer or workspace too small";
+        case ZSM_E_RANGE: return "layer index or range outside the cache";
+        case ZSM_E_HIP: return g_hip_msg;
+        default: return "unknown status";
+    }
+}
+
+}  // extern "C"

@@ -1,0 +1,115 @@
+// Shared device-side definitions of the ZSMerge cache step (gfx950 only).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace zsm {
+
+typedef _Float16 f16_t;
+struct bf16_t { uint16_t bits; };
+
+// Where one cache lives in the caller's device buffer.  Every array is indexed by the
+// global unit number ug = (layer * S + seq) * H + head, slots within a unit by slot index.
+struct CacheView {
+    int32_t L, S, H, G, D;
+    int32_t cap;        // slot stride (slot_capacity)
+    int32_t Br;         // residual slots per unit
+    int32_t cap_tok;    // cap - Br
+    int32_t dtype;
+    float lambda, alpha;   // used as (double)lambda, (double)alpha
+    double scale;          // logit scale (1/sqrt(d) in fp64 unless the caller set one)
+    int32_t* Bp;        // [S]
+    int32_t* Bc;        // [S]
+    int64_t* n_seen;    // [units]   tokens seen (T)
+    int32_t* n_occ;     // [units]   occupied token slots
+    float* s;           // [units][cap]
+    int32_t* pos;       // [units][cap]
+    int32_t* w;         // [units][cap]
+    float* Kr;          // [units][Br][D]
+    float* Vr;
+    void* Kt;           // [units][cap_tok][D] in kv dtype
+    void* Vt;
+};
+
+// ---- element access -------------------------------------------------------------------
+// load_seg<KT, N>(p, out): N consecutive elements starting at p (16-byte aligned when
+// N * sizeof(KT) is a multiple of 16) converted to float.
+
+template <int N>
+__device__ __forceinline__ void load_seg(const float* p, float* out) {
+    static_assert(N % 4 == 0, "");
+#pragma unroll
+    for (int i = 0; i < N / 4; ++i) {
+        const float4 v = reinterpret_cast<const float4*>(p)[i];
+        out[4 * i + 0] = v.x; out[4 * i + 1] = v.y; out[4 * i + 2] = v.z; out[4 * i + 3] = v.w;
+    }
+}
+
+template <int N>
+__device__ __forceinline__ void load_seg(const f16_t* p, float* out) {
+    static_assert(N % 8 == 0, "");
+    typedef f16_t h8 __attribute__((ext_vector_type(8)));
+#pragma unroll
+    for (int i = 0; i < N / 8; ++i) {
+        const h8 v = reinterpret_cast<const h8*>(p)[i];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) out[8 * i + e] = (float)v[e];
+    }
+}
+
+template <int N>
+__device__ __forceinline__ void load_seg(const bf16_t* p, float* out) {
+    static_assert(N % 8 == 0, "");
+#pragma unroll
+    for (int i = 0; i < N / 8; ++i) {
+        const uint4 v = reinterpret_cast<const uint4*>(p)[i];
+        const uint32_t d[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            out[8 * i + 2 * e + 0] = __uint_as_float(d[e] << 16);
+            out[8 * i + 2 * e + 1] = __uint_as_float(d[e] & 0xffff0000u);
+        }
+    }
+}
+
+__device__ __forceinline__ float to_float(float x) { return x; }
+__device__ __forceinline__ float to_float(f16_t x) { return (float)x; }
+__device__ __forceinline__ float to_float(bf16_t x) { return __uint_as_float(((uint32_t)x.bits) << 16); }
+
+// ---- wave-level helpers (64 lanes) ----------------------------------------------------
+
+// Orders LDS traffic between lanes of one wave: a later read by any lane sees an earlier
+// write by any lane (LDS executes a wave's instructions in order; this only stops the
+// compiler from moving them).
+__device__ __forceinline__ void wave_sync() {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
+    return v;
+}
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+    return v;
+}
+__device__ __forceinline__ double wave_sum(double v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+    return v;
+}
+__device__ __forceinline__ unsigned long long wave_min(unsigned long long v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+        const unsigned long long t = __shfl_xor(v, o, 64);
+        v = t < v ? t : v;
+    }
+    return v;
+}
+
+}  // namespace zsm

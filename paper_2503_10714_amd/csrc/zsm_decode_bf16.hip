@@ -1,0 +1,7 @@
+// Decode-step instantiations for bf16 token slots.
+#include "zsm_decode.hpp"
+
+namespace zsm {
+hipError_t launch_decode_bf16(const DecodeArgs& a, hipStream_t stream) { return launch_decode_t<bf16_t>(a, stream); }
+size_t decode_lds_bf16(int D, int G, int cap) { return decode_lds_t<bf16_t>(D, G, cap); }
+}  // namespace zsm

@@ -1,0 +1,7 @@
+// Decode-step instantiations for f16 token slots.
+#include "zsm_decode.hpp"
+
+namespace zsm {
+hipError_t launch_decode_f16(const DecodeArgs& a, hipStream_t stream) { return launch_decode_t<f16_t>(a, stream); }
+size_t decode_lds_f16(int D, int G, int cap) { return decode_lds_t<f16_t>(D, G, cap); }
+}  // namespace zsm

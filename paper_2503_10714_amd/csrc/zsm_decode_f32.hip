@@ -1,0 +1,7 @@
+// Decode-step instantiations for f32 token slots.
+#include "zsm_decode.hpp"
+
+namespace zsm {
+hipError_t launch_decode_f32(const DecodeArgs& a, hipStream_t stream) { return launch_decode_t<float>(a, stream); }
+size_t decode_lds_f32(int D, int G, int cap) { return decode_lds_t<float>(D, G, cap); }
+}  // namespace zsm

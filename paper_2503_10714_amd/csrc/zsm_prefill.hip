@@ -1,0 +1,434 @@
+// Prefill compression kernels (see zsm_prefill.hpp).  All score arithmetic is fp64 (exact
+// products, one rounding to the fp32 score at the end) so that the top-B_c selection does
+// not depend on the summation order used here.
+#include "zsm_prefill.hpp"
+
+namespace zsm {
+namespace {
+
+__device__ __forceinline__ double shfl_xor_d(double v, int o) { return __shfl_xor(v, o, 64); }
+
+// the lengths live in device memory and cannot be checked on the host: clamp them here
+__device__ __forceinline__ int seq_len_of(const PrefillArgs& a, int b) {
+    const int t = a.seq_lens[b];
+    return t < 0 ? 0 : (t > a.T_max ? a.T_max : t);
+}
+
+__device__ __forceinline__ double wave_max_d(double v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v = fmax(v, shfl_xor_d(v, o));
+    return v;
+}
+
+// ---- Q -> fp64, rows padded to a multiple of PF_MR with zeros ----------------------------
+template <typename T>
+__global__ void pf_convert_q(const T* __restrict__ Q, double* __restrict__ Qd, int W, int Wp, int D, size_t n_heads) {
+    // one (unit, g) pair = "head"; Qd[head][Wp][D]
+    const size_t total = n_heads * Wp * D;
+    for (size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x; i < total; i += (size_t)gridDim.x * blockDim.x) {
+        const int c = (int)(i % D);
+        const int r = (int)((i / D) % Wp);
+        const size_t h = i / ((size_t)D * Wp);
+        Qd[i] = r < W ? (double)to_float(Q[(h * W + r) * D + c]) : 0.0;
+    }
+}
+
+// ---- P1 / P2: logits of the window queries against a tile of keys ------------------------
+// MODE 0: per (row, tile) maximum and sum of exp for the causal softmax row (Eq. 1).
+// MODE 1: s_t = sum over rows of roww * exp(z - rowm)  (Eq. 3 unrolled over the window).
+// One thread per key; the query rows are wave-uniform and come through scalar loads.
+template <typename T, int D, int MODE>
+__global__ __launch_bounds__(PF_TK) void pf_score_kernel(PrefillArgs a, PrefillWs ws) {
+    const CacheView& cv = a.cv;
+    const int lu = blockIdx.y;
+    const int b = lu / cv.H;
+    const int Tb = seq_len_of(a, b);
+    const int tile = blockIdx.x;
+    const int t0 = tile * PF_TK;
+    if (t0 >= Tb) return;
+    const int W = a.W, G = cv.G, Wp = ws.Wp;
+    const int nb = W < Tb ? W : Tb;
+    const int qpos0 = Tb - nb;                 // position of query row 0
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int t = t0 + tid;
+    const bool tvalid = t < Tb;
+    const T* krow = reinterpret_cast<const T*>(a.K) + ((size_t)lu * a.T_max + (tvalid ? t : Tb - 1)) * D;
+    const double* Qd = reinterpret_cast<const double*>(a.ws + ws.Qd);
+    double* pm = reinterpret_cast<double*>(a.ws + ws.pm);
+    double* pl = reinterpret_cast<double*>(a.ws + ws.pl);
+    const double* rowm = reinterpret_cast<const double*>(a.ws + ws.rowm);
+    const double* roww = reinterpret_cast<const double*>(a.ws + ws.roww);
+    const double scale = cv.scale;
+    constexpr int NWV = PF_TK / 64;
+    __shared__ double red[PF_MR][NWV];
+    __shared__ double bm[PF_MR];
+
+    double s_acc = 0.0;
+    for (int g = 0; g < G; ++g) {
+        const size_t head = (size_t)lu * G + g;
+        for (int r0 = 0; r0 < nb; r0 += PF_MR) {
+            const int rlast = (r0 + PF_MR < nb ? r0 + PF_MR : nb) - 1;
+            const size_t rowbase = head * Wp + r0;
+            if (t0 > qpos0 + rlast) {          // every key of this tile is in the future of these rows
+                if (MODE == 0 && tid < PF_MR) {
+                    pm[(rowbase + tid) * ws.ntiles + tile] = -INFINITY;
+                    pl[(rowbase + tid) * ws.ntiles + tile] = 0.0;
+                }
+                continue;
+            }
+            double acc[PF_MR];
+#pragma unroll
+            for (int i = 0; i < PF_MR; ++i) acc[i] = 0.0;
+            const double* qb = Qd + rowbase * D;
+            for (int c0 = 0; c0 < D; c0 += 8) {
+                float kf[8];
+                load_seg<8>(krow + c0, kf);
+                double kd[8];
+#pragma unroll
+                for (int e = 0; e < 8; ++e) kd[e] = (double)kf[e];
+#pragma unroll
+                for (int i = 0; i < PF_MR; ++i) {
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) acc[i] = fma(qb[(size_t)i * D + c0 + e], kd[e], acc[i]);
+                }
+            }
+            if (MODE == 0) {
+                double z[PF_MR];
+#pragma unroll
+                for (int i = 0; i < PF_MR; ++i) {
+                    const bool ok = tvalid && (r0 + i) < nb && t <= qpos0 + r0 + i;
+                    z[i] = ok ? acc[i] * scale : -INFINITY;
+                    const double wm = wave_max_d(z[i]);
+                    if (lane == 0) red[i][wave] = wm;
+                }
+                __syncthreads();
+                if (tid < PF_MR) {
+                    double m = red[tid][0];
+                    for (int x = 1; x < NWV; ++x) m = fmax(m, red[tid][x]);
+                    bm[tid] = m;
+                }
+                __syncthreads();
+#pragma unroll
+                for (int i = 0; i < PF_MR; ++i) {
+                    const double m = bm[i];
+                    const double e = z[i] == -INFINITY ? 0.0 : exp(z[i] - m);
+                    const double ws_ = wave_sum(e);
+                    if (lane == 0) red[i][wave] = ws_;
+                }
+                __syncthreads();
+                if (tid < PF_MR) {
+                    double l = 0.0;
+                    for (int x = 0; x < NWV; ++x) l += red[tid][x];
+                    pm[(rowbase + tid) * ws.ntiles + tile] = bm[tid];
+                    pl[(rowbase + tid) * ws.ntiles + tile] = l;
+                }
+                __syncthreads();
+            } else {
+#pragma unroll
+                for (int i = 0; i < PF_MR; ++i) {
+                    const bool ok = tvalid && (r0 + i) < nb && t <= qpos0 + r0 + i;
+                    if (ok) s_acc += roww[rowbase + i] * exp(acc[i] * scale - rowm[rowbase + i]);
+                }
+            }
+        }
+    }
+    if (MODE == 1 && tvalid) reinterpret_cast<float*>(a.ws + ws.sc)[(size_t)lu * a.T_max + t] = (float)s_acc;
+}
+
+// ---- P1b: combine the tiles' (max, sum) per query row -----------------------------------
+__global__ void pf_row_combine(PrefillArgs a, PrefillWs ws) {
+    const CacheView& cv = a.cv;
+    const int lu = blockIdx.x;
+    const int b = lu / cv.H;
+    const int Tb = seq_len_of(a, b);
+    const int nb = a.W < Tb ? a.W : Tb;
+    const int G = cv.G, Wp = ws.Wp;
+    const double* pm = reinterpret_cast<const double*>(a.ws + ws.pm);
+    const double* pl = reinterpret_cast<const double*>(a.ws + ws.pl);
+    double* rowm = reinterpret_cast<double*>(a.ws + ws.rowm);
+    double* roww = reinterpret_cast<double*>(a.ws + ws.roww);
+    const int nt = (Tb + PF_TK - 1) / PF_TK;
+    const double lam = (double)cv.lambda;
+    for (int idx = threadIdx.x; idx < G * nb; idx += blockDim.x) {
+        const int g = idx / nb, r = idx % nb;
+        const size_t row = ((size_t)lu * G + g) * Wp + r;
+        double M = -INFINITY;
+        for (int x = 0; x < nt; ++x) M = fmax(M, pm[row * ws.ntiles + x]);
+        double L = 0.0;
+        for (int x = 0; x < nt; ++x) {
+            const double m = pm[row * ws.ntiles + x];
+            if (m > -INFINITY) L += pl[row * ws.ntiles + x] * exp(m - M);
+        }
+        rowm[row] = M;
+        roww[row] = pow(lam, (double)(nb - 1 - r)) / ((double)G * L);
+    }
+}
+
+// ---- P3: top-B_c selection and slot order ------------------------------------------------
+// Radix select on the fp32 bit patterns (scores are >= 0, so the unsigned order is the value
+// order), then an ordered compaction: kept = latest B_p, every score above the threshold,
+// and the earliest positions among scores equal to it.
+constexpr int SEL_NT = 1024;
+
+__global__ __launch_bounds__(SEL_NT) void pf_select(PrefillArgs a, PrefillWs ws) {
+    const CacheView& cv = a.cv;
+    const int lu = blockIdx.x;
+    const int ug = a.unit0 + lu;
+    const int b = lu / cv.H;
+    const int Tb = seq_len_of(a, b);
+    const int Bp = cv.Bp[b], Bc = cv.Bc[b];
+    const int ntok = Bp + Bc;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const uint32_t* sc = reinterpret_cast<const uint32_t*>(a.ws + ws.sc) + (size_t)lu * a.T_max;
+    unsigned char* keep = reinterpret_cast<unsigned char*>(a.ws + ws.keep) + (size_t)lu * a.T_max;
+    int32_t* kept_pos = reinterpret_cast<int32_t*>(a.ws + ws.kept_pos) + (size_t)lu * cv.cap_tok;
+    int32_t* sel = reinterpret_cast<int32_t*>(a.ws + ws.sel) + (size_t)lu * 4;
+    (void)ug;
+
+    if (Tb <= ntok) {   // short prompt: everything is kept, in position order
+        for (int t = tid; t < Tb; t += SEL_NT) { kept_pos[t] = t; keep[t] = 1; }
+        if (tid == 0) { sel[0] = Tb; sel[1] = -1; }
+        return;
+    }
+    const int N = Tb - Bp;   // candidates for the context set: positions [0, N)
+    __shared__ int hist[256];
+    __shared__ uint32_t sh_prefix;
+    __shared__ int sh_k;
+    uint32_t prefix = 0, mask = 0;
+    int k = Bc;              // rank (from the top) still to find inside the prefix class
+    if (Bc > 0) {
+        for (int shift = 24; shift >= 0; shift -= 8) {
+            if (tid < 256) hist[tid] = 0;
+            __syncthreads();
+            for (int t = tid; t < N; t += SEL_NT) {
+                const uint32_t v = sc[t];
+                if ((v & mask) == prefix) atomicAdd(&hist[(v >> shift) & 255], 1);
+            }
+            __syncthreads();
+            if (tid == 0) {
+                int kk = k, bin = 255;
+                for (; bin > 0; --bin) {
+                    if (hist[bin] >= kk) break;
+                    kk -= hist[bin];
+                }
+                sh_prefix = prefix | ((uint32_t)bin << shift);
+                sh_k = kk;
+            }
+            __syncthreads();
+            prefix = sh_prefix;
+            k = sh_k;
+            mask |= 255u << shift;
+            __syncthreads();
+        }
+    }
+    // prefix = bit pattern of the B_c-th largest score; k = how many equal to it are kept
+    const uint32_t thr = prefix;
+    const int r_eq = Bc > 0 ? k : 0;
+    __shared__ unsigned long long wsum[SEL_NT / 64];
+    __shared__ unsigned long long carry_sh;
+    __shared__ int first_drop;
+    if (tid == 0) { carry_sh = 0; first_drop = 0x7fffffff; }
+    __syncthreads();
+    for (int c0 = 0; c0 < N; c0 += SEL_NT) {
+        const int t = c0 + tid;
+        uint32_t v = 0;
+        bool gt = false, eq = false;
+        if (t < N && Bc > 0) { v = sc[t]; gt = v > thr; eq = v == thr; }
+        const unsigned long long mine = ((unsigned long long)gt << 32) | (unsigned long long)eq;
+        // inclusive scan inside the wave, then across waves
+        unsigned long long inc = mine;
+#pragma unroll
+        for (int o = 1; o < 64; o <<= 1) {
+            const unsigned long long up = __shfl_up(inc, o, 64);
+            if (lane >= o) inc += up;
+        }
+        if (lane == 63) wsum[wave] = inc;
+        __syncthreads();
+        unsigned long long base = carry_sh;
+        for (int x = 0; x < wave; ++x) base += wsum[x];
+        const unsigned long long exc = base + inc - mine;
+        const int gt_before = (int)(exc >> 32), eq_before = (int)(exc & 0xffffffffull);
+        if (t < N) {
+            const bool kp = gt || (eq && eq_before < r_eq);
+            keep[t] = kp ? 1 : 0;
+            if (kp) kept_pos[gt_before + (eq_before < r_eq ? eq_before : r_eq)] = t;
+            else atomicMin(&first_drop, t);
+        }
+        __syncthreads();
+        if (tid == SEL_NT - 1) carry_sh = base + inc;
+        __syncthreads();
+    }
+    for (int i = tid; i < Bp; i += SEL_NT) { kept_pos[Bc + i] = N + i; keep[N + i] = 1; }
+    __syncthreads();
+    if (tid == 0) { sel[0] = ntok; sel[1] = first_drop; }
+}
+
+// ---- P4: gather the kept rows into their slots, write all slot metadata ------------------
+template <typename T, int D>
+__global__ __launch_bounds__(256) void pf_gather(PrefillArgs a, PrefillWs ws) {
+    const CacheView& cv = a.cv;
+    const int lu = blockIdx.y;
+    const int ug = a.unit0 + lu;
+    const int b = lu / cv.H;
+    const int Tb = seq_len_of(a, b);
+    const int Br = cv.Br;
+    const int32_t* kept_pos = reinterpret_cast<const int32_t*>(a.ws + ws.kept_pos) + (size_t)lu * cv.cap_tok;
+    const int32_t* sel = reinterpret_cast<const int32_t*>(a.ws + ws.sel) + (size_t)lu * 4;
+    const float* sc = reinterpret_cast<const float*>(a.ws + ws.sc) + (size_t)lu * a.T_max;
+    const int nkept = sel[0];
+    constexpr int EPL = 16 / sizeof(T), LPR = D / EPL, RPB = 256 / LPR;   // rows per block pass
+    const T* Ksrc = reinterpret_cast<const T*>(a.K) + (size_t)lu * a.T_max * D;
+    const T* Vsrc = reinterpret_cast<const T*>(a.V) + (size_t)lu * a.T_max * D;
+    T* Kt = reinterpret_cast<T*>(cv.Kt) + (size_t)ug * cv.cap_tok * D;
+    T* Vt = reinterpret_cast<T*>(cv.Vt) + (size_t)ug * cv.cap_tok * D;
+    const int tid = threadIdx.x;
+    const int j0 = blockIdx.x * RPB * 4;
+    for (int p = 0; p < 4; ++p) {
+        const int j = j0 + p * RPB + tid / LPR;
+        if (j < nkept) {
+            const int t = kept_pos[j];
+            const int sg = (tid % LPR) * EPL;
+            const uint4 kv = *reinterpret_cast<const uint4*>(Ksrc + (size_t)t * D + sg);
+            const uint4 vv = *reinterpret_cast<const uint4*>(Vsrc + (size_t)t * D + sg);
+            *reinterpret_cast<uint4*>(Kt + (size_t)j * D + sg) = kv;
+            *reinterpret_cast<uint4*>(Vt + (size_t)j * D + sg) = vv;
+        }
+    }
+    // metadata of every token slot in this block's range, and (block 0) unit header
+    float* s = cv.s + (size_t)ug * cv.cap;
+    int32_t* pos = cv.pos + (size_t)ug * cv.cap;
+    int32_t* w = cv.w + (size_t)ug * cv.cap;
+    for (int j = j0 + tid; j < j0 + RPB * 4 && j < cv.cap_tok; j += 256) {
+        if (j < nkept) {
+            const int t = kept_pos[j];
+            pos[Br + j] = t; w[Br + j] = 1; s[Br + j] = sc[t];
+        } else {
+            pos[Br + j] = -1; w[Br + j] = 0; s[Br + j] = 0.f;
+        }
+    }
+    if (blockIdx.x == 0 && tid == 0) {
+        cv.n_seen[ug] = Tb;
+        cv.n_occ[ug] = nkept;
+    }
+}
+
+// ---- P5: sum of the rows that were not kept ------------------------------------------------
+template <typename T, int D>
+__global__ __launch_bounds__(256) void pf_residual_partial(PrefillArgs a, PrefillWs ws) {
+    const CacheView& cv = a.cv;
+    const int lu = blockIdx.y;
+    const int b = lu / cv.H;
+    const int Tb = seq_len_of(a, b);
+    const int chunk = blockIdx.x;
+    const int t0 = chunk * PF_RC;
+    double* rsum = reinterpret_cast<double*>(a.ws + ws.rsum) + ((size_t)lu * ws.nchunks + chunk) * 2 * D;
+    const int tid = threadIdx.x;
+    constexpr int EPL = 16 / sizeof(T), LPR = D / EPL, RPB = 256 / LPR;
+    const int seg = tid % LPR, rg = tid / LPR;
+    __shared__ double red[2][RPB][D + 1];
+    double ak[EPL], av[EPL];
+#pragma unroll
+    for (int e = 0; e < EPL; ++e) { ak[e] = 0.0; av[e] = 0.0; }
+    if (t0 < Tb) {
+        const unsigned char* keep = reinterpret_cast<const unsigned char*>(a.ws + ws.keep) + (size_t)lu * a.T_max;
+        const T* Ksrc = reinterpret_cast<const T*>(a.K) + (size_t)lu * a.T_max * D;
+        const T* Vsrc = reinterpret_cast<const T*>(a.V) + (size_t)lu * a.T_max * D;
+        const int t1 = t0 + PF_RC < Tb ? t0 + PF_RC : Tb;
+        for (int t = t0 + rg; t < t1; t += RPB) {
+            if (keep[t]) continue;
+            float kf[EPL], vf[EPL];
+            load_seg<EPL>(Ksrc + (size_t)t * D + seg * EPL, kf);
+            load_seg<EPL>(Vsrc + (size_t)t * D + seg * EPL, vf);
+#pragma unroll
+            for (int e = 0; e < EPL; ++e) { ak[e] += (double)kf[e]; av[e] += (double)vf[e]; }
+        }
+    }
+#pragma unroll
+    for (int e = 0; e < EPL; ++e) { red[0][rg][seg * EPL + e] = ak[e]; red[1][rg][seg * EPL + e] = av[e]; }
+    __syncthreads();
+    for (int i = tid; i < 2 * D; i += 256) {
+        const int which = i / D, c = i % D;
+        double t = 0.0;
+        for (int r = 0; r < RPB; ++r) t += red[which][r][c];
+        rsum[i] = t;
+    }
+}
+
+template <int D>
+__global__ __launch_bounds__(256) void pf_residual_final(PrefillArgs a, PrefillWs ws) {
+    const CacheView& cv = a.cv;
+    const int lu = blockIdx.x;
+    const int ug = a.unit0 + lu;
+    const int b = lu / cv.H;
+    const int Tb = seq_len_of(a, b);
+    const int Br = cv.Br;
+    const int32_t* sel = reinterpret_cast<const int32_t*>(a.ws + ws.sel) + (size_t)lu * 4;
+    const int nkept = sel[0], first_drop = sel[1];
+    const int ndrop = Tb - nkept;
+    float* s = cv.s + (size_t)ug * cv.cap;
+    int32_t* pos = cv.pos + (size_t)ug * cv.cap;
+    int32_t* w = cv.w + (size_t)ug * cv.cap;
+    float* Kr = cv.Kr + (size_t)ug * Br * D;
+    float* Vr = cv.Vr + (size_t)ug * Br * D;
+    const int tid = threadIdx.x;
+    if (Br == 0) return;
+    if (ndrop <= 0) {
+        for (int i = tid; i < Br * D; i += 256) { Kr[i] = 0.f; Vr[i] = 0.f; }
+        if (tid < Br) { w[tid] = 0; pos[tid] = -1; s[tid] = 0.f; }
+        return;
+    }
+    const double* rsum = reinterpret_cast<const double*>(a.ws + ws.rsum) + (size_t)lu * ws.nchunks * 2 * D;
+    const int nch = (Tb + PF_RC - 1) / PF_RC;
+    for (int i = tid; i < 2 * D; i += 256) {
+        double t = 0.0;
+        for (int c = 0; c < nch; ++c) t += rsum[(size_t)c * 2 * D + i];
+        const float m = (float)(t / (double)ndrop);
+        if (i < D) Kr[i] = m; else Vr[i - D] = m;
+    }
+    if (tid == 0 && first_drop >= 0 && first_drop < Tb) {
+        // the slot was opened by the first absorbed token and carries its position and score
+        w[0] = ndrop; pos[0] = first_drop;
+        s[0] = reinterpret_cast<const float*>(a.ws + ws.sc)[(size_t)lu * a.T_max + first_drop];
+    }
+}
+
+template <typename T, int D>
+hipError_t launch_prefill_td(const PrefillArgs& a, hipStream_t st) {
+    const CacheView& cv = a.cv;
+    const PrefillWs ws = prefill_ws_layout(cv, a.T_max, a.W);
+    const size_t n_heads = (size_t)a.n_units * cv.G;
+    hipLaunchKernelGGL((pf_convert_q<T>), dim3(1024), dim3(256), 0, st, reinterpret_cast<const T*>(a.Q),
+                       reinterpret_cast<double*>(a.ws + ws.Qd), a.W, ws.Wp, D, n_heads);
+    const dim3 gs(ws.ntiles, a.n_units);
+    hipLaunchKernelGGL((pf_score_kernel<T, D, 0>), gs, dim3(PF_TK), 0, st, a, ws);
+    hipLaunchKernelGGL(pf_row_combine, dim3(a.n_units), dim3(256), 0, st, a, ws);
+    hipLaunchKernelGGL((pf_score_kernel<T, D, 1>), gs, dim3(PF_TK), 0, st, a, ws);
+    hipLaunchKernelGGL(pf_select, dim3(a.n_units), dim3(SEL_NT), 0, st, a, ws);
+    constexpr int EPL = 16 / sizeof(T), LPR = D / EPL, RPB = 256 / LPR;
+    const int gblocks = (cv.cap_tok + RPB * 4 - 1) / (RPB * 4);
+    hipLaunchKernelGGL((pf_gather<T, D>), dim3(gblocks > 0 ? gblocks : 1, a.n_units), dim3(256), 0, st, a, ws);
+    if (cv.Br > 0) {
+        hipLaunchKernelGGL((pf_residual_partial<T, D>), dim3(ws.nchunks, a.n_units), dim3(256), 0, st, a, ws);
+        hipLaunchKernelGGL((pf_residual_final<D>), dim3(a.n_units), dim3(256), 0, st, a, ws);
+    }
+    return hipGetLastError();
+}
+
+template <typename T>
+hipError_t launch_prefill_t(const PrefillArgs& a, hipStream_t st) {
+    if (a.cv.D == 64) return launch_prefill_td<T, 64>(a, st);
+    if (a.cv.D == 128) return launch_prefill_td<T, 128>(a, st);
+    return hipErrorInvalidValue;
+}
+
+}  // namespace
+
+hipError_t launch_prefill(const PrefillArgs& a, hipStream_t stream) {
+    switch (a.cv.dtype) {
+        case 0: return launch_prefill_t<float>(a, stream);
+        case 1: return launch_prefill_t<f16_t>(a, stream);
+        default: return launch_prefill_t<bf16_t>(a, stream);
+    }
+}
+
+}  // namespace zsm

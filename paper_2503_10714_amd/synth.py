@@ -121,6 +121,7 @@ class Workload:
     ragged: Optional[Tuple[int, int]] = None   # inclusive range of T_b
     budget_ratio: Optional[float] = None       # B_b = ceil(ratio * T_b) when ragged
     n_residual: int = 1
+    prox: Optional[int] = None                 # B_p override (default: half of the budget)
     lam: float = 0.98
     alpha: float = 1.0
     seed: int = MASTER_SEED
@@ -148,7 +149,7 @@ class Workload:
         bp, bc = [], []
         for t in self.seq_lens():
             b = self.budget if self.budget_ratio is None else int(math.ceil(self.budget_ratio * t - 1e-9))
-            p = b // 2
+            p = b // 2 if self.prox is None else self.prox
             bp.append(p)
             bc.append(b - p - self.n_residual)
         return bp, bc, self.n_residual

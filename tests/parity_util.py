@@ -1,0 +1,234 @@
+"""Shared machinery of the GPU-vs-oracle parity tests.
+
+The GPU side is called through the C ABI (paper_2503_10714_amd.binding); the oracle side
+is oracle/zsmerge_oracle.py.  Both get the same bytes: inputs are generated once (on the
+device the test says) and copied.
+
+Tolerances (the benchmark definition's): slot indices, counts, positions and eviction
+choices bit-exact, except that the device may pick another eviction victim (or another
+boundary token in the prefill selection) when the oracle's competing scores differ by
+less than 1e-6 relative; outputs, merged K/V and scores within max-abs 2e-3 for
+fp16/bf16 storage and 1e-5 for fp32.
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass, field
+from typing import Dict, List, Optional, Sequence, Tuple
+
+import numpy as np
+import torch
+
+from oracle.zsmerge_oracle import UnitCache
+from paper_2503_10714_amd import synth
+
+TIE_REL = 1e-6
+
+
+def tol_for(dtype: str) -> float:
+    return 1e-5 if dtype == "f32" else 2e-3
+
+
+def lam32(x: float) -> float:
+    """The decay / alpha value the library actually uses: the fp32 config field widened to fp64."""
+    return float(np.float32(x))
+
+
+def np64(t: torch.Tensor) -> np.ndarray:
+    return t.detach().to("cpu").to(torch.float64).numpy()
+
+
+# ---------------------------------------------------------------------------------------
+# oracle <-> tensors
+# ---------------------------------------------------------------------------------------
+
+def new_oracle_unit(wl: synth.Workload, b_local: int) -> UnitCache:
+    bp, bc, br = wl.budgets()
+    return UnitCache(wl.head_dim, wl.q_per_kv, bp[b_local], bc[b_local], br,
+                     lam=lam32(wl.lam), alpha=lam32(wl.alpha))
+
+
+def pack_states(units: List[List[UnitCache]], cap: int, Br: int, d: int, kv_dtype: torch.dtype) -> Dict[str, torch.Tensor]:
+    """Oracle states of one layer ([S][H] UnitCache) -> the export/import arrays (CPU tensors)."""
+    S, H = len(units), len(units[0])
+    K = torch.zeros(S, H, cap - Br, d, dtype=torch.float64)
+    V = torch.zeros(S, H, cap - Br, d, dtype=torch.float64)
+    Kr = torch.zeros(S, H, Br, d, dtype=torch.float64)
+    Vr = torch.zeros(S, H, Br, d, dtype=torch.float64)
+    s = torch.zeros(S, H, cap, dtype=torch.float64)
+    pos = torch.full((S, H, cap), -1, dtype=torch.int32)
+    w = torch.zeros(S, H, cap, dtype=torch.int32)
+    n_seen = torch.zeros(S, H, dtype=torch.int64)
+    for b in range(S):
+        for h in range(H):
+            u = units[b][h]
+            B = u.B
+            K[b, h, :B - Br] = torch.from_numpy(u.K[Br:])
+            V[b, h, :B - Br] = torch.from_numpy(u.V[Br:])
+            Kr[b, h] = torch.from_numpy(u.K[:Br])
+            Vr[b, h] = torch.from_numpy(u.V[:Br])
+            s[b, h, :B] = torch.from_numpy(u.s)
+            pos[b, h, :B] = torch.from_numpy(u.pos.astype(np.int32))
+            w[b, h, :B] = torch.from_numpy(u.w.astype(np.int32))
+            n_seen[b, h] = u.n_seen
+    return dict(K=K.to(torch.float32).to(kv_dtype), V=V.to(torch.float32).to(kv_dtype), Kr=Kr.to(torch.float32),
+                Vr=Vr.to(torch.float32), s=s.to(torch.float32), pos=pos, w=w, n_seen=n_seen)
+
+
+@dataclass
+class Mismatch:
+    what: str
+    detail: str
+
+
+def compare_state(gpu: Dict[str, torch.Tensor], units: List[List[UnitCache]], Br: int, tol: float,
+                  where: str = "", sel: Optional[Sequence[Tuple[int, int]]] = None) -> None:
+    """Exported GPU state of one layer vs the oracle units: integers exact, floats within tol.
+    `sel` restricts the comparison to some (b, h) pairs (units[b][h] may be None elsewhere)."""
+    g = {k: v.cpu() for k, v in gpu.items()}
+    S, H = len(units), len(units[0])
+    pairs = sel if sel is not None else [(b, h) for b in range(S) for h in range(H)]
+    for b, h in pairs:
+        u = units[b][h]
+        B = u.B
+        tag = f"{where} unit(b={b},h={h})"
+        assert int(g["n_seen"][b, h]) == u.n_seen, f"{tag}: n_seen {int(g['n_seen'][b, h])} != {u.n_seen}"
+        gp = g["pos"][b, h, :B].numpy().astype(np.int64)
+        gw = g["w"][b, h, :B].numpy().astype(np.int64)
+        assert (gw == u.w).all(), f"{tag}: w differs at slots {np.flatnonzero(gw != u.w)[:8]}"
+        occ = u.w > 0
+        assert (gp[occ] == u.pos[occ]).all(), f"{tag}: pos differs at slots {np.flatnonzero((gp != u.pos) & occ)[:8]}"
+        assert (g["pos"][b, h, B:] == -1).all() and (g["w"][b, h, B:] == 0).all(), f"{tag}: slots past B touched"
+        tok = occ[Br:]
+        gK = np64(g["K"][b, h, :B - Br]); gV = np64(g["V"][b, h, :B - Br])
+        assert (gK[tok] == u.K[Br:][tok]).all(), f"{tag}: token K rows differ"
+        assert (gV[tok] == u.V[Br:][tok]).all(), f"{tag}: token V rows differ"
+        if Br:
+            ro = occ[:Br]
+            dk = np.abs(np64(g["Kr"][b, h]) - u.K[:Br])[ro]
+            dv = np.abs(np64(g["Vr"][b, h]) - u.V[:Br])[ro]
+            if dk.size:
+                assert dk.max() <= tol and dv.max() <= tol, f"{tag}: residual K/V off by {dk.max():.3e}/{dv.max():.3e}"
+        ds = np.abs(np64(g["s"][b, h, :B]) - u.s)[occ]
+        if ds.size:
+            assert ds.max() <= tol, f"{tag}: scores off by {ds.max():.3e}"
+
+
+@dataclass
+class StepStats:
+    steps: int = 0
+    unit_steps: int = 0
+    near_ties: int = 0
+    max_out_err: float = 0.0
+    evictions: int = 0
+    merges: int = 0
+    s_bit_equal: int = 0
+    s_total: int = 0
+
+
+def check_step(out_gpu: np.ndarray, info_gpu, out_or: np.ndarray, info_or, unit: UnitCache, tol: float,
+               stats: StepStats, tag: str) -> bool:
+    """One unit, one decode step.  Returns True when the device legitimately took another
+    eviction victim (a near tie) and the two sides have to be brought together again."""
+    err = float(np.abs(out_gpu - out_or).max())
+    stats.max_out_err = max(stats.max_out_err, err)
+    assert err <= tol, f"{tag}: attention output off by {err:.3e} (tol {tol})"
+    ws, ep, ms = info_gpu
+    stats.unit_steps += 1
+    if info_or.evicted_pos >= 0:
+        stats.evictions += 1
+    if info_or.merged_slot >= 0:
+        stats.merges += 1
+    if ep == info_or.evicted_pos and ws == info_or.write_slot:
+        assert ms == info_or.merged_slot, f"{tag}: merged_slot {ms} != {info_or.merged_slot}"
+        return False
+    # another victim: allowed only inside the near-tie band of the oracle's own scores
+    assert info_or.evicted_pos >= 0 and ep >= 0, f"{tag}: write_slot/evicted_pos {ws}/{ep} vs {info_or.write_slot}/{info_or.evicted_pos}"
+    cp = info_or.cand_pos.tolist()
+    assert ep in cp, f"{tag}: device evicted position {ep}, which is not a candidate"
+    s_dev = float(info_or.cand_s[cp.index(ep)])
+    s_best = float(info_or.cand_s[cp.index(info_or.evicted_pos)])
+    rel = abs(s_dev - s_best) / max(abs(s_best), 1e-300)
+    assert rel < TIE_REL, f"{tag}: device evicted pos {ep} (s={s_dev:.9e}) but the lowest score is pos {info_or.evicted_pos} (s={s_best:.9e}), rel gap {rel:.2e}"
+    stats.near_ties += 1
+    return True
+
+
+# ---------------------------------------------------------------------------------------
+# drivers
+# ---------------------------------------------------------------------------------------
+
+def oracle_prefill_layer(wl: synth.Workload, Q: torch.Tensor, K: torch.Tensor, V: torch.Tensor, lens: Sequence[int],
+                         sel: Optional[Sequence[Tuple[int, int]]] = None) -> List[List[Optional[UnitCache]]]:
+    """Oracle prefill of one layer from the tensors the device got (any device)."""
+    S, H = K.shape[0], K.shape[1]
+    units: List[List[Optional[UnitCache]]] = [[None] * H for _ in range(S)]
+    pairs = sel if sel is not None else [(b, h) for b in range(S) for h in range(H)]
+    for b, h in pairs:
+        u = new_oracle_unit(wl, b)
+        tb = lens[b]
+        nb = min(Q.shape[3], tb)
+        if tb > 0:
+            u.prefill_compress(np64(Q[b, h, :, :nb]), np64(K[b, h, :tb]), np64(V[b, h, :tb]))
+        units[b][h] = u
+    return units
+
+
+def make_cache(wl: synth.Workload, device="cuda:0"):
+    from paper_2503_10714_amd.binding import Cache
+    bp, bc, br = wl.budgets()
+    return Cache(wl.n_layers, wl.n_seqs, wl.n_kv_heads, wl.q_per_kv, wl.head_dim, bp, bc, br, wl.dtype,
+                 lam=wl.lam, alpha=wl.alpha, slot_capacity=wl.slot_capacity, device=device)
+
+
+def run_decode_parity(wl: synth.Workload, cache, units_by_layer: List[List[List[UnitCache]]], n_steps: int,
+                      sel: Optional[Sequence[Tuple[int, int, int]]] = None, gen_device="cpu",
+                      state_every: int = 0) -> StepStats:
+    """Lock-step decode of GPU cache and oracle units; all layers per launch.
+
+    sel: (layer, b, h) triples to check (default: all).  state_every: also compare the
+    whole exported state every that many steps (0 = only at the end)."""
+    L, S, H, G, d = wl.n_layers, wl.n_seqs, wl.n_kv_heads, wl.q_per_kv, wl.head_dim
+    tol = tol_for(wl.dtype)
+    stats = StepStats()
+    triples = sel if sel is not None else [(l, b, h) for l in range(L) for b in range(S) for h in range(H)]
+    dev = cache.device
+    for step in range(n_steps):
+        qs, ks, vs = [], [], []
+        for l in range(L):
+            q, k, v = synth.decode_inputs(wl, l, step, device=gen_device)
+            qs.append(q); ks.append(k); vs.append(v)
+        q = torch.stack(qs).to(dev); k = torch.stack(ks).to(dev); v = torch.stack(vs).to(dev)
+        out, (ws, ep, ms) = cache.decode_step(q, k, v)
+        out_c, ws_c, ep_c, ms_c = out.cpu().numpy().astype(np.float64), ws.cpu().numpy(), ep.cpu().numpy(), ms.cpu().numpy()
+        qc, kc, vc = np64(q), np64(k), np64(v)
+        resync_layers = set()
+        for (l, b, h) in triples:
+            u = units_by_layer[l][b][h]
+            o, info = u.decode_step(qc[l, b, h], kc[l, b, h], vc[l, b, h])
+            tag = f"{wl.name} step {step} unit(l={l},b={b},h={h})"
+            if check_step(out_c[l, b, h], (int(ws_c[l, b, h]), int(ep_c[l, b, h]), int(ms_c[l, b, h])), o, info, u, tol, stats, tag):
+                resync_layers.add(l)
+        for l in resync_layers:
+            assert sel is None, "a near tie in a sampled run cannot be re-synchronised"
+            cache.import_layer(l, **pack_states(units_by_layer[l], cache.cap, cache.B_r, d, cache.kv_dtype))
+        stats.steps += 1
+        if state_every and (step + 1) % state_every == 0 and step + 1 < n_steps:
+            compare_all_state(wl, cache, units_by_layer, tol, f"after step {step}", sel)
+    compare_all_state(wl, cache, units_by_layer, tol, "final", sel, stats)
+    return stats
+
+
+def compare_all_state(wl, cache, units_by_layer, tol, where, sel=None, stats: Optional[StepStats] = None):
+    for l in range(wl.n_layers):
+        pairs = None if sel is None else [(b, h) for (ll, b, h) in sel if ll == l]
+        if pairs is not None and not pairs:
+            continue
+        st = cache.export_layer(l)
+        compare_state(st, units_by_layer[l], cache.B_r, tol, f"{wl.name} {where} layer {l}", pairs)
+        if stats is not None:
+            g = st["s"].cpu().numpy()
+            for (b, h) in (pairs if pairs is not None else [(b, h) for b in range(wl.n_seqs) for h in range(wl.n_kv_heads)]):
+                u = units_by_layer[l][b][h]
+                occ = u.w > 0
+                stats.s_total += int(occ.sum())
+                stats.s_bit_equal += int((g[b, h, :u.B][occ] == u.s[occ].astype(np.float32)).sum())

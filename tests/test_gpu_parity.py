@@ -1,0 +1,169 @@
+"""GPU-vs-oracle parity, through the C ABI.  Needs an MI355X (pytest -m gpu)."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2503_10714_amd import synth
+from tests import parity_util as pu
+
+pytestmark = pytest.mark.gpu
+
+DEV = "cuda:0"
+
+
+def small(name, **kw):
+    base = dict(name=name, n_layers=1, n_seqs=1, n_kv_heads=2, q_per_kv=1, head_dim=64, dtype="f32",
+                prompt_len=200, budget=48, decode_steps=40, window=16, outliers=False)
+    base.update(kw)
+    return synth.Workload(**base)
+
+
+DECODE_CASES = {
+    "cfg0": lambda: synth.workload(0),
+    "cfg1": lambda: synth.workload(1),
+    "evict_only": lambda: small("evict_only", n_residual=0),
+    "three_residual_f16": lambda: small("three_residual_f16", n_residual=3, dtype="f16", head_dim=128, outliers=True),
+    "alpha_half_bf16_gqa4": lambda: small("alpha_half_bf16_gqa4", alpha=0.5, dtype="bf16", q_per_kv=4, head_dim=128,
+                                         n_kv_heads=2, outliers=True, budget=70),
+    "gqa2_d64_f16": lambda: small("gqa2_d64_f16", dtype="f16", q_per_kv=2),
+    "gqa8_f32_d128": lambda: small("gqa8_f32_d128", q_per_kv=8, head_dim=128, budget=33, prompt_len=120),
+    "fills_up": lambda: small("fills_up", prompt_len=20, budget=48, decode_steps=60, window=8),       # T < B: free slots first
+    "empty_start": lambda: small("empty_start", prompt_len=0, budget=24, decode_steps=50, n_residual=2, window=4),
+    "ragged_multi_layer": lambda: small("ragged_multi_layer", n_layers=2, n_seqs=3, dtype="f16", head_dim=128,
+                                        prompt_len=300, ragged=(40, 300), budget_ratio=0.2, budget=60, decode_steps=30),
+    "tiny_budget": lambda: small("tiny_budget", budget=3, prompt_len=50, decode_steps=30),            # B_p = 1, B_c = 1, B_r = 1
+    "no_context": lambda: small("no_context", prompt_len=60, budget=9, prox=8, decode_steps=30, window=8),     # B_c = 0
+}
+
+
+def oracle_states(wl, device="cpu"):
+    units = []
+    for l in range(wl.n_layers):
+        if wl.prompt_len > 0:
+            Q, K, V, lens = synth.prompt(wl, l, device=device)
+            units.append(pu.oracle_prefill_layer(wl, Q, K, V, lens))
+        else:
+            units.append([[pu.new_oracle_unit(wl, b) for _ in range(wl.n_kv_heads)] for b in range(wl.n_seqs)])
+    return units
+
+
+@pytest.mark.parametrize("case", list(DECODE_CASES))
+def test_decode_from_oracle_state(case):
+    """Decode kernel alone: the oracle's prefill state is imported, then both step together."""
+    wl = DECODE_CASES[case]()
+    print(f"[case] {case} {wl.name} units={wl.n_units} B={wl.slot_capacity} steps={wl.decode_steps}", flush=True)
+    units = oracle_states(wl)
+    cache = pu.make_cache(wl, DEV)
+    for l in range(wl.n_layers):
+        cache.import_layer(l, **pu.pack_states(units[l], cache.cap, cache.B_r, wl.head_dim, cache.kv_dtype))
+    pu.compare_all_state(wl, cache, units, pu.tol_for(wl.dtype), "after import")
+    st = pu.run_decode_parity(wl, cache, units, wl.decode_steps, state_every=16)
+    print(f"[done] {case}: unit-steps={st.unit_steps} evictions={st.evictions} merges={st.merges} near_ties={st.near_ties} "
+          f"max|out err|={st.max_out_err:.2e} scores bit-equal {st.s_bit_equal}/{st.s_total}", flush=True)
+    assert st.near_ties == 0 or st.near_ties < 0.01 * st.unit_steps
+    if wl.decode_steps + wl.prompt_len > wl.slot_capacity:
+        assert st.evictions > 0
+    cache.close()
+
+
+PREFILL_CASES = {
+    "cfg0": lambda: synth.workload(0),
+    "cfg1": lambda: synth.workload(1),
+    "gqa4_bf16": lambda: small("pf_gqa4_bf16", dtype="bf16", q_per_kv=4, head_dim=128, prompt_len=700, budget=64, window=32, outliers=True),
+    "ragged_f16": lambda: small("pf_ragged_f16", n_seqs=4, dtype="f16", head_dim=128, prompt_len=900, ragged=(100, 900),
+                                budget_ratio=0.1, budget=90, window=32, outliers=True),
+    "short_prompt_kept_whole": lambda: small("pf_short", prompt_len=30, budget=48, window=8),
+    "window_longer_than_prompt": lambda: small("pf_longwin", prompt_len=20, budget=12, window=32),
+    "evict_only": lambda: small("pf_evict_only", n_residual=0, prompt_len=300, budget=40),
+    "no_context": lambda: small("pf_no_context", prompt_len=300, budget=9, prox=8, window=8),
+    "full_history_gqa2": lambda: small("pf_fullhist_gqa2", q_per_kv=2, prompt_len=300, budget=40, window=0, dtype="f16"),
+    "tile_edges": lambda: small("pf_tile_edges", prompt_len=513, budget=64, window=32, n_kv_heads=3),
+}
+
+
+def prefill_gpu_and_oracle(wl, gen_device="cpu"):
+    cache = pu.make_cache(wl, DEV)
+    units = []
+    for l in range(wl.n_layers):
+        Q, K, V, lens = synth.prompt(wl, l, device=gen_device)
+        cache.prefill_compress(l, Q.to(DEV), K.to(DEV), V.to(DEV), lens)
+        units.append(pu.oracle_prefill_layer(wl, Q, K, V, lens))
+    torch.cuda.synchronize()
+    return cache, units
+
+
+@pytest.mark.parametrize("case", list(PREFILL_CASES))
+def test_prefill_compress(case):
+    wl = PREFILL_CASES[case]()
+    print(f"[case] prefill {case} {wl.name} T={wl.prompt_len} lens={wl.seq_lens()[:4]} B={wl.slot_capacity}", flush=True)
+    cache, units = prefill_gpu_and_oracle(wl)
+    stats = pu.StepStats()
+    pu.compare_all_state(wl, cache, units, pu.tol_for(wl.dtype), "after prefill", None, stats)
+    print(f"[done] prefill {case}: scores bit-equal {stats.s_bit_equal}/{stats.s_total}", flush=True)
+    for l in range(wl.n_layers):
+        for row in units[l]:
+            for u in row:
+                assert u.w.sum() == u.n_seen or u.B_r == 0      # merged-slot weights sum to tokens seen
+    cache.close()
+
+
+FULL_CASES = {
+    "cfg0": (lambda: synth.workload(0), None),
+    "cfg1": (lambda: synth.workload(1), None),
+    # the deep / wide workloads at their true per-unit shape, fewer layers, sequences and heads
+    "cfg2_slice": (lambda: synth.workload(2).sliced(n_layers=2, n_kv_heads=3, layer0=7, head0=5), 24),
+    "cfg3_slice": (lambda: synth.workload(3).sliced(n_layers=1, n_seqs=3, n_kv_heads=2, layer0=3, seq0=11, head0=9), 24),
+    "cfg4_slice": (lambda: synth.workload(4).sliced(n_layers=1, n_seqs=2, n_kv_heads=2, layer0=30, seq0=3, head0=6), 24),
+}
+
+
+@pytest.mark.parametrize("case", list(FULL_CASES))
+def test_prefill_then_decode(case):
+    """The whole path on the device (no import): prefill compression, then decode steps."""
+    mk, steps = FULL_CASES[case]
+    wl = mk()
+    steps = wl.decode_steps if steps is None else steps
+    print(f"[case] full {case} {wl.name} units={wl.n_units} T={wl.prompt_len} B={wl.slot_capacity} steps={steps}", flush=True)
+    cache, units = prefill_gpu_and_oracle(wl, gen_device=DEV if wl.prompt_len > 8192 else "cpu")
+    pu.compare_all_state(wl, cache, units, pu.tol_for(wl.dtype), "after prefill")
+    print("[step] prefill parity ok", flush=True)
+    st = pu.run_decode_parity(wl, cache, units, steps, state_every=0)
+    print(f"[done] full {case}: unit-steps={st.unit_steps} evictions={st.evictions} near_ties={st.near_ties} "
+          f"max|out err|={st.max_out_err:.2e} scores bit-equal {st.s_bit_equal}/{st.s_total}", flush=True)
+    assert st.evictions == st.unit_steps or wl.prompt_len + steps <= wl.slot_capacity
+    cache.close()
+
+
+def test_error_paths_on_device():
+    from paper_2503_10714_amd import binding as zb
+    wl = small("errs")
+    cache = pu.make_cache(wl, DEV)
+    q, k, v = synth.decode_inputs(wl, 0, 0)
+    q, k, v = q[None].to(DEV), k[None].to(DEV), v[None].to(DEV)
+    out = torch.empty(1, 1, 2, 1, 64, device=DEV)
+    with pytest.raises(zb.ZsmError) as e:
+        zb.zsm_decode_step(cache.handle, 0, 2, q, k, v, out)
+    assert e.value.status == -6
+    with pytest.raises(zb.ZsmError) as e:
+        zb.zsm_decode_step(cache.handle, 0, 1, None, k, v, out)
+    assert e.value.status == -1
+    with pytest.raises(zb.ZsmError) as e:                       # a view that starts 4 bytes into a buffer
+        zb.zsm_decode_step(cache.handle, 0, 1, q, k, v, torch.empty(129, device=DEV)[1:])
+    assert e.value.status == -4
+    ws = torch.empty(16, dtype=torch.uint8, device=DEV)
+    Q, K, V, lens = synth.prompt(wl, 0)
+    with pytest.raises(zb.ZsmError) as e:
+        zb.zsm_prefill_compress(cache.handle, 0, Q.to(DEV), Q.shape[-2], K.to(DEV), V.to(DEV),
+                                torch.tensor(lens, dtype=torch.int32, device=DEV), K.shape[-2], ws)
+    assert e.value.status == -5
+    # nothing above may have touched the cache
+    st = cache.export_layer(0)
+    assert (st["pos"] == -1).all() and (st["w"] == 0).all() and (st["n_seen"] == 0).all()
+    # a budget whose logits do not fit the LDS is refused, not launched
+    big = zb.Cache(1, 1, 1, 8, 128, 2000, 2000, 1, "f16", device=DEV)
+    qq = torch.zeros(1, 1, 1, 8, 128, dtype=torch.float16, device=DEV)
+    kk = torch.zeros(1, 1, 1, 128, dtype=torch.float16, device=DEV)
+    with pytest.raises(zb.ZsmError) as e:
+        big.decode_step(qq, kk, kk)
+    assert e.value.status == -2
+    big.close(); cache.close()
