@@ -73,6 +73,55 @@ __device__ __forceinline__ void load_seg(const bf16_t* p, float* out) {
     }
 }
 
+// Raw<KT, N>: the register image of N consecutive elements (N * sizeof(KT) is a multiple
+// of 16): loaded with 16-byte loads, converted element by element only where it is used.
+typedef float f32x4_t __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
+typedef f16_t f16x8_t __attribute__((ext_vector_type(8)));
+
+template <typename KT, int N> struct Raw;
+template <int N> struct Raw<float, N> {
+    f32x4_t v[N / 4];
+    __device__ __forceinline__ void load(const float* p) {
+#pragma unroll
+        for (int i = 0; i < N / 4; ++i) v[i] = reinterpret_cast<const f32x4_t*>(p)[i];
+    }
+    __device__ __forceinline__ void zero() {
+#pragma unroll
+        for (int i = 0; i < N / 4; ++i) v[i] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+    }
+    __device__ __forceinline__ float get(int e) const { return v[e / 4][e % 4]; }
+};
+template <int N> struct Raw<f16_t, N> {
+    f16x8_t v[N / 8];
+    __device__ __forceinline__ void load(const f16_t* p) {
+#pragma unroll
+        for (int i = 0; i < N / 8; ++i) v[i] = reinterpret_cast<const f16x8_t*>(p)[i];
+    }
+    __device__ __forceinline__ void zero() {
+#pragma unroll
+        for (int i = 0; i < N / 8; ++i)
+#pragma unroll
+            for (int e = 0; e < 8; ++e) v[i][e] = (f16_t)0;
+    }
+    __device__ __forceinline__ float get(int e) const { return (float)v[e / 8][e % 8]; }
+};
+template <int N> struct Raw<bf16_t, N> {
+    u32x4_t v[N / 8];
+    __device__ __forceinline__ void load(const bf16_t* p) {
+#pragma unroll
+        for (int i = 0; i < N / 8; ++i) v[i] = reinterpret_cast<const u32x4_t*>(p)[i];
+    }
+    __device__ __forceinline__ void zero() {
+#pragma unroll
+        for (int i = 0; i < N / 8; ++i) v[i] = u32x4_t{0u, 0u, 0u, 0u};
+    }
+    __device__ __forceinline__ float get(int e) const {
+        const uint32_t d = v[e / 8][(e % 8) / 2];
+        return __uint_as_float((e & 1) ? (d & 0xffff0000u) : (d << 16));
+    }
+};
+
 __device__ __forceinline__ float to_float(float x) { return x; }
 __device__ __forceinline__ float to_float(f16_t x) { return (float)x; }
 __device__ __forceinline__ float to_float(bf16_t x) { return __uint_as_float(((uint32_t)x.bits) << 16); }

@@ -69,9 +69,13 @@ struct WaveState {
 };
 
 // Process UU wave-wide loads of rows [row0, row0 + UU*RPL) of the row arrays Kb / Vb
-// (element type KT, row length D).  Rows >= nrows do not exist.  posb / wb, when given,
-// mask empty rows (pos < 0, w == 0) and wb adds alpha*log(w) to the logit (Eq. 4).
-template <typename KT, int UU, int D, int G, int EPL, int LPR, int RPL>
+// (element type KT, row length D).  Rows >= nrows do not exist.
+// MASKED = false: every existing row is occupied; the loads are branch-free (a row index
+// past the end is clamped to the last row and its result discarded).
+// MASKED = true: posb / wb, when given, mark empty rows (pos < 0, w == 0), which take no
+// part and are never loaded (an empty slot may hold any bit pattern); wb also adds
+// alpha*log(w) to the logit (Eq. 4).
+template <typename KT, int UU, bool MASKED, int D, int G, int EPL, int LPR, int RPL>
 __device__ __forceinline__ void decode_tile(const KT* __restrict__ Kb, const KT* __restrict__ Vb,
                                             int row0, int nrows, int zidx0,
                                             const int32_t* __restrict__ posb,
@@ -80,17 +84,22 @@ __device__ __forceinline__ void decode_tile(const KT* __restrict__ Kb, const KT*
                                             int Bz, double* part_w, float* pbuf_w, int lane) {
     constexpr int RR = UU * RPL;
     const int grp = lane / LPR, seg = lane % LPR;
-    float kf[UU][EPL], vf[UU][EPL];
+    Raw<KT, EPL> kr[UU], vr[UU];
 #pragma unroll
     for (int u = 0; u < UU; ++u) {
         const int r = row0 + u * RPL + grp;
-        // an empty slot may hold anything (also NaN bit patterns): never let it reach the sums
-        if (r < nrows && (posb == nullptr || posb[r] >= 0)) {
-            load_seg<EPL>(Kb + (size_t)r * D + seg * EPL, kf[u]);
-            load_seg<EPL>(Vb + (size_t)r * D + seg * EPL, vf[u]);
+        if (MASKED) {
+            if (r < nrows && (posb == nullptr || posb[r] >= 0) && (wb == nullptr || wb[r] > 0)) {
+                kr[u].load(Kb + (size_t)r * D + seg * EPL);
+                vr[u].load(Vb + (size_t)r * D + seg * EPL);
+            } else {
+                kr[u].zero();
+                vr[u].zero();
+            }
         } else {
-#pragma unroll
-            for (int e = 0; e < EPL; ++e) { kf[u][e] = 0.f; vf[u][e] = 0.f; }
+            const int rc = r < nrows ? r : nrows - 1;
+            kr[u].load(Kb + (size_t)rc * D + seg * EPL);
+            vr[u].load(Vb + (size_t)rc * D + seg * EPL);
         }
     }
     // lane h < RR "holds" row row0 + h: it finishes that row's logit and probability
@@ -98,11 +107,13 @@ __device__ __forceinline__ void decode_tile(const KT* __restrict__ Kb, const KT*
     const bool hexist = lane < RR && hr < nrows;
     bool hvalid = hexist;
     double addend = 0.0;
-    if (hvalid && posb) hvalid = posb[hr] >= 0;
-    if (hvalid && wb) {
-        const int wv = wb[hr];
-        hvalid = wv > 0;
-        if (wv > 1) addend = alpha * log((double)wv);
+    if (MASKED) {
+        if (hvalid && posb) hvalid = posb[hr] >= 0;
+        if (hvalid && wb) {
+            const int wv = wb[hr];
+            hvalid = wv > 0;
+            if (wv > 1) addend = alpha * log((double)wv);
+        }
     }
 #pragma unroll
     for (int g = 0; g < G; ++g) {
@@ -110,7 +121,7 @@ __device__ __forceinline__ void decode_tile(const KT* __restrict__ Kb, const KT*
         for (int u = 0; u < UU; ++u) {
             double p = 0.0;
 #pragma unroll
-            for (int e = 0; e < EPL; ++e) p = fma(st.qd[g][e], (double)kf[u][e], p);
+            for (int e = 0; e < EPL; ++e) p = fma(st.qd[g][e], (double)kr[u].get(e), p);
             part_w[(u * RPL + grp) * (LPR + 1) + seg] = p;
         }
         wave_sync();
@@ -138,7 +149,7 @@ __device__ __forceinline__ void decode_tile(const KT* __restrict__ Kb, const KT*
             for (int u = 0; u < UU; ++u) {
                 const float pu = pbuf_w[grp * UU + u];
 #pragma unroll
-                for (int e = 0; e < EPL; ++e) st.acc[g][e] = fmaf(pu, vf[u][e], st.acc[g][e]);
+                for (int e = 0; e < EPL; ++e) st.acc[g][e] = fmaf(pu, vr[u].get(e), st.acc[g][e]);
             }
         }
         wave_sync();
@@ -146,7 +157,7 @@ __device__ __forceinline__ void decode_tile(const KT* __restrict__ Kb, const KT*
 }
 
 template <typename T, int D, int G, int NW, int U>
-__global__ __launch_bounds__(NW * 64) void decode_kernel(DecodeArgs a) {
+__global__ __launch_bounds__(NW * 64, (G == 1 ? 4 : (G == 2 ? 2 : 1))) void decode_kernel(DecodeArgs a) {
     using Sh = DecodeShape<T, D, G, NW, U>;
     constexpr int EPL = Sh::EPL, LPR = Sh::LPR, RPL = Sh::RPL, R = Sh::R, PART = Sh::PART, NT = Sh::NT;
     const CacheView& cv = a.cv;
@@ -205,17 +216,22 @@ __global__ __launch_bounds__(NW * 64) void decode_kernel(DecodeArgs a) {
 
     // ---- D1 + D2: one sweep over the token slots -------------------------------------
     const int ntiles = (ntok + R - 1) / R;
-    const int32_t* posb = full ? nullptr : pos + Br;
-    for (int t = wave; t < ntiles; t += NW)
-        decode_tile<T, U, D, G, EPL, LPR, RPL>(Kt, Vt, t * R, ntok, Br, posb, nullptr, alpha, scale,
-                                               st, zt, Bz, part_w, pbuf_w, lane);
+    if (full) {
+        for (int t = wave; t < ntiles; t += NW)
+            decode_tile<T, U, false, D, G, EPL, LPR, RPL>(Kt, Vt, t * R, ntok, Br, nullptr, nullptr, alpha, scale,
+                                                          st, zt, Bz, part_w, pbuf_w, lane);
+    } else {
+        for (int t = wave; t * RPL < ntok; t += NW)
+            decode_tile<T, 1, true, D, G, EPL, LPR, RPL>(Kt, Vt, t * RPL, ntok, Br, pos + Br, nullptr, alpha, scale,
+                                                         st, zt, Bz, part_w, pbuf_w, lane);
+    }
     // residual slots (fp32 rows, log-count term) and the incoming token itself
     for (int t = wave; t * RPL < Br; t += NW)
-        decode_tile<float, 1, D, G, EPL, LPR, RPL>(Kr, Vr, t * RPL, Br, 0, nullptr, w, alpha, scale,
-                                                   st, zt, Bz, part_w, pbuf_w, lane);
+        decode_tile<float, 1, true, D, G, EPL, LPR, RPL>(Kr, Vr, t * RPL, Br, 0, nullptr, w, alpha, scale,
+                                                         st, zt, Bz, part_w, pbuf_w, lane);
     if (wave == NW - 1)
-        decode_tile<T, 1, D, G, EPL, LPR, RPL>(knew, vnew, 0, 1, B, nullptr, nullptr, alpha, scale,
-                                               st, zt, Bz, part_w, pbuf_w, lane);
+        decode_tile<T, 1, false, D, G, EPL, LPR, RPL>(knew, vnew, 0, 1, B, nullptr, nullptr, alpha, scale,
+                                                      st, zt, Bz, part_w, pbuf_w, lane);
 
     // ---- combine the waves' partial softmaxes -> out ---------------------------------
 #pragma unroll
