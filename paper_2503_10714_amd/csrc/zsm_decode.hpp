@@ -1,17 +1,23 @@
 // Fused decode step of the ZSMerge cache (Alg. 1 loop body with the attention of Eq. 4).
 //
-// One workgroup per unit.  Each wave streams its own tiles of K and V rows with 16-byte
-// loads (a row of d*e bytes is spread over LPR consecutive lanes, so a wave-wide load
-// covers RPL = 64/LPR whole rows) and keeps a private online softmax, so there is no
-// block-wide barrier inside the sweep and K and V are read exactly once.
+// One workgroup per unit, two streaming passes inside it, K and V each read exactly once:
+//   pass 1 streams K: every wave takes tiles of rows with 16-byte loads (a row of d*e
+//     bytes is spread over LPR consecutive lanes, a wave-wide load covers RPL = 64/LPR
+//     whole rows), forms the logits and stores exp(logit - C) per slot in LDS, C being the
+//     incoming token's own logit (any reference works in fp64: see below);
+//   one barrier gives every wave the softmax denominator L;
+//   pass 2 streams V and accumulates p * v with p = exp(.)/L read back from LDS.
+// After that: score update (Eq. 3), eviction choice, residual merge (Eq. 5, Eq. 6) and the
+// write of the incoming token, all from the per-slot values kept in LDS plus 12 bytes of
+// metadata per slot.
 //
-// Two precisions run side by side:
-//   * the attention output uses fp32 probabilities and fp32 accumulators;
-//   * everything that feeds a stored score or a decision (logits, the softmax that updates
-//     s, Eq. 5's dot products, Eq. 6's mean) is evaluated in fp64 and rounded once to the
-//     fp32 storage type.  Products of two fp16/bf16/fp32 values are exact in fp64, so the
-//     logits are the exactly rounded dot products and the eviction choice does not depend
-//     on the summation order of this kernel.
+// Precision.  Everything that feeds a stored score or a decision (logits, exp, L, Eq. 5's
+// dot products, Eq. 6's mean) is evaluated in fp64 and rounded once to the fp32 storage
+// type; products of two fp16/bf16/fp32 values are exact in fp64, so the logits are the
+// exactly rounded dot products and the eviction choice does not depend on the summation
+// order of this kernel.  The attention output uses fp32 probabilities and accumulators.
+// With fp64 exponentials no running maximum is needed: exp(z - C) cannot overflow unless a
+// logit exceeds the incoming token's by more than 690, at which the difference is clamped.
 #pragma once
 
 #include "zsm_common.hpp"
@@ -31,135 +37,176 @@ struct DecodeArgs {
     int32_t* merged_slot;
 };
 
-template <typename T, int D, int G, int NW, int U>
+template <typename T, int D, int G, int NW>
 struct DecodeShape {
     static constexpr int EPL = 16 / sizeof(T);   // elements per lane (one 16-byte load)
     static constexpr int LPR = D / EPL;          // lanes per row
     static constexpr int RPL = 64 / LPR;         // rows per wave-wide load
-    static constexpr int R = U * RPL;            // rows per wave tile
-    static constexpr int PART = R * (LPR + 1);   // doubles of partial-dot staging per wave
+    static constexpr int UT = 8;                 // wave-wide loads per tile
+    static constexpr int UH = 4;                 // loads per reduction granule
+    static constexpr int R = UT * RPL;           // rows per wave tile
+    static constexpr int PART = UH * RPL * (LPR + 1);   // doubles of partial-dot staging per wave
     static constexpr int NT = NW * 64;
+    static constexpr bool QLDS = G > 2;          // queries live in LDS instead of registers
     static_assert(LPR >= 1 && LPR <= 64 && 64 % LPR == 0, "row must split over a wave");
 
     // dynamic LDS bytes for a slot capacity `cap` (same formula on host and device)
     __host__ __device__ static size_t lds_bytes(int cap) {
         size_t n = 0;
-        n += sizeof(double) * G * (size_t)(cap + 1);   // zt
+        n += sizeof(double) * G * (size_t)(cap + 1);   // et
         n += sizeof(double) * NW * PART;               // part
         n += sizeof(double) * NW * G;                  // red64
-        n += sizeof(double) * G;                       // l64
+        n += sizeof(double) * (QLDS ? G * D : 0);      // qlds
         n += sizeof(unsigned long long) * NW;          // keyw
         n += sizeof(double) * NW;                      // dotw
         n += sizeof(float) * NW * G * D;               // accw
-        n += sizeof(float) * NW * R;                   // pbuf
-        n += sizeof(float) * NW * G * 2;               // mw, lw
-        n += sizeof(float) * G;                        // Mg
         n += sizeof(int) * (4 + NW);                   // misc
         return (n + 15) & ~(size_t)15;
     }
 };
 
-// State a wave carries through its sweep.
-template <int G, int EPL>
-struct WaveState {
-    double qd[G][EPL];   // this lane's segment of every query head, fp64
-    float m[G];          // running maximum (wave-uniform)
-    float l[G];          // running sum of exp(z - m) for the rows this lane holds
-    float acc[G][EPL];   // running sum of p * v for this lane's channel segment
+// The G query vectors, fp64: this lane's segment in registers, or all of them in LDS.
+template <int G, int EPL, bool QLDS>
+struct Query {
+    double r[QLDS ? 1 : G][EPL];
+    const double* lds;    // [G][D] when QLDS
+    __device__ __forceinline__ void get(int g, int seg, int D, double* out) const {
+        if (QLDS) {
+#pragma unroll
+            for (int e = 0; e < EPL; ++e) out[e] = lds[g * D + seg * EPL + e];
+        } else {
+#pragma unroll
+            for (int e = 0; e < EPL; ++e) out[e] = r[QLDS ? 0 : g][e];
+        }
+    }
 };
 
-// Process UU wave-wide loads of rows [row0, row0 + UU*RPL) of the row arrays Kb / Vb
-// (element type KT, row length D).  Rows >= nrows do not exist.
-// MASKED = false: every existing row is occupied; the loads are branch-free (a row index
-// past the end is clamped to the last row and its result discarded).
-// MASKED = true: posb / wb, when given, mark empty rows (pos < 0, w == 0), which take no
-// part and are never loaded (an empty slot may hold any bit pattern); wb also adds
-// alpha*log(w) to the logit (Eq. 4).
-template <typename KT, int UU, bool MASKED, int D, int G, int EPL, int LPR, int RPL>
-__device__ __forceinline__ void decode_tile(const KT* __restrict__ Kb, const KT* __restrict__ Vb,
-                                            int row0, int nrows, int zidx0,
-                                            const int32_t* __restrict__ posb,
-                                            const int32_t* __restrict__ wb, double alpha,
-                                            double scale, WaveState<G, EPL>& st, double* zt,
-                                            int Bz, double* part_w, float* pbuf_w, int lane) {
-    constexpr int RR = UU * RPL;
+// Pass 1 on UU wave-wide loads of K rows [row0, row0 + UU*RPL) of the row array Kb (element
+// type KT, row length D); rows >= nrows do not exist.  For every existing row the holder lane
+// stores exp(logit - C) (0 for an empty row) at et[g][zidx0 + row] and adds it to lsum[g].
+// MASKED = false: every existing row is occupied; loads are branch-free (a row index past the
+//   end is clamped to the last row and its result discarded).
+// MASKED = true: posb / wb mark empty rows (pos < 0, w == 0), which are never loaded (an empty
+//   slot may hold any bit pattern); wb also adds alpha*log(w) to the logit (Eq. 4).
+template <typename KT, int UU, bool MASKED, int D, int G, int EPL, int LPR, int RPL, bool QLDS>
+__device__ __forceinline__ void k_tile(const KT* __restrict__ Kb, int row0, int nrows, int zidx0,
+                                       const int32_t* __restrict__ posb, const int32_t* __restrict__ wb,
+                                       double alpha, double scale, const Query<G, EPL, QLDS>& qq,
+                                       const double* C, double* lsum, double* et, int Bz,
+                                       double* part_w, int lane) {
+    constexpr int UH = UU < 4 ? UU : 4;
     const int grp = lane / LPR, seg = lane % LPR;
-    Raw<KT, EPL> kr[UU], vr[UU];
+    Raw<KT, EPL> kr[UU];
 #pragma unroll
     for (int u = 0; u < UU; ++u) {
         const int r = row0 + u * RPL + grp;
         if (MASKED) {
-            if (r < nrows && (posb == nullptr || posb[r] >= 0) && (wb == nullptr || wb[r] > 0)) {
+            if (r < nrows && (posb == nullptr || posb[r] >= 0) && (wb == nullptr || wb[r] > 0))
                 kr[u].load(Kb + (size_t)r * D + seg * EPL);
-                vr[u].load(Vb + (size_t)r * D + seg * EPL);
-            } else {
+            else
                 kr[u].zero();
-                vr[u].zero();
-            }
         } else {
             const int rc = r < nrows ? r : nrows - 1;
             kr[u].load(Kb + (size_t)rc * D + seg * EPL);
-            vr[u].load(Vb + (size_t)rc * D + seg * EPL);
-        }
-    }
-    // lane h < RR "holds" row row0 + h: it finishes that row's logit and probability
-    const int hr = row0 + lane;
-    const bool hexist = lane < RR && hr < nrows;
-    bool hvalid = hexist;
-    double addend = 0.0;
-    if (MASKED) {
-        if (hvalid && posb) hvalid = posb[hr] >= 0;
-        if (hvalid && wb) {
-            const int wv = wb[hr];
-            hvalid = wv > 0;
-            if (wv > 1) addend = alpha * log((double)wv);
         }
     }
 #pragma unroll
-    for (int g = 0; g < G; ++g) {
-#pragma unroll
-        for (int u = 0; u < UU; ++u) {
-            double p = 0.0;
-#pragma unroll
-            for (int e = 0; e < EPL; ++e) p = fma(st.qd[g][e], (double)kr[u].get(e), p);
-            part_w[(u * RPL + grp) * (LPR + 1) + seg] = p;
-        }
-        wave_sync();
-        double z = -INFINITY;
-        if (hvalid) {
-            double a = 0.0;
-#pragma unroll
-            for (int i = 0; i < LPR; ++i) a += part_w[lane * (LPR + 1) + i];
-            z = a * scale + addend;
-        }
-        if (hexist) zt[(size_t)g * Bz + zidx0 + hr] = z;
-        const float zf = (float)z;
-        const float tmax = wave_max(zf);
-        if (tmax > -INFINITY) {   // wave-uniform
-            const float m_new = fmaxf(st.m[g], tmax);
-            const float corr = __expf(st.m[g] - m_new);
-            const float p = hvalid ? __expf(zf - m_new) : 0.f;
-            st.l[g] = st.l[g] * corr + p;
-            st.m[g] = m_new;
-            if (lane < RR) pbuf_w[(lane % RPL) * UU + lane / RPL] = p;
-            wave_sync();
-#pragma unroll
-            for (int e = 0; e < EPL; ++e) st.acc[g][e] *= corr;
-#pragma unroll
-            for (int u = 0; u < UU; ++u) {
-                const float pu = pbuf_w[grp * UU + u];
-#pragma unroll
-                for (int e = 0; e < EPL; ++e) st.acc[g][e] = fmaf(pu, vr[u].get(e), st.acc[g][e]);
+    for (int h = 0; h < UU; h += UH) {
+        // lane x < UH*RPL "holds" row row0 + h*RPL + x: it finishes that row's logit
+        const int hr = row0 + h * RPL + lane;
+        const bool hexist = lane < UH * RPL && hr < nrows;
+        bool hvalid = hexist;
+        double addend = 0.0;
+        if (MASKED) {
+            if (hvalid && posb) hvalid = posb[hr] >= 0;
+            if (hvalid && wb) {
+                const int wv = wb[hr];
+                hvalid = wv > 0;
+                if (wv > 1) addend = alpha * log((double)wv);
             }
         }
-        wave_sync();
+#pragma unroll
+        for (int g = 0; g < G; ++g) {
+            double qv[EPL];
+            qq.get(g, seg, D, qv);
+#pragma unroll
+            for (int u = 0; u < UH; ++u) {
+                double p = 0.0;
+#pragma unroll
+                for (int e = 0; e < EPL; ++e) p = fma(qv[e], (double)kr[h + u].get(e), p);
+                part_w[(u * RPL + grp) * (LPR + 1) + seg] = p;
+            }
+            wave_sync();
+            if (hexist) {
+                double ev = 0.0;
+                if (hvalid) {
+                    double a = 0.0;
+#pragma unroll
+                    for (int i = 0; i < LPR; ++i) a += part_w[lane * (LPR + 1) + i];
+                    const double z = a * scale + addend;
+                    ev = exp(fmin(z - C[g], 690.0));
+                    lsum[g] += ev;
+                }
+                et[(size_t)g * Bz + zidx0 + hr] = ev;
+            }
+            wave_sync();
+        }
     }
 }
 
-template <typename T, int D, int G, int NW, int U>
-__global__ __launch_bounds__(NW * 64, (G == 1 ? 4 : (G == 2 ? 2 : 1))) void decode_kernel(DecodeArgs a) {
-    using Sh = DecodeShape<T, D, G, NW, U>;
-    constexpr int EPL = Sh::EPL, LPR = Sh::LPR, RPL = Sh::RPL, R = Sh::R, PART = Sh::PART, NT = Sh::NT;
+// Pass 2 on UU wave-wide loads of V rows: acc[g] += p * v with p = et * rL (fp32).
+// MASKED = true: rows whose probability is exactly 0 (empty slots among them) are not loaded.
+template <typename KT, int UU, bool MASKED, int D, int G, int EPL, int LPR, int RPL>
+__device__ __forceinline__ void v_tile(const KT* __restrict__ Vb, int row0, int nrows, int zidx0,
+                                       const double* rL, float (*acc)[EPL], const double* et, int Bz,
+                                       int lane) {
+    const int grp = lane / LPR, seg = lane % LPR;
+    Raw<KT, EPL> vr[UU];
+    float p[G][UU];
+#pragma unroll
+    for (int u = 0; u < UU; ++u) {
+        const int r = row0 + u * RPL + grp;
+        const bool exist = r < nrows;
+        if (!MASKED) {
+            const int rc = exist ? r : nrows - 1;
+            vr[u].load(Vb + (size_t)rc * D + seg * EPL);
+        }
+        bool any = false;
+#pragma unroll
+        for (int g = 0; g < G; ++g) {
+            const double ev = exist ? et[(size_t)g * Bz + zidx0 + r] : 0.0;
+            p[g][u] = (float)(ev * rL[g]);
+            any = any || (ev != 0.0);
+        }
+        if (MASKED) {
+            if (any) vr[u].load(Vb + (size_t)r * D + seg * EPL);
+            else vr[u].zero();
+        }
+    }
+#pragma unroll
+    for (int g = 0; g < G; ++g)
+#pragma unroll
+        for (int u = 0; u < UU; ++u)
+#pragma unroll
+            for (int e = 0; e < EPL; ++e) acc[g][e] = fmaf(p[g][u], vr[u].get(e), acc[g][e]);
+}
+
+// A wave that is behind gets the issue priority: the workgroups that share a compute unit
+// then advance together instead of oldest-first, which keeps all of them streaming to the
+// end of the sweep.  `done` of `total` work items are finished.
+__device__ __forceinline__ void prio_from_progress(int done, int total) {
+    const int q = (4 * done) / (total > 0 ? total : 1);
+    if (q >= 3) __builtin_amdgcn_s_setprio(0);
+    else if (q == 2) __builtin_amdgcn_s_setprio(1);
+    else if (q == 1) __builtin_amdgcn_s_setprio(2);
+    else __builtin_amdgcn_s_setprio(3);
+}
+
+template <typename T, int D, int G, int NW>
+__global__ __launch_bounds__(NW * 64, 4) void decode_kernel(DecodeArgs a) {
+    using Sh = DecodeShape<T, D, G, NW>;
+    constexpr int EPL = Sh::EPL, LPR = Sh::LPR, RPL = Sh::RPL, R = Sh::R, PART = Sh::PART, NT = Sh::NT, UT = Sh::UT;
+    constexpr bool QLDS = Sh::QLDS;
     const CacheView& cv = a.cv;
     const int lu = blockIdx.x;
     const int ug = a.unit0 + lu;
@@ -171,18 +218,14 @@ __global__ __launch_bounds__(NW * 64, (G == 1 ? 4 : (G == 2 ? 2 : 1))) void deco
 
     extern __shared__ __align__(16) unsigned char smem[];
     const int Bz = cv.cap + 1;
-    double* zt = reinterpret_cast<double*>(smem);                 // [G][Bz] logits, later exp(z - M)
-    double* part = zt + (size_t)G * Bz;                           // [NW][PART]
+    double* et = reinterpret_cast<double*>(smem);                 // [G][Bz] exp(logit - C) per slot
+    double* part = et + (size_t)G * Bz;                           // [NW][PART]
     double* red64 = part + NW * PART;                             // [NW][G]
-    double* l64 = red64 + NW * G;                                 // [G]
-    unsigned long long* keyw = reinterpret_cast<unsigned long long*>(l64 + G);   // [NW]
+    double* qlds = red64 + NW * G;                                // [G][D] (QLDS only)
+    unsigned long long* keyw = reinterpret_cast<unsigned long long*>(qlds + (QLDS ? G * D : 0));   // [NW]
     double* dotw = reinterpret_cast<double*>(keyw + NW);          // [NW]
     float* accw = reinterpret_cast<float*>(dotw + NW);            // [NW][G][D]
-    float* pbuf = accw + NW * G * D;                              // [NW][R]
-    float* mw = pbuf + NW * R;                                    // [NW][G]
-    float* lw = mw + NW * G;                                      // [NW][G]
-    float* Mg = lw + NW * G;                                      // [G]
-    int* misc = reinterpret_cast<int*>(Mg + G);                   // [4 + NW]
+    int* misc = reinterpret_cast<int*>(accw + NW * G * D);        // [4 + NW]
 
     T* Kt = reinterpret_cast<T*>(cv.Kt) + (size_t)ug * cv.cap_tok * D;
     T* Vt = reinterpret_cast<T*>(cv.Vt) + (size_t)ug * cv.cap_tok * D;
@@ -200,119 +243,160 @@ __global__ __launch_bounds__(NW * 64, (G == 1 ? 4 : (G == 2 ? 2 : 1))) void deco
     const double scale = cv.scale;
     const double alpha = (double)cv.alpha;
 
-    WaveState<G, EPL> st;
-#pragma unroll
-    for (int g = 0; g < G; ++g) {
-        float qf[EPL];
-        load_seg<EPL>(qp + g * D + seg * EPL, qf);
-#pragma unroll
-        for (int e = 0; e < EPL; ++e) { st.qd[g][e] = (double)qf[e]; st.acc[g][e] = 0.f; }
-        st.m[g] = -INFINITY;
-        st.l[g] = 0.f;
-    }
     if (tid == 0) misc[0] = -1;
+    Query<G, EPL, QLDS> qq;
+    qq.lds = qlds;
+    if (QLDS) {
+        for (int i = tid; i < G * D; i += NT) qlds[i] = (double)to_float(qp[i]);
+        __syncthreads();
+    } else {
+#pragma unroll
+        for (int g = 0; g < (QLDS ? 1 : G); ++g) {
+            float qf[EPL];
+            load_seg<EPL>(qp + g * D + seg * EPL, qf);
+#pragma unroll
+            for (int e = 0; e < EPL; ++e) qq.r[g][e] = (double)qf[e];
+        }
+    }
+    // reference logit C[g]: the incoming token against itself (every lane of every wave)
+    double C[G], lsum[G];
+    {
+        float kf[EPL];
+        load_seg<EPL>(knew + seg * EPL, kf);
+#pragma unroll
+        for (int g = 0; g < G; ++g) {
+            double qv[EPL];
+            qq.get(g, seg, D, qv);
+            double p = 0.0;
+#pragma unroll
+            for (int e = 0; e < EPL; ++e) p = fma(qv[e], (double)kf[e], p);
+#pragma unroll
+            for (int o = 1; o < LPR; o <<= 1) p += __shfl_xor(p, o, 64);
+            C[g] = p * scale;
+            lsum[g] = 0.0;
+        }
+    }
     double* part_w = part + wave * PART;
-    float* pbuf_w = pbuf + wave * R;
 
-    // ---- D1 + D2: one sweep over the token slots -------------------------------------
+    // ---- pass 1 (D1): logits of all slots, exp(logit - C) into LDS ---------------------
     const int ntiles = (ntok + R - 1) / R;
     if (full) {
-        for (int t = wave; t < ntiles; t += NW)
-            decode_tile<T, U, false, D, G, EPL, LPR, RPL>(Kt, Vt, t * R, ntok, Br, nullptr, nullptr, alpha, scale,
-                                                          st, zt, Bz, part_w, pbuf_w, lane);
+        for (int t = wave; t < ntiles; t += NW) {
+            prio_from_progress(t, 2 * ntiles);
+            k_tile<T, UT, false, D, G, EPL, LPR, RPL, QLDS>(Kt, t * R, ntok, Br, nullptr, nullptr, alpha, scale, qq, C,
+                                                            lsum, et, Bz, part_w, lane);
+        }
     } else {
         for (int t = wave; t * RPL < ntok; t += NW)
-            decode_tile<T, 1, true, D, G, EPL, LPR, RPL>(Kt, Vt, t * RPL, ntok, Br, pos + Br, nullptr, alpha, scale,
-                                                         st, zt, Bz, part_w, pbuf_w, lane);
+            k_tile<T, 1, true, D, G, EPL, LPR, RPL, QLDS>(Kt, t * RPL, ntok, Br, pos + Br, nullptr, alpha, scale, qq, C,
+                                                          lsum, et, Bz, part_w, lane);
     }
     // residual slots (fp32 rows, log-count term) and the incoming token itself
     for (int t = wave; t * RPL < Br; t += NW)
-        decode_tile<float, 1, true, D, G, EPL, LPR, RPL>(Kr, Vr, t * RPL, Br, 0, nullptr, w, alpha, scale,
-                                                         st, zt, Bz, part_w, pbuf_w, lane);
+        k_tile<float, 1, true, D, G, EPL, LPR, RPL, QLDS>(Kr, t * RPL, Br, 0, nullptr, w, alpha, scale, qq, C, lsum, et,
+                                                          Bz, part_w, lane);
     if (wave == NW - 1)
-        decode_tile<T, 1, false, D, G, EPL, LPR, RPL>(knew, vnew, 0, 1, B, nullptr, nullptr, alpha, scale,
-                                                      st, zt, Bz, part_w, pbuf_w, lane);
-
-    // ---- combine the waves' partial softmaxes -> out ---------------------------------
+        k_tile<T, 1, false, D, G, EPL, LPR, RPL, QLDS>(knew, 0, 1, B, nullptr, nullptr, alpha, scale, qq, C, lsum, et, Bz,
+                                                       part_w, lane);
 #pragma unroll
     for (int g = 0; g < G; ++g) {
-        const float ls = wave_sum(st.l[g]);
+        const double t = wave_sum(lsum[g]);
+        if (lane == 0) red64[wave * G + g] = t;
+    }
+    __syncthreads();
+    double rL[G];
+#pragma unroll
+    for (int g = 0; g < G; ++g) {
+        double t = 0.0;
+#pragma unroll
+        for (int x = 0; x < NW; ++x) t += red64[x * G + g];
+        rL[g] = 1.0 / t;
+    }
+
+    // ---- pass 2 (D2): out = sum p * v --------------------------------------------------
+    float acc[G][EPL];
+#pragma unroll
+    for (int g = 0; g < G; ++g)
+#pragma unroll
+        for (int e = 0; e < EPL; ++e) acc[g][e] = 0.f;
+    if (full) {
+        for (int t = wave; t < ntiles; t += NW) {
+            prio_from_progress(ntiles + t, 2 * ntiles);
+            v_tile<T, UT, false, D, G, EPL, LPR, RPL>(Vt, t * R, ntok, Br, rL, acc, et, Bz, lane);
+        }
+    } else {
+        for (int t = wave; t * RPL < ntok; t += NW)
+            v_tile<T, 1, true, D, G, EPL, LPR, RPL>(Vt, t * RPL, ntok, Br, rL, acc, et, Bz, lane);
+    }
+    __builtin_amdgcn_s_setprio(0);
+    for (int t = wave; t * RPL < Br; t += NW)
+        v_tile<float, 1, true, D, G, EPL, LPR, RPL>(Vr, t * RPL, Br, 0, rL, acc, et, Bz, lane);
+    if (wave == NW - 1)
+        v_tile<T, 1, false, D, G, EPL, LPR, RPL>(vnew, 0, 1, B, rL, acc, et, Bz, lane);
+
+    // Scores and positions of this thread's first batch of slots: requested now, used after the
+    // output has been combined, so that their latency is hidden.
+    constexpr int MCH = 8;
+    int pj[MCH];
+    float sj[MCH];
+#pragma unroll
+    for (int k = 0; k < MCH; ++k) {
+        const int j = k * NT + tid;
+        pj[k] = j < B ? pos[j] : -1;
+        sj[k] = j < B ? s[j] : 0.f;
+    }
+    // ---- combine the waves' partial outputs -> out -------------------------------------
+#pragma unroll
+    for (int g = 0; g < G; ++g) {
 #pragma unroll
         for (int e = 0; e < EPL; ++e) {
-            float v = st.acc[g][e];
+            float v = acc[g][e];
 #pragma unroll
             for (int o = LPR; o < 64; o <<= 1) v += __shfl_xor(v, o, 64);
             if (grp == 0) accw[(wave * G + g) * D + seg * EPL + e] = v;
         }
-        if (lane == 0) { mw[wave * G + g] = st.m[g]; lw[wave * G + g] = ls; }
     }
     __syncthreads();
     for (int idx = tid; idx < G * D; idx += NT) {
-        const int g = idx / D, c = idx % D;
-        float M = -INFINITY;
+        float o = 0.f;
 #pragma unroll
-        for (int x = 0; x < NW; ++x) M = fmaxf(M, mw[x * G + g]);
-        float L = 0.f, o = 0.f;
-#pragma unroll
-        for (int x = 0; x < NW; ++x) {
-            const float mx = mw[x * G + g];
-            const float f = mx > -INFINITY ? __expf(mx - M) : 0.f;
-            L += f * lw[x * G + g];
-            o += f * accw[(x * G + g) * D + c];
-        }
-        a.out[(size_t)lu * G * D + idx] = o / L;
-        if (c == 0) Mg[g] = M;
+        for (int x = 0; x < NW; ++x) o += accw[x * G * D + idx];
+        a.out[(size_t)lu * G * D + idx] = o;
     }
-    __syncthreads();
 
-    // ---- D3: fp64 softmax over the stored logits, score update ------------------------
-    {
-        double lsum[G];
-#pragma unroll
-        for (int g = 0; g < G; ++g) lsum[g] = 0.0;
-        for (int j = tid; j <= B; j += NT) {
-#pragma unroll
-            for (int g = 0; g < G; ++g) {
-                const double z = zt[(size_t)g * Bz + j];
-                const double e = z == -INFINITY ? 0.0 : exp(z - (double)Mg[g]);
-                zt[(size_t)g * Bz + j] = e;
-                lsum[g] += e;
-            }
-        }
-#pragma unroll
-        for (int g = 0; g < G; ++g) {
-            const double t = wave_sum(lsum[g]);
-            if (lane == 0) red64[wave * G + g] = t;
-        }
-        __syncthreads();
-        if (tid < G) {
-            double t = 0.0;
-            for (int x = 0; x < NW; ++x) t += red64[x * G + tid];
-            l64[tid] = t;
-        }
-        __syncthreads();
-    }
+    // ---- D3: score update (Eq. 3) and D4: eviction choice ------------------------------
     const double lam = (double)cv.lambda;
     const long long cand_hi = Tseen - Bp;   // evictable: position <= T - B_p (outside the latest B_p)
     unsigned long long best = ~0ull;
     int best_slot = -1;
-    for (int j = tid; j < B; j += NT) {
-        const int pj = pos[j];
-        const bool occ = j < Br ? (w[j] > 0) : (pj >= 0);
-        if (occ) {
-            double pm = 0.0;
+    for (int base = 0; base < B; base += NT * MCH) {
+        if (base > 0) {
 #pragma unroll
-            for (int g = 0; g < G; ++g) pm += zt[(size_t)g * Bz + j] / l64[g];
-            pm /= (double)G;
-            const float sn = (float)(lam * (double)s[j] + pm);
-            s[j] = sn;
-            if (full && j >= Br && (long long)pj <= cand_hi) {
-                const unsigned long long key = ((unsigned long long)__float_as_uint(sn) << 32) | (uint32_t)pj;
+            for (int k = 0; k < MCH; ++k) {
+                const int j = base + k * NT + tid;
+                pj[k] = j < B ? pos[j] : -1;
+                sj[k] = j < B ? s[j] : 0.f;
+            }
+        }
+#pragma unroll
+        for (int k = 0; k < MCH; ++k) {
+            const int j = base + k * NT + tid;
+            if (j >= B) continue;
+            if (pj[k] >= 0) {   // occupied (a residual slot carries the position of its first token)
+                double pm = 0.0;
+#pragma unroll
+                for (int g = 0; g < G; ++g) pm += et[(size_t)g * Bz + j] * rL[g];
+                pm /= (double)G;
+                const float sn = (float)(lam * (double)sj[k] + pm);
+                s[j] = sn;
+                if (full && j >= Br && (long long)pj[k] <= cand_hi) {
+                    const unsigned long long key = ((unsigned long long)__float_as_uint(sn) << 32) | (uint32_t)pj[k];
+                    if (key < best) { best = key; best_slot = j; }
+                }
+            } else if (!full && j >= Br) {
+                const unsigned long long key = (unsigned long long)j;   // lowest free token slot
                 if (key < best) { best = key; best_slot = j; }
             }
-        } else if (!full && j >= Br) {
-            const unsigned long long key = (unsigned long long)j;   // lowest free token slot
-            if (key < best) { best = key; best_slot = j; }
         }
     }
     {
@@ -389,7 +473,7 @@ __global__ __launch_bounds__(NW * 64, (G == 1 ? 4 : (G == 2 ? 2 : 1))) void deco
     if (tid == 0) {
         double pm = 0.0;
 #pragma unroll
-        for (int g = 0; g < G; ++g) pm += zt[(size_t)g * Bz + B] / l64[g];
+        for (int g = 0; g < G; ++g) pm += et[(size_t)g * Bz + B] * rL[g];
         pm /= (double)G;
         pos[c] = (int32_t)Tseen;
         w[c] = 1;
@@ -403,12 +487,13 @@ __global__ __launch_bounds__(NW * 64, (G == 1 ? 4 : (G == 2 ? 2 : 1))) void deco
 }
 
 // Host side: pick the instantiation for (D, G) and launch one workgroup per unit.
+constexpr int DECODE_NW = 4;
+
 template <typename T, int D, int G>
 inline hipError_t launch_decode_dg(const DecodeArgs& a, hipStream_t stream) {
-    constexpr int NW = 4, U = 4;
-    using Sh = DecodeShape<T, D, G, NW, U>;
+    using Sh = DecodeShape<T, D, G, DECODE_NW>;
     const size_t lds = Sh::lds_bytes(a.cv.cap);
-    auto kern = decode_kernel<T, D, G, NW, U>;
+    auto kern = decode_kernel<T, D, G, DECODE_NW>;
     static bool attr_set = false;
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
@@ -416,12 +501,12 @@ inline hipError_t launch_decode_dg(const DecodeArgs& a, hipStream_t stream) {
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    hipLaunchKernelGGL(kern, dim3(a.n_units), dim3(NW * 64), lds, stream, a);
+    hipLaunchKernelGGL(kern, dim3(a.n_units), dim3(DECODE_NW * 64), lds, stream, a);
     return hipGetLastError();
 }
 
 template <typename T, int D, int G>
-inline size_t decode_lds_dg(int cap) { return DecodeShape<T, D, G, 4, 4>::lds_bytes(cap); }
+inline size_t decode_lds_dg(int cap) { return DecodeShape<T, D, G, DECODE_NW>::lds_bytes(cap); }
 
 template <typename T>
 inline hipError_t launch_decode_t(const DecodeArgs& a, hipStream_t stream) {
