@@ -42,7 +42,7 @@ struct DecodeShape {
     static constexpr int EPL = 16 / sizeof(T);   // elements per lane (one 16-byte load)
     static constexpr int LPR = D / EPL;          // lanes per row
     static constexpr int RPL = 64 / LPR;         // rows per wave-wide load
-    static constexpr int UT = 8;                 // wave-wide loads per tile
+    static constexpr int UT = 4;                 // wave-wide loads per tile (two tiles are in flight)
     static constexpr int UH = 4;                 // loads per reduction granule
     static constexpr int R = UT * RPL;           // rows per wave tile
     static constexpr int PART = UH * RPL * (LPR + 1);   // doubles of partial-dot staging per wave
@@ -81,35 +81,38 @@ struct Query {
     }
 };
 
-// Pass 1 on UU wave-wide loads of K rows [row0, row0 + UU*RPL) of the row array Kb (element
-// type KT, row length D); rows >= nrows do not exist.  For every existing row the holder lane
-// stores exp(logit - C) (0 for an empty row) at et[g][zidx0 + row] and adds it to lsum[g].
-// MASKED = false: every existing row is occupied; loads are branch-free (a row index past the
-//   end is clamped to the last row and its result discarded).
-// MASKED = true: posb / wb mark empty rows (pos < 0, w == 0), which are never loaded (an empty
-//   slot may hold any bit pattern); wb also adds alpha*log(w) to the logit (Eq. 4).
-template <typename KT, int UU, bool MASKED, int D, int G, int EPL, int LPR, int RPL, bool QLDS>
-__device__ __forceinline__ void k_tile(const KT* __restrict__ Kb, int row0, int nrows, int zidx0,
-                                       const int32_t* __restrict__ posb, const int32_t* __restrict__ wb,
-                                       double alpha, double scale, const Query<G, EPL, QLDS>& qq,
-                                       const double* C, double* lsum, double* et, int Bz,
-                                       double* part_w, int lane) {
-    constexpr int UH = UU < 4 ? UU : 4;
+// Branch-free load of UU wave-wide loads of rows [row0, row0 + UU*RPL) of a row array whose
+// rows all exist and are occupied up to nrows: a row index past the end is clamped to the last
+// row (its result is discarded by the compute step).
+template <typename KT, int UU, int D, int EPL, int LPR, int RPL>
+__device__ __forceinline__ void tile_load(Raw<KT, EPL>* dst, const KT* __restrict__ base, int row0, int nrows,
+                                          int lane) {
     const int grp = lane / LPR, seg = lane % LPR;
-    Raw<KT, EPL> kr[UU];
+    if (row0 + UU * RPL <= nrows) {
+        const KT* p = base + ((size_t)(row0 + grp) * D + seg * EPL);
 #pragma unroll
-    for (int u = 0; u < UU; ++u) {
-        const int r = row0 + u * RPL + grp;
-        if (MASKED) {
-            if (r < nrows && (posb == nullptr || posb[r] >= 0) && (wb == nullptr || wb[r] > 0))
-                kr[u].load(Kb + (size_t)r * D + seg * EPL);
-            else
-                kr[u].zero();
-        } else {
-            const int rc = r < nrows ? r : nrows - 1;
-            kr[u].load(Kb + (size_t)rc * D + seg * EPL);
+        for (int u = 0; u < UU; ++u) dst[u].load(p + (size_t)u * RPL * D);
+    } else {
+#pragma unroll
+        for (int u = 0; u < UU; ++u) {
+            const int r = row0 + u * RPL + grp;
+            dst[u].load(base + (size_t)(r < nrows ? r : nrows - 1) * D + seg * EPL);
         }
     }
+}
+
+// Pass 1 on UU loaded wave-wide loads of K rows [row0, row0 + UU*RPL); rows >= nrows do not
+// exist.  For every existing row the holder lane stores exp(logit - C) (0 for an empty row) at
+// et[g][zidx0 + row] and adds it to lsum[g].  posb / wb (MASKED only) mark empty rows (pos < 0,
+// w == 0); wb also adds alpha*log(w) to the logit (Eq. 4).
+template <typename KT, int UU, bool MASKED, int D, int G, int EPL, int LPR, int RPL, bool QLDS>
+__device__ __forceinline__ void k_compute(const Raw<KT, EPL>* kr, int row0, int nrows, int zidx0,
+                                          const int32_t* __restrict__ posb, const int32_t* __restrict__ wb,
+                                          double alpha, double scale, const Query<G, EPL, QLDS>& qq,
+                                          const double* C, double* lsum, double* et, int Bz,
+                                          double* part_w, int lane) {
+    constexpr int UH = UU < 4 ? UU : 4;
+    const int grp = lane / LPR, seg = lane % LPR;
 #pragma unroll
     for (int h = 0; h < UU; h += UH) {
         // lane x < UH*RPL "holds" row row0 + h*RPL + x: it finishes that row's logit
@@ -154,41 +157,67 @@ __device__ __forceinline__ void k_tile(const KT* __restrict__ Kb, int row0, int 
     }
 }
 
-// Pass 2 on UU wave-wide loads of V rows: acc[g] += p * v with p = et * rL (fp32).
-// MASKED = true: rows whose probability is exactly 0 (empty slots among them) are not loaded.
-template <typename KT, int UU, bool MASKED, int D, int G, int EPL, int LPR, int RPL>
-__device__ __forceinline__ void v_tile(const KT* __restrict__ Vb, int row0, int nrows, int zidx0,
-                                       const double* rL, float (*acc)[EPL], const double* et, int Bz,
-                                       int lane) {
+// Pass 1 for rows that may be empty: load only the occupied ones (an empty slot may hold any
+// bit pattern), then k_compute.
+template <typename KT, int UU, int D, int G, int EPL, int LPR, int RPL, bool QLDS>
+__device__ __forceinline__ void k_tile_masked(const KT* __restrict__ Kb, int row0, int nrows, int zidx0,
+                                              const int32_t* __restrict__ posb, const int32_t* __restrict__ wb,
+                                              double alpha, double scale, const Query<G, EPL, QLDS>& qq,
+                                              const double* C, double* lsum, double* et, int Bz,
+                                              double* part_w, int lane) {
     const int grp = lane / LPR, seg = lane % LPR;
-    Raw<KT, EPL> vr[UU];
-    float p[G][UU];
+    Raw<KT, EPL> kr[UU];
 #pragma unroll
     for (int u = 0; u < UU; ++u) {
         const int r = row0 + u * RPL + grp;
-        const bool exist = r < nrows;
-        if (!MASKED) {
-            const int rc = exist ? r : nrows - 1;
-            vr[u].load(Vb + (size_t)rc * D + seg * EPL);
-        }
-        bool any = false;
+        if (r < nrows && (posb == nullptr || posb[r] >= 0) && (wb == nullptr || wb[r] > 0))
+            kr[u].load(Kb + (size_t)r * D + seg * EPL);
+        else
+            kr[u].zero();
+    }
+    k_compute<KT, UU, true, D, G, EPL, LPR, RPL, QLDS>(kr, row0, nrows, zidx0, posb, wb, alpha, scale, qq, C, lsum, et,
+                                                       Bz, part_w, lane);
+}
+
+// Pass 2 on UU loaded wave-wide loads of V rows: acc[g] += p * v with p = et * rL (fp32).
+template <typename KT, int UU, int D, int G, int EPL, int LPR, int RPL>
+__device__ __forceinline__ void v_compute(const Raw<KT, EPL>* vr, int row0, int nrows, int zidx0,
+                                          const double* rL, float (*acc)[EPL], const double* et, int Bz,
+                                          int lane) {
+    const int grp = lane / LPR;
+#pragma unroll
+    for (int u = 0; u < UU; ++u) {
+        const int r = row0 + u * RPL + grp;
 #pragma unroll
         for (int g = 0; g < G; ++g) {
-            const double ev = exist ? et[(size_t)g * Bz + zidx0 + r] : 0.0;
-            p[g][u] = (float)(ev * rL[g]);
-            any = any || (ev != 0.0);
-        }
-        if (MASKED) {
-            if (any) vr[u].load(Vb + (size_t)r * D + seg * EPL);
-            else vr[u].zero();
+            const double ev = r < nrows ? et[(size_t)g * Bz + zidx0 + r] : 0.0;
+            const float p = (float)(ev * rL[g]);
+#pragma unroll
+            for (int e = 0; e < EPL; ++e) acc[g][e] = fmaf(p, vr[u].get(e), acc[g][e]);
         }
     }
+}
+
+// Pass 2 for rows that may be empty: rows whose probability is exactly 0 (empty slots among
+// them) are not loaded.
+template <typename KT, int UU, int D, int G, int EPL, int LPR, int RPL>
+__device__ __forceinline__ void v_tile_masked(const KT* __restrict__ Vb, int row0, int nrows, int zidx0,
+                                              const double* rL, float (*acc)[EPL], const double* et, int Bz,
+                                              int lane) {
+    const int grp = lane / LPR, seg = lane % LPR;
+    Raw<KT, EPL> vr[UU];
 #pragma unroll
-    for (int g = 0; g < G; ++g)
+    for (int u = 0; u < UU; ++u) {
+        const int r = row0 + u * RPL + grp;
+        bool any = false;
+        if (r < nrows) {
 #pragma unroll
-        for (int u = 0; u < UU; ++u)
-#pragma unroll
-            for (int e = 0; e < EPL; ++e) acc[g][e] = fmaf(p[g][u], vr[u].get(e), acc[g][e]);
+            for (int g = 0; g < G; ++g) any = any || (et[(size_t)g * Bz + zidx0 + r] != 0.0);
+        }
+        if (any) vr[u].load(Vb + (size_t)r * D + seg * EPL);
+        else vr[u].zero();
+    }
+    v_compute<KT, UU, D, G, EPL, LPR, RPL>(vr, row0, nrows, zidx0, rL, acc, et, Bz, lane);
 }
 
 // A wave that is behind gets the issue priority: the workgroups that share a compute unit
@@ -279,24 +308,35 @@ __global__ __launch_bounds__(NW * 64, 4) void decode_kernel(DecodeArgs a) {
     double* part_w = part + wave * PART;
 
     // ---- pass 1 (D1): logits of all slots, exp(logit - C) into LDS ---------------------
+    // Fast path (every token slot occupied): tiles are double-buffered in registers, the loads
+    // of the wave's next tile (or of its first V tile) are in flight while it works on this one.
     const int ntiles = (ntok + R - 1) / R;
+    Raw<T, EPL> bufA[UT], bufB[UT];
     if (full) {
-        for (int t = wave; t < ntiles; t += NW) {
+        int t = wave;
+        if (t < ntiles) tile_load<T, UT, D, EPL, LPR, RPL>(bufA, Kt, t * R, ntok, lane);
+        while (t < ntiles) {
+            const int tn = t + NW;
             prio_from_progress(t, 2 * ntiles);
-            k_tile<T, UT, false, D, G, EPL, LPR, RPL, QLDS>(Kt, t * R, ntok, Br, nullptr, nullptr, alpha, scale, qq, C,
-                                                            lsum, et, Bz, part_w, lane);
+            if (tn < ntiles) tile_load<T, UT, D, EPL, LPR, RPL>(bufB, Kt, tn * R, ntok, lane);
+            else tile_load<T, UT, D, EPL, LPR, RPL>(bufB, Vt, wave * R, ntok, lane);   // wave < ntiles here
+            k_compute<T, UT, false, D, G, EPL, LPR, RPL, QLDS>(bufA, t * R, ntok, Br, nullptr, nullptr, alpha, scale, qq,
+                                                               C, lsum, et, Bz, part_w, lane);
+#pragma unroll
+            for (int u = 0; u < UT; ++u) bufA[u] = bufB[u];
+            t = tn;
         }
     } else {
         for (int t = wave; t * RPL < ntok; t += NW)
-            k_tile<T, 1, true, D, G, EPL, LPR, RPL, QLDS>(Kt, t * RPL, ntok, Br, pos + Br, nullptr, alpha, scale, qq, C,
-                                                          lsum, et, Bz, part_w, lane);
+            k_tile_masked<T, 1, D, G, EPL, LPR, RPL, QLDS>(Kt, t * RPL, ntok, Br, pos + Br, nullptr, alpha, scale, qq, C,
+                                                           lsum, et, Bz, part_w, lane);
     }
     // residual slots (fp32 rows, log-count term) and the incoming token itself
     for (int t = wave; t * RPL < Br; t += NW)
-        k_tile<float, 1, true, D, G, EPL, LPR, RPL, QLDS>(Kr, t * RPL, Br, 0, nullptr, w, alpha, scale, qq, C, lsum, et,
-                                                          Bz, part_w, lane);
+        k_tile_masked<float, 1, D, G, EPL, LPR, RPL, QLDS>(Kr, t * RPL, Br, 0, nullptr, w, alpha, scale, qq, C, lsum, et,
+                                                           Bz, part_w, lane);
     if (wave == NW - 1)
-        k_tile<T, 1, false, D, G, EPL, LPR, RPL, QLDS>(knew, 0, 1, B, nullptr, nullptr, alpha, scale, qq, C, lsum, et, Bz,
+        k_tile_masked<T, 1, D, G, EPL, LPR, RPL, QLDS>(knew, 0, 1, B, nullptr, nullptr, alpha, scale, qq, C, lsum, et, Bz,
                                                        part_w, lane);
 #pragma unroll
     for (int g = 0; g < G; ++g) {
@@ -320,19 +360,25 @@ __global__ __launch_bounds__(NW * 64, 4) void decode_kernel(DecodeArgs a) {
 #pragma unroll
         for (int e = 0; e < EPL; ++e) acc[g][e] = 0.f;
     if (full) {
-        for (int t = wave; t < ntiles; t += NW) {
+        int t = wave;   // bufA already holds this wave's first V tile
+        while (t < ntiles) {
+            const int tn = t + NW;
             prio_from_progress(ntiles + t, 2 * ntiles);
-            v_tile<T, UT, false, D, G, EPL, LPR, RPL>(Vt, t * R, ntok, Br, rL, acc, et, Bz, lane);
+            if (tn < ntiles) tile_load<T, UT, D, EPL, LPR, RPL>(bufB, Vt, tn * R, ntok, lane);
+            v_compute<T, UT, D, G, EPL, LPR, RPL>(bufA, t * R, ntok, Br, rL, acc, et, Bz, lane);
+#pragma unroll
+            for (int u = 0; u < UT; ++u) bufA[u] = bufB[u];
+            t = tn;
         }
     } else {
         for (int t = wave; t * RPL < ntok; t += NW)
-            v_tile<T, 1, true, D, G, EPL, LPR, RPL>(Vt, t * RPL, ntok, Br, rL, acc, et, Bz, lane);
+            v_tile_masked<T, 1, D, G, EPL, LPR, RPL>(Vt, t * RPL, ntok, Br, rL, acc, et, Bz, lane);
     }
     __builtin_amdgcn_s_setprio(0);
     for (int t = wave; t * RPL < Br; t += NW)
-        v_tile<float, 1, true, D, G, EPL, LPR, RPL>(Vr, t * RPL, Br, 0, rL, acc, et, Bz, lane);
+        v_tile_masked<float, 1, D, G, EPL, LPR, RPL>(Vr, t * RPL, Br, 0, rL, acc, et, Bz, lane);
     if (wave == NW - 1)
-        v_tile<T, 1, false, D, G, EPL, LPR, RPL>(vnew, 0, 1, B, rL, acc, et, Bz, lane);
+        v_tile_masked<T, 1, D, G, EPL, LPR, RPL>(vnew, 0, 1, B, rL, acc, et, Bz, lane);
 
     // Scores and positions of this thread's first batch of slots: requested now, used after the
     // output has been combined, so that their latency is hidden.
