@@ -101,6 +101,9 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-units", type=int, default=4)
     ap.add_argument("--cpu-steps", type=int, default=512)
+    ap.add_argument("--pmc-calibration", action="store_true",
+                    help="after the run, copy a 1 GiB buffer three times with the library's plain copy kernel, so that "
+                         "a counter run holds dispatches of known size to scale FETCH_SIZE / WRITE_SIZE by")
     ap.add_argument("--skip-prefill", action="store_true",
                     help="fill the cache by import of synthetic rows instead of running the prefill (profiling runs)")
     args = ap.parse_args()
@@ -226,6 +229,13 @@ def main():
         "prefill_compress_ms_all_layers": prefill_ms,
         "setup_s": setup_s,
     }
+    if args.pmc_calibration:
+        src = torch.ones(1 << 30, dtype=torch.uint8, device=dev)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            zb.zsm_stream_copy(dst, src)
+        torch.cuda.synchronize()
+        res["pmc_calibration"] = {"kernel": "stream_copy_kernel", "bytes_read": 1 << 30, "bytes_written": 1 << 30, "launches": 3}
     if not args.no_cpu_baseline:
         res["cpu_baseline"] = cpu_baseline(wl, args.cpu_units, args.cpu_steps)
     print(json.dumps(res))
