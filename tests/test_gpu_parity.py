@@ -167,3 +167,37 @@ def test_error_paths_on_device():
         big.decode_step(qq, kk, kk)
     assert e.value.status == -2
     big.close(); cache.close()
+
+
+def test_workload2_full_size_sampled_units():
+    """The benchmark's launch configuration (1024 units, all 32 layers per launch, B = 2700 after a
+    54 000-token prompt): prefill and decode run at full size on the device, a sample of units
+    is recomputed by the oracle from the very bytes the device read."""
+    wl = synth.workload(2)
+    sample = [(0, 0, 0), (13, 0, 7), (20, 0, 16), (31, 0, 31)]
+    print(f"[case] workload 2 full size, sampled units {sample}", flush=True)
+    cache = pu.make_cache(wl, DEV)
+    units = [[[None] * wl.n_kv_heads for _ in range(wl.n_seqs)] for _ in range(wl.n_layers)]
+    for l in range(wl.n_layers):
+        Q, K, V, lens = synth.prompt(wl, l, device=DEV)
+        cache.prefill_compress(l, Q, K, V, lens)
+        pairs = [(b, h) for (ll, b, h) in sample if ll == l]
+        if pairs:
+            torch.cuda.synchronize()
+            got = pu.oracle_prefill_layer(wl, Q, K, V, lens, sel=pairs)
+            for b, h in pairs:
+                units[l][b][h] = got[b][h]
+            print(f"[step] layer {l}: oracle prefill of {pairs} done", flush=True)
+        del Q, K, V
+    cache.release_workspace()
+    pu.compare_all_state(wl, cache, units, pu.tol_for(wl.dtype), "after prefill", sample)
+    print("[step] prefill parity ok on the sampled units", flush=True)
+    st = pu.run_decode_parity(wl, cache, units, 8, sel=sample, gen_device=DEV)
+    print(f"[done] workload 2 full size: unit-steps={st.unit_steps} evictions={st.evictions} near_ties={st.near_ties} "
+          f"max|out err|={st.max_out_err:.2e} scores bit-equal {st.s_bit_equal}/{st.s_total}", flush=True)
+    assert st.evictions == st.unit_steps
+    # every unit of the launch advanced, not only the sampled ones
+    for l in (0, 17, 31):
+        n_seen = cache.export_layer(l)["n_seen"]
+        assert (n_seen == wl.prompt_len + 8).all()
+    cache.close()
