@@ -231,8 +231,11 @@ __device__ __forceinline__ void prio_from_progress(int done, int total) {
     else __builtin_amdgcn_s_setprio(3);
 }
 
+// Occupancy target: 4 waves per SIMD for G = 1 (four workgroups per compute unit, LDS permitting);
+// the per-head state of grouped queries needs more registers and its LDS footprint caps the
+// residency anyway.
 template <typename T, int D, int G, int NW>
-__global__ __launch_bounds__(NW * 64, 4) void decode_kernel(DecodeArgs a) {
+__global__ __launch_bounds__(NW * 64, (G == 1 ? 4 : 2)) void decode_kernel(DecodeArgs a) {
     using Sh = DecodeShape<T, D, G, NW>;
     constexpr int EPL = Sh::EPL, LPR = Sh::LPR, RPL = Sh::RPL, R = Sh::R, PART = Sh::PART, NT = Sh::NT, UT = Sh::UT;
     constexpr bool QLDS = Sh::QLDS;

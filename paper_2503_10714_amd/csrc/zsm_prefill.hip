@@ -33,35 +33,59 @@ __global__ void pf_convert_q(const T* __restrict__ Q, double* __restrict__ Qd, i
     }
 }
 
-// ---- P1 / P2: logits of the window queries against a tile of keys ------------------------
-// MODE 0: per (row, tile) maximum and sum of exp for the causal softmax row (Eq. 1).
-// MODE 1: s_t = sum over rows of roww * exp(z - rowm)  (Eq. 3 unrolled over the window).
-// One thread per key; the query rows are wave-uniform and come through scalar loads.
-template <typename T, int D, int MODE>
-__global__ __launch_bounds__(PF_TK) void pf_score_kernel(PrefillArgs a, PrefillWs ws) {
+// ---- reference logit of every query row: the row's own key (Eq. 1 with t = i) -------------
+// With fp64 exponentials a softmax row needs no running maximum, only a reference that keeps
+// exp() in range; the query's logit against its own position is one (differences are clamped
+// at 690, far outside anything a softmax in the storage precision could resolve).
+template <typename T, int D>
+__global__ __launch_bounds__(64) void pf_self_logit(PrefillArgs a, PrefillWs ws) {
     const CacheView& cv = a.cv;
     const int lu = blockIdx.y;
     const int b = lu / cv.H;
     const int Tb = seq_len_of(a, b);
+    const int nb = a.W < Tb ? a.W : Tb;
+    const int G = cv.G;
+    const int idx = blockIdx.x;             // g * Wp + r
+    const int g = idx / ws.Wp, r = idx % ws.Wp;
+    if (g >= G || r >= nb) return;
+    const int lane = threadIdx.x;
+    const double* q = reinterpret_cast<const double*>(a.ws + ws.Qd) + (((size_t)lu * G + g) * ws.Wp + r) * D;
+    const T* k = reinterpret_cast<const T*>(a.K) + ((size_t)lu * a.T_max + (Tb - nb + r)) * D;
+    double p = 0.0;
+    for (int c = lane; c < D; c += 64) p = fma(q[c], (double)to_float(k[c]), p);
+    p = wave_sum(p);
+    if (lane == 0) reinterpret_cast<double*>(a.ws + ws.rowm)[((size_t)lu * G + g) * ws.Wp + r] = p * cv.scale;
+}
+
+// ---- P1 / P2: logits of the window queries against the keys ------------------------------
+// One thread per key; the query rows are wave-uniform and come through scalar loads.
+// MODE 0: l_i = sum over keys t <= i of exp(z_it - C_i) (the softmax denominator of Eq. 1);
+//         a workgroup covers PF_KCH passes of PF_TK keys, keeps per-thread partial sums and
+//         reduces them once; the partial per (row, workgroup) goes to the workspace.
+// MODE 1: s_t = sum over rows of roww_i * exp(z_it - C_i)  (Eq. 3 unrolled over the window).
+// The workspace arrays come as separate restrict-qualified arguments: that tells the compiler
+// that the stores of one mode cannot touch the query rows, which keeps their loads scalar.
+template <typename T, int D, int MODE>
+__global__ __launch_bounds__(PF_TK) void pf_score_kernel(PrefillArgs a, PrefillWs ws, const double* __restrict__ Qd,
+                                                         const double* __restrict__ rowm,
+                                                         const double* __restrict__ roww, double* __restrict__ pl,
+                                                         float* __restrict__ sc) {
+    const CacheView& cv = a.cv;
+    const int lu = blockIdx.y;
+    const int b = lu / cv.H;
+    const int Tb = seq_len_of(a, b);
+    constexpr int NPASS = MODE == 0 ? PF_KCH : 1;
     const int tile = blockIdx.x;
-    const int t0 = tile * PF_TK;
-    if (t0 >= Tb) return;
+    const int tbase = tile * PF_TK * NPASS;
+    if (tbase >= Tb) return;
     const int W = a.W, G = cv.G, Wp = ws.Wp;
     const int nb = W < Tb ? W : Tb;
     const int qpos0 = Tb - nb;                 // position of query row 0
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int t = t0 + tid;
-    const bool tvalid = t < Tb;
-    const T* krow = reinterpret_cast<const T*>(a.K) + ((size_t)lu * a.T_max + (tvalid ? t : Tb - 1)) * D;
-    const double* Qd = reinterpret_cast<const double*>(a.ws + ws.Qd);
-    double* pm = reinterpret_cast<double*>(a.ws + ws.pm);
-    double* pl = reinterpret_cast<double*>(a.ws + ws.pl);
-    const double* rowm = reinterpret_cast<const double*>(a.ws + ws.rowm);
-    const double* roww = reinterpret_cast<const double*>(a.ws + ws.roww);
+    const T* Kbase = reinterpret_cast<const T*>(a.K) + (size_t)lu * a.T_max * D;
     const double scale = cv.scale;
     constexpr int NWV = PF_TK / 64;
     __shared__ double red[PF_MR][NWV];
-    __shared__ double bm[PF_MR];
 
     double s_acc = 0.0;
     for (int g = 0; g < G; ++g) {
@@ -69,73 +93,67 @@ __global__ __launch_bounds__(PF_TK) void pf_score_kernel(PrefillArgs a, PrefillW
         for (int r0 = 0; r0 < nb; r0 += PF_MR) {
             const int rlast = (r0 + PF_MR < nb ? r0 + PF_MR : nb) - 1;
             const size_t rowbase = head * Wp + r0;
-            if (t0 > qpos0 + rlast) {          // every key of this tile is in the future of these rows
-                if (MODE == 0 && tid < PF_MR) {
-                    pm[(rowbase + tid) * ws.ntiles + tile] = -INFINITY;
-                    pl[(rowbase + tid) * ws.ntiles + tile] = 0.0;
-                }
-                continue;
-            }
-            double acc[PF_MR];
-#pragma unroll
-            for (int i = 0; i < PF_MR; ++i) acc[i] = 0.0;
-            const double* qb = Qd + rowbase * D;
-            for (int c0 = 0; c0 < D; c0 += 8) {
-                float kf[8];
-                load_seg<8>(krow + c0, kf);
-                double kd[8];
-#pragma unroll
-                for (int e = 0; e < 8; ++e) kd[e] = (double)kf[e];
-#pragma unroll
-                for (int i = 0; i < PF_MR; ++i) {
-#pragma unroll
-                    for (int e = 0; e < 8; ++e) acc[i] = fma(qb[(size_t)i * D + c0 + e], kd[e], acc[i]);
-                }
-            }
+            double lsum[MODE == 0 ? PF_MR : 1];
             if (MODE == 0) {
-                double z[PF_MR];
+#pragma unroll
+                for (int i = 0; i < PF_MR; ++i) lsum[i] = 0.0;
+            }
+            for (int pass = 0; pass < NPASS; ++pass) {
+                const int t0 = tbase + pass * PF_TK;
+                // every key of this pass in the future of these rows, or past the prompt: nothing to add
+                if (t0 >= Tb || t0 > qpos0 + rlast) break;
+                const int t = t0 + tid;
+                const bool tvalid = t < Tb;
+                const T* krow = Kbase + (size_t)(tvalid ? t : Tb - 1) * D;
+                double acc[PF_MR];
+#pragma unroll
+                for (int i = 0; i < PF_MR; ++i) acc[i] = 0.0;
+                const double* qb = Qd + rowbase * D;
+                for (int c0 = 0; c0 < D; c0 += 8) {
+                    float kf[8];
+                    load_seg<8>(krow + c0, kf);
+                    double kd[8];
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) kd[e] = (double)kf[e];
+#pragma unroll
+                    for (int i = 0; i < PF_MR; ++i) {
+#pragma unroll
+                        for (int e = 0; e < 8; ++e) acc[i] = fma(qb[(size_t)i * D + c0 + e], kd[e], acc[i]);
+                    }
+                }
 #pragma unroll
                 for (int i = 0; i < PF_MR; ++i) {
                     const bool ok = tvalid && (r0 + i) < nb && t <= qpos0 + r0 + i;
-                    z[i] = ok ? acc[i] * scale : -INFINITY;
-                    const double wm = wave_max_d(z[i]);
-                    if (lane == 0) red[i][wave] = wm;
+                    if (ok) {
+                        const double e = exp(fmin(acc[i] * scale - rowm[rowbase + i], 690.0));
+                        if (MODE == 0) lsum[i] += e;
+                        else s_acc += roww[rowbase + i] * e;
+                    }
                 }
-                __syncthreads();
-                if (tid < PF_MR) {
-                    double m = red[tid][0];
-                    for (int x = 1; x < NWV; ++x) m = fmax(m, red[tid][x]);
-                    bm[tid] = m;
-                }
-                __syncthreads();
+            }
+            if (MODE == 0) {
 #pragma unroll
                 for (int i = 0; i < PF_MR; ++i) {
-                    const double m = bm[i];
-                    const double e = z[i] == -INFINITY ? 0.0 : exp(z[i] - m);
-                    const double ws_ = wave_sum(e);
+                    const double ws_ = wave_sum(lsum[i]);
                     if (lane == 0) red[i][wave] = ws_;
                 }
                 __syncthreads();
                 if (tid < PF_MR) {
                     double l = 0.0;
                     for (int x = 0; x < NWV; ++x) l += red[tid][x];
-                    pm[(rowbase + tid) * ws.ntiles + tile] = bm[tid];
-                    pl[(rowbase + tid) * ws.ntiles + tile] = l;
+                    pl[(rowbase + tid) * ws.nsums + tile] = l;
                 }
                 __syncthreads();
-            } else {
-#pragma unroll
-                for (int i = 0; i < PF_MR; ++i) {
-                    const bool ok = tvalid && (r0 + i) < nb && t <= qpos0 + r0 + i;
-                    if (ok) s_acc += roww[rowbase + i] * exp(acc[i] * scale - rowm[rowbase + i]);
-                }
             }
         }
     }
-    if (MODE == 1 && tvalid) reinterpret_cast<float*>(a.ws + ws.sc)[(size_t)lu * a.T_max + t] = (float)s_acc;
+    if (MODE == 1) {
+        const int t = tbase + tid;
+        if (t < Tb) sc[(size_t)lu * a.T_max + t] = (float)s_acc;
+    }
 }
 
-// ---- P1b: combine the tiles' (max, sum) per query row -----------------------------------
+// ---- P1b: combine the workgroups' partial denominators per query row ---------------------
 __global__ void pf_row_combine(PrefillArgs a, PrefillWs ws) {
     const CacheView& cv = a.cv;
     const int lu = blockIdx.x;
@@ -143,23 +161,15 @@ __global__ void pf_row_combine(PrefillArgs a, PrefillWs ws) {
     const int Tb = seq_len_of(a, b);
     const int nb = a.W < Tb ? a.W : Tb;
     const int G = cv.G, Wp = ws.Wp;
-    const double* pm = reinterpret_cast<const double*>(a.ws + ws.pm);
     const double* pl = reinterpret_cast<const double*>(a.ws + ws.pl);
-    double* rowm = reinterpret_cast<double*>(a.ws + ws.rowm);
     double* roww = reinterpret_cast<double*>(a.ws + ws.roww);
-    const int nt = (Tb + PF_TK - 1) / PF_TK;
+    const int nt = (Tb + PF_TK * PF_KCH - 1) / (PF_TK * PF_KCH);
     const double lam = (double)cv.lambda;
     for (int idx = threadIdx.x; idx < G * nb; idx += blockDim.x) {
         const int g = idx / nb, r = idx % nb;
         const size_t row = ((size_t)lu * G + g) * Wp + r;
-        double M = -INFINITY;
-        for (int x = 0; x < nt; ++x) M = fmax(M, pm[row * ws.ntiles + x]);
         double L = 0.0;
-        for (int x = 0; x < nt; ++x) {
-            const double m = pm[row * ws.ntiles + x];
-            if (m > -INFINITY) L += pl[row * ws.ntiles + x] * exp(m - M);
-        }
-        rowm[row] = M;
+        for (int x = 0; x < nt; ++x) L += pl[row * ws.nsums + x];
         roww[row] = pow(lam, (double)(nb - 1 - r)) / ((double)G * L);
     }
 }
@@ -400,9 +410,15 @@ hipError_t launch_prefill_td(const PrefillArgs& a, hipStream_t st) {
     hipLaunchKernelGGL((pf_convert_q<T>), dim3(1024), dim3(256), 0, st, reinterpret_cast<const T*>(a.Q),
                        reinterpret_cast<double*>(a.ws + ws.Qd), a.W, ws.Wp, D, n_heads);
     const dim3 gs(ws.ntiles, a.n_units);
-    hipLaunchKernelGGL((pf_score_kernel<T, D, 0>), gs, dim3(PF_TK), 0, st, a, ws);
+    hipLaunchKernelGGL((pf_self_logit<T, D>), dim3(cv.G * ws.Wp, a.n_units), dim3(64), 0, st, a, ws);
+    const double* Qd = reinterpret_cast<const double*>(a.ws + ws.Qd);
+    const double* rowm = reinterpret_cast<const double*>(a.ws + ws.rowm);
+    const double* roww = reinterpret_cast<const double*>(a.ws + ws.roww);
+    double* pl = reinterpret_cast<double*>(a.ws + ws.pl);
+    float* sc = reinterpret_cast<float*>(a.ws + ws.sc);
+    hipLaunchKernelGGL((pf_score_kernel<T, D, 0>), dim3(ws.nsums, a.n_units), dim3(PF_TK), 0, st, a, ws, Qd, rowm, roww, pl, sc);
     hipLaunchKernelGGL(pf_row_combine, dim3(a.n_units), dim3(256), 0, st, a, ws);
-    hipLaunchKernelGGL((pf_score_kernel<T, D, 1>), gs, dim3(PF_TK), 0, st, a, ws);
+    hipLaunchKernelGGL((pf_score_kernel<T, D, 1>), gs, dim3(PF_TK), 0, st, a, ws, Qd, rowm, roww, pl, sc);
     hipLaunchKernelGGL(pf_select, dim3(a.n_units), dim3(SEL_NT), 0, st, a, ws);
     constexpr int EPL = 16 / sizeof(T), LPR = D / EPL, RPB = 256 / LPR;
     const int gblocks = (cv.cap_tok + RPB * 4 - 1) / (RPB * 4);

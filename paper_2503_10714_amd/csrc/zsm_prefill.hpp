@@ -19,13 +19,14 @@ struct PrefillArgs {
     char* ws;
 };
 
-constexpr int PF_TK = 256;     // keys per workgroup in the scoring kernels
+constexpr int PF_TK = 256;     // keys per workgroup pass in the scoring kernels (one per thread)
+constexpr int PF_KCH = 4;      // key passes per workgroup in the row-sum kernel (PF_TK * PF_KCH keys)
 constexpr int PF_MR = 32;      // query rows per pass
 constexpr int PF_RC = 512;     // prompt positions per workgroup in the residual sum
 
 struct PrefillWs {
-    size_t Qd, pm, pl, rowm, roww, sc, keep, kept_pos, sel, rsum, total;
-    int Wp, ntiles, nchunks;
+    size_t Qd, pl, rowm, roww, sc, keep, kept_pos, sel, rsum, total;
+    int Wp, ntiles, nsums, nchunks;
 };
 
 inline PrefillWs prefill_ws_layout(const CacheView& cv, int T_max, int W) {
@@ -33,12 +34,12 @@ inline PrefillWs prefill_ws_layout(const CacheView& cv, int T_max, int W) {
     const size_t units = (size_t)cv.S * cv.H;
     w.Wp = (W + PF_MR - 1) / PF_MR * PF_MR;
     w.ntiles = (T_max + PF_TK - 1) / PF_TK;
+    w.nsums = (T_max + PF_TK * PF_KCH - 1) / (PF_TK * PF_KCH);
     w.nchunks = (T_max + PF_RC - 1) / PF_RC;
     auto up = [](size_t x) { return (x + 255) & ~(size_t)255; };
     size_t o = 0;
     w.Qd = o; o += up(sizeof(double) * units * cv.G * w.Wp * cv.D);
-    w.pm = o; o += up(sizeof(double) * units * cv.G * w.Wp * w.ntiles);
-    w.pl = o; o += up(sizeof(double) * units * cv.G * w.Wp * w.ntiles);
+    w.pl = o; o += up(sizeof(double) * units * cv.G * w.Wp * w.nsums);
     w.rowm = o; o += up(sizeof(double) * units * cv.G * w.Wp);
     w.roww = o; o += up(sizeof(double) * units * cv.G * w.Wp);
     w.sc = o; o += up(sizeof(float) * units * T_max);
