@@ -97,8 +97,10 @@ size_t zsm_prefill_workspace_bytes(const zsm_cache_t* cache, int32_t T_max, int3
  *   seq_lens   device int32 [S]: T_b, 0 <= T_b <= T_max.
  *   workspace  device, 256-byte aligned, ws_bytes >= zsm_prefill_workspace_bytes().
  * The layer's cache must be empty (freshly allocated or re-imported empty).
- * B_r > 1 is accepted by the decode step; this call currently supports B_r <= 1 and
- * returns ZSM_E_SHAPE otherwise.
+ * With B_r = 1 the residual slot is the mean of all absorbed tokens (parallel sums); with
+ * B_r >= 2 the tokens are absorbed one after the other as Alg. 1 prescribes (sequential per
+ * unit: about a microsecond per absorbed token).  B_r <= 64 here (the decode step takes any
+ * B_r); ZSM_E_SHAPE otherwise.
  */
 int zsm_prefill_compress(zsm_cache_t* cache, int32_t layer, const void* Q, int32_t W,
                          const void* K, const void* V, const int32_t* seq_lens,

@@ -233,7 +233,7 @@ int zsm_prefill_compress(zsm_cache_t* cache, int32_t layer, const void* Q, int32
     int rc = check_layer(cache, layer);
     if (rc) return rc;
     if (T_max < 1 || W < 1) return ZSM_E_SHAPE;
-    if (cache->cfg.n_residual > 1) return ZSM_E_SHAPE;
+    if (cache->cfg.n_residual > 64) return ZSM_E_SHAPE;
     if (!aligned16(Q) || !aligned16(K) || !aligned16(V)) return ZSM_E_ALIGN;
     if ((reinterpret_cast<uintptr_t>(workspace) & 255) != 0) return ZSM_E_ALIGN;
     if (ws_bytes < prefill_workspace_bytes(cache->cv, T_max, W)) return ZSM_E_NOMEM;

@@ -402,6 +402,134 @@ __global__ __launch_bounds__(256) void pf_residual_final(PrefillArgs a, PrefillW
     }
 }
 
+// ---- P5 for B_r >= 2: Alg. 1's residual branch, token by token --------------------------
+// The tokens that were not kept are absorbed in position order: the first B_r open the
+// residual slots, every later one is merged into the slot with the largest key dot product
+// (Eq. 5, lowest index on ties) by the incremental mean of Eq. 6.  Each merge changes a key
+// the next token's choice depends on, so the walk is sequential per unit: one wave per unit,
+// lane r owns residual slot r for the dot products (keys and values live in LDS in their fp32
+// storage form and are rounded to it after every merge), lanes own channels for the merge.
+constexpr int PF_RMAX = 64;   // residual slots the wave can own
+
+template <typename T, int D>
+__global__ __launch_bounds__(64) void pf_residual_greedy(PrefillArgs a, PrefillWs ws) {
+    const CacheView& cv = a.cv;
+    const int lu = blockIdx.x;
+    const int ug = a.unit0 + lu;
+    const int b = lu / cv.H;
+    const int Tb = seq_len_of(a, b);
+    const int Br = cv.Br;
+    const int lane = threadIdx.x;
+    constexpr int RS = D + 4;   // padded row stride (floats): lanes reading 16 bytes of different rows hit different banks
+    constexpr int CPL = D / 64; // channels per lane in the merge
+    extern __shared__ __align__(16) unsigned char smem[];
+    float* Krs = reinterpret_cast<float*>(smem);            // [Br][RS]
+    float* Vrs = Krs + (size_t)Br * RS;                      // [Br][RS]
+    double* ktok = reinterpret_cast<double*>(Vrs + (size_t)Br * RS);   // [D]
+    float* s = cv.s + (size_t)ug * cv.cap;
+    int32_t* pos = cv.pos + (size_t)ug * cv.cap;
+    int32_t* w = cv.w + (size_t)ug * cv.cap;
+    float* Kr = cv.Kr + (size_t)ug * Br * D;
+    float* Vr = cv.Vr + (size_t)ug * Br * D;
+    const unsigned char* keep = reinterpret_cast<const unsigned char*>(a.ws + ws.keep) + (size_t)lu * a.T_max;
+    const float* sc = reinterpret_cast<const float*>(a.ws + ws.sc) + (size_t)lu * a.T_max;
+    const T* Ksrc = reinterpret_cast<const T*>(a.K) + (size_t)lu * a.T_max * D;
+    const T* Vsrc = reinterpret_cast<const T*>(a.V) + (size_t)lu * a.T_max * D;
+
+    for (int i = lane; i < Br * RS; i += 64) { Krs[i] = 0.f; Vrs[i] = 0.f; }
+    int wcnt = 0;          // lane r: fusion count of slot r
+    int n_open = 0;        // residual slots opened so far (wave-uniform)
+    wave_sync();
+    // next token's row is requested one step ahead
+    int t = 0;
+    while (t < Tb && keep[t]) ++t;
+    float kc[CPL], vc[CPL];
+    if (t < Tb) {
+#pragma unroll
+        for (int x = 0; x < CPL; ++x) {
+            kc[x] = to_float(Ksrc[(size_t)t * D + lane + 64 * x]);
+            vc[x] = to_float(Vsrc[(size_t)t * D + lane + 64 * x]);
+        }
+    }
+    while (t < Tb) {
+        int tn = t + 1;
+        while (tn < Tb && keep[tn]) ++tn;
+        float kn[CPL], vn[CPL];
+        if (tn < Tb) {
+#pragma unroll
+            for (int x = 0; x < CPL; ++x) {
+                kn[x] = to_float(Ksrc[(size_t)tn * D + lane + 64 * x]);
+                vn[x] = to_float(Vsrc[(size_t)tn * D + lane + 64 * x]);
+            }
+        }
+        if (n_open < Br) {
+            // Alg. 1: the residual set still has room, the token opens slot n_open
+#pragma unroll
+            for (int x = 0; x < CPL; ++x) {
+                Krs[n_open * RS + lane + 64 * x] = kc[x];
+                Vrs[n_open * RS + lane + 64 * x] = vc[x];
+            }
+            if (lane == n_open) {
+                wcnt = 1;
+                pos[n_open] = t;
+                s[n_open] = sc[t];
+            }
+            ++n_open;
+            wave_sync();
+        } else {
+#pragma unroll
+            for (int x = 0; x < CPL; ++x) ktok[lane + 64 * x] = (double)kc[x];
+            wave_sync();
+            // Eq. 5: lane r forms k_r . k_t
+            double dot = -INFINITY;
+            if (lane < Br) {
+                double p = 0.0;
+                const float* kr = Krs + lane * RS;
+#pragma unroll 4
+                for (int c = 0; c < D; c += 4) {
+                    const float4 kv = *reinterpret_cast<const float4*>(kr + c);
+                    p = fma((double)kv.x, ktok[c + 0], p);
+                    p = fma((double)kv.y, ktok[c + 1], p);
+                    p = fma((double)kv.z, ktok[c + 2], p);
+                    p = fma((double)kv.w, ktok[c + 3], p);
+                }
+                dot = p;
+            }
+            int rbest = lane < Br ? lane : 0x7fffffff;
+#pragma unroll
+            for (int o = 32; o > 0; o >>= 1) {
+                const double d2 = __shfl_xor(dot, o, 64);
+                const int r2 = __shfl_xor(rbest, o, 64);
+                if (r2 != 0x7fffffff && (rbest == 0x7fffffff || d2 > dot || (d2 == dot && r2 < rbest))) { dot = d2; rbest = r2; }
+            }
+            // Eq. 6 on the chosen slot, rounded to the fp32 storage form
+            const double wd = (double)__shfl(wcnt, rbest, 64);
+#pragma unroll
+            for (int x = 0; x < CPL; ++x) {
+                const int c = lane + 64 * x;
+                const double k0 = (double)Krs[rbest * RS + c], v0 = (double)Vrs[rbest * RS + c];
+                Krs[rbest * RS + c] = (float)(__dadd_rn(__dmul_rn(wd, k0), (double)kc[x]) / (wd + 1.0));
+                Vrs[rbest * RS + c] = (float)(__dadd_rn(__dmul_rn(wd, v0), (double)vc[x]) / (wd + 1.0));
+            }
+            if (lane == rbest) ++wcnt;
+            wave_sync();
+        }
+#pragma unroll
+        for (int x = 0; x < CPL; ++x) { kc[x] = kn[x]; vc[x] = vn[x]; }
+        t = tn;
+    }
+    // write the residual slots back; slots never opened are empty
+    for (int i = lane; i < Br * D; i += 64) {
+        const int r = i / D, c = i % D;
+        Kr[i] = Krs[r * RS + c];
+        Vr[i] = Vrs[r * RS + c];
+    }
+    if (lane < Br) {
+        w[lane] = wcnt;
+        if (wcnt == 0) { pos[lane] = -1; s[lane] = 0.f; }
+    }
+}
+
 template <typename T, int D>
 hipError_t launch_prefill_td(const PrefillArgs& a, hipStream_t st) {
     const CacheView& cv = a.cv;
@@ -423,9 +551,21 @@ hipError_t launch_prefill_td(const PrefillArgs& a, hipStream_t st) {
     constexpr int EPL = 16 / sizeof(T), LPR = D / EPL, RPB = 256 / LPR;
     const int gblocks = (cv.cap_tok + RPB * 4 - 1) / (RPB * 4);
     hipLaunchKernelGGL((pf_gather<T, D>), dim3(gblocks > 0 ? gblocks : 1, a.n_units), dim3(256), 0, st, a, ws);
-    if (cv.Br > 0) {
+    if (cv.Br == 1) {
+        // a single residual slot is the plain mean of everything absorbed: parallel sums
         hipLaunchKernelGGL((pf_residual_partial<T, D>), dim3(ws.nchunks, a.n_units), dim3(256), 0, st, a, ws);
         hipLaunchKernelGGL((pf_residual_final<D>), dim3(a.n_units), dim3(256), 0, st, a, ws);
+    } else if (cv.Br > 1) {
+        const size_t lds = sizeof(float) * 2 * (size_t)cv.Br * (D + 4) + sizeof(double) * D;
+        auto kern = pf_residual_greedy<T, D>;
+        static bool attr_set = false;
+        if (!attr_set) {
+            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                               hipFuncAttributeMaxDynamicSharedMemorySize, 96 * 1024);
+            if (e != hipSuccess) return e;
+            attr_set = true;
+        }
+        hipLaunchKernelGGL(kern, dim3(a.n_units), dim3(64), lds, st, a, ws);
     }
     return hipGetLastError();
 }

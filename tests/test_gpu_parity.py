@@ -78,6 +78,12 @@ PREFILL_CASES = {
     "no_context": lambda: small("pf_no_context", prompt_len=300, budget=9, prox=8, window=8),
     "full_history_gqa2": lambda: small("pf_fullhist_gqa2", q_per_kv=2, prompt_len=300, budget=40, window=0, dtype="f16"),
     "tile_edges": lambda: small("pf_tile_edges", prompt_len=513, budget=64, window=32, n_kv_heads=3),
+    # more than one residual slot: the absorbed tokens choose their slot one after the other (Eq. 5)
+    "two_residual": lambda: small("pf_two_residual", n_residual=2, prompt_len=400, budget=40),
+    "five_residual_gqa2_f16": lambda: small("pf_five_residual", n_residual=5, prompt_len=600, budget=64, dtype="f16",
+                                            head_dim=128, q_per_kv=2, outliers=True),
+    "residual_not_filled": lambda: small("pf_res_not_filled", n_residual=8, prompt_len=45, budget=48, window=8),
+    "residual_64_bf16": lambda: small("pf_res64", n_residual=64, prompt_len=700, budget=200, dtype="bf16", head_dim=128),
 }
 
 
@@ -114,6 +120,8 @@ FULL_CASES = {
     "cfg2_slice": (lambda: synth.workload(2).sliced(n_layers=2, n_kv_heads=3, layer0=7, head0=5), 24),
     "cfg3_slice": (lambda: synth.workload(3).sliced(n_layers=1, n_seqs=3, n_kv_heads=2, layer0=3, seq0=11, head0=9), 24),
     "cfg4_slice": (lambda: synth.workload(4).sliced(n_layers=1, n_seqs=2, n_kv_heads=2, layer0=30, seq0=3, head0=6), 24),
+    # the paper's recommended residual share (dense ratio 0.02 of B - B_p: 27 slots at B = 2700) on workload 2's shape
+    "cfg2_slice_27_residual": (lambda: synth.workload(2).sliced(n_layers=1, n_kv_heads=2, layer0=11, head0=20, n_residual=27), 24),
 }
 
 
