@@ -101,6 +101,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-units", type=int, default=4)
     ap.add_argument("--cpu-steps", type=int, default=512)
+    ap.add_argument("--n-residual", type=int, default=None,
+                    help="override the workload's number of residual slots B_r (B stays the same, B_c shrinks)")
     ap.add_argument("--pmc-calibration", action="store_true",
                     help="after the run, copy a 1 GiB buffer three times with the library's plain copy kernel, so that "
                          "a counter run holds dispatches of known size to scale FETCH_SIZE / WRITE_SIZE by")
@@ -123,6 +125,8 @@ def main():
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
     wl = synth.workload(args.workload)
+    if args.n_residual is not None:
+        wl = wl.sliced(n_residual=args.n_residual)
     if wl.ragged is not None:
         print("bench.py: ragged workloads are parity-test cases, not bench lines", file=sys.stderr)
         sys.exit(2)
