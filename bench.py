@@ -101,6 +101,9 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-units", type=int, default=4)
     ap.add_argument("--cpu-steps", type=int, default=512)
+    ap.add_argument("--layers-per-launch", type=int, default=0,
+                    help="0 = all layers of the workload in one launch (the headline configuration); N = one launch "
+                         "per N layers, as a model that runs its layers one after the other would call it")
     ap.add_argument("--n-residual", type=int, default=None,
                     help="override the workload's number of residual slots B_r (B stays the same, B_c shrinks)")
     ap.add_argument("--pmc-calibration", action="store_true",
@@ -175,8 +178,13 @@ def main():
     torch.cuda.synchronize()
     setup_s = time.perf_counter() - t_setup
 
+    lpl = args.layers_per_launch if args.layers_per_launch > 0 else L
+
     def step(i):
-        zb.zsm_decode_step(cache.handle, 0, L, q_all[i], k_all[i], v_all[i], out, info[0], info[1], info[2])
+        for l0 in range(0, L, lpl):
+            l1 = min(L, l0 + lpl)
+            zb.zsm_decode_step(cache.handle, l0, l1, q_all[i, l0:l1], k_all[i, l0:l1], v_all[i, l0:l1], out[l0:l1],
+                               info[0][l0:l1], info[1][l0:l1], info[2][l0:l1])
 
     for i in range(args.warmup):
         step(i)
@@ -192,12 +200,12 @@ def main():
     gpu_ms = evs[0].elapsed_time(evs[-1])
     per = sorted(evs[i].elapsed_time(evs[i + 1]) for i in range(args.steps))
     ms_per_step = wall * 1e3 / args.steps
-    kernel_ms = gpu_ms / args.steps            # average launch duration over the timed region (HIP events)
+    kernel_ms = gpu_ms / args.steps / ((L + lpl - 1) // lpl)   # average launch duration over the timed region (HIP events)
     units = wl.n_units
     value = units * args.steps / wall
 
     bytes_unit = algorithmic_bytes_per_unit_step(bp[0] + bc[0], br, d, e, G)
-    bytes_launch = bytes_unit * units
+    bytes_launch = bytes_unit * units / ((L + lpl - 1) // lpl)
     achieved = bytes_launch / (kernel_ms * 1e-3) / 1e9
     traffic = read_traffic_from_profiles(f"decode_step_cfg{args.workload}_pmc.md")
 
@@ -222,7 +230,8 @@ def main():
         "dtype": wl.dtype, "data": "synthetic",
         "config": {"workload": f"cfg{args.workload} {wl.name}: {L} layers x {S} seq x {H} KV heads = {units} units, G={G}, d={d}, "
                                f"{wl.dtype} KV, prompt {wl.prompt_len} tokens -> B={wl.slot_capacity} slots "
-                               f"(B_p={bp[0]}, B_c={bc[0]}, B_r={br}), all layers in one launch",
+                               f"(B_p={bp[0]}, B_c={bc[0]}, B_r={br}), "
+                               + ("all layers in one launch" if lpl >= L else f"{lpl} layer(s) per launch"),
                    "units": units, "slots_per_unit": wl.slot_capacity},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
                      "traffic": traffic, "kernel": "zsm::decode_kernel", "kernel_ms": kernel_ms,

@@ -103,13 +103,14 @@ __device__ __forceinline__ void tile_load(Raw<KT, EPL>* dst, const KT* __restric
 
 // Pass 1 on UU loaded wave-wide loads of K rows [row0, row0 + UU*RPL); rows >= nrows do not
 // exist.  For every existing row the holder lane stores exp(logit - C) (0 for an empty row) at
-// et[g][zidx0 + row] and adds it to lsum[g].  posb / wb (MASKED only) mark empty rows (pos < 0,
-// w == 0); wb also adds alpha*log(w) to the logit (Eq. 4).
+// et[g][zidx0 + row] and adds it to lsum[g] (and, when mz is given, keeps the largest logit - C
+// in mz[g]).  posb / wb (MASKED only) mark empty rows (pos < 0, w == 0); wb also adds
+// alpha*log(w) to the logit (Eq. 4).
 template <typename KT, int UU, bool MASKED, int D, int G, int EPL, int LPR, int RPL, bool QLDS>
 __device__ __forceinline__ void k_compute(const Raw<KT, EPL>* kr, int row0, int nrows, int zidx0,
                                           const int32_t* __restrict__ posb, const int32_t* __restrict__ wb,
                                           double alpha, double scale, const Query<G, EPL, QLDS>& qq,
-                                          const double* C, double* lsum, double* et, int Bz,
+                                          const double* C, double* lsum, float* mz, double* et, int Bz,
                                           double* part_w, int lane) {
     constexpr int UH = UU < 4 ? UU : 4;
     const int grp = lane / LPR, seg = lane % LPR;
@@ -149,6 +150,7 @@ __device__ __forceinline__ void k_compute(const Raw<KT, EPL>* kr, int row0, int 
                     const double z = a * scale + addend;
                     ev = exp(fmin(z - C[g], 690.0));
                     lsum[g] += ev;
+                    if (mz) mz[g] = fmaxf(mz[g], (float)(z - C[g]));
                 }
                 et[(size_t)g * Bz + zidx0 + hr] = ev;
             }
@@ -163,7 +165,7 @@ template <typename KT, int UU, int D, int G, int EPL, int LPR, int RPL, bool QLD
 __device__ __forceinline__ void k_tile_masked(const KT* __restrict__ Kb, int row0, int nrows, int zidx0,
                                               const int32_t* __restrict__ posb, const int32_t* __restrict__ wb,
                                               double alpha, double scale, const Query<G, EPL, QLDS>& qq,
-                                              const double* C, double* lsum, double* et, int Bz,
+                                              const double* C, double* lsum, float* mz, double* et, int Bz,
                                               double* part_w, int lane) {
     const int grp = lane / LPR, seg = lane % LPR;
     Raw<KT, EPL> kr[UU];
@@ -175,8 +177,8 @@ __device__ __forceinline__ void k_tile_masked(const KT* __restrict__ Kb, int row
         else
             kr[u].zero();
     }
-    k_compute<KT, UU, true, D, G, EPL, LPR, RPL, QLDS>(kr, row0, nrows, zidx0, posb, wb, alpha, scale, qq, C, lsum, et,
-                                                       Bz, part_w, lane);
+    k_compute<KT, UU, true, D, G, EPL, LPR, RPL, QLDS>(kr, row0, nrows, zidx0, posb, wb, alpha, scale, qq, C, lsum, mz,
+                                                       et, Bz, part_w, lane);
 }
 
 // Pass 2 on UU loaded wave-wide loads of V rows: acc[g] += p * v with p = et * rL (fp32).
@@ -231,188 +233,32 @@ __device__ __forceinline__ void prio_from_progress(int done, int total) {
     else __builtin_amdgcn_s_setprio(3);
 }
 
-// Occupancy target: 4 waves per SIMD for G = 1 (four workgroups per compute unit, LDS permitting);
-// the per-head state of grouped queries needs more registers and its LDS footprint caps the
-// residency anyway.
+// Everything of a unit's cache that the end of a step touches.
+template <typename T>
+struct UnitRefs {
+    T* Kt; T* Vt;              // token slots
+    float* Kr; float* Vr;      // residual slots
+    float* s; int32_t* pos; int32_t* w;
+    const T* knew; const T* vnew;
+};
+
+constexpr int DECODE_MCH = 8;   // slots per thread whose score and position are requested ahead
+
+// D3-D6 of one unit, by the whole workgroup: score update (Eq. 3) from the per-slot
+// exp(logit - C) values in `et` (stride Bz per query head; LDS or global) and 1/L in rL,
+// eviction choice, residual absorption (Eq. 5, Eq. 6) and the write of the incoming token.
+// pj / sj hold the positions and scores of slots k*NT + tid, k < DECODE_MCH, loaded by the caller.
 template <typename T, int D, int G, int NW>
-__global__ __launch_bounds__(NW * 64, (G == 1 ? 4 : 2)) void decode_kernel(DecodeArgs a) {
-    using Sh = DecodeShape<T, D, G, NW>;
-    constexpr int EPL = Sh::EPL, LPR = Sh::LPR, RPL = Sh::RPL, R = Sh::R, PART = Sh::PART, NT = Sh::NT, UT = Sh::UT;
-    constexpr bool QLDS = Sh::QLDS;
-    const CacheView& cv = a.cv;
-    const int lu = blockIdx.x;
-    const int ug = a.unit0 + lu;
-    const int b = (ug / cv.H) % cv.S;
-    const int Bp = cv.Bp[b], Bc = cv.Bc[b], Br = cv.Br;
-    const int ntok = Bp + Bc, B = ntok + Br;
+__device__ __forceinline__ void decode_finish(const DecodeArgs& a, const CacheView& cv, const UnitRefs<T>& u, int lu,
+                                              int ug, int Bp, int Br, int B, long long Tseen, int nocc, bool full,
+                                              const double* et, int Bz, const double* rL, int* pj, float* sj,
+                                              unsigned long long* keyw, double* dotw, int* misc) {
+    constexpr int NT = NW * 64, MCH = DECODE_MCH;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int grp = lane / LPR, seg = lane % LPR;
-
-    extern __shared__ __align__(16) unsigned char smem[];
-    const int Bz = cv.cap + 1;
-    double* et = reinterpret_cast<double*>(smem);                 // [G][Bz] exp(logit - C) per slot
-    double* part = et + (size_t)G * Bz;                           // [NW][PART]
-    double* red64 = part + NW * PART;                             // [NW][G]
-    double* qlds = red64 + NW * G;                                // [G][D] (QLDS only)
-    unsigned long long* keyw = reinterpret_cast<unsigned long long*>(qlds + (QLDS ? G * D : 0));   // [NW]
-    double* dotw = reinterpret_cast<double*>(keyw + NW);          // [NW]
-    float* accw = reinterpret_cast<float*>(dotw + NW);            // [NW][G][D]
-    int* misc = reinterpret_cast<int*>(accw + NW * G * D);        // [4 + NW]
-
-    T* Kt = reinterpret_cast<T*>(cv.Kt) + (size_t)ug * cv.cap_tok * D;
-    T* Vt = reinterpret_cast<T*>(cv.Vt) + (size_t)ug * cv.cap_tok * D;
-    float* Kr = cv.Kr + (size_t)ug * Br * D;
-    float* Vr = cv.Vr + (size_t)ug * Br * D;
-    float* s = cv.s + (size_t)ug * cv.cap;
-    int32_t* pos = cv.pos + (size_t)ug * cv.cap;
-    int32_t* w = cv.w + (size_t)ug * cv.cap;
-    const T* qp = reinterpret_cast<const T*>(a.q) + (size_t)lu * G * D;
-    const T* knew = reinterpret_cast<const T*>(a.k_new) + (size_t)lu * D;
-    const T* vnew = reinterpret_cast<const T*>(a.v_new) + (size_t)lu * D;
-    const long long Tseen = cv.n_seen[ug];
-    const int nocc = cv.n_occ[ug];
-    const bool full = nocc == ntok;
-    const double scale = cv.scale;
-    const double alpha = (double)cv.alpha;
-
-    if (tid == 0) misc[0] = -1;
-    Query<G, EPL, QLDS> qq;
-    qq.lds = qlds;
-    if (QLDS) {
-        for (int i = tid; i < G * D; i += NT) qlds[i] = (double)to_float(qp[i]);
-        __syncthreads();
-    } else {
-#pragma unroll
-        for (int g = 0; g < (QLDS ? 1 : G); ++g) {
-            float qf[EPL];
-            load_seg<EPL>(qp + g * D + seg * EPL, qf);
-#pragma unroll
-            for (int e = 0; e < EPL; ++e) qq.r[g][e] = (double)qf[e];
-        }
-    }
-    // reference logit C[g]: the incoming token against itself (every lane of every wave)
-    double C[G], lsum[G];
-    {
-        float kf[EPL];
-        load_seg<EPL>(knew + seg * EPL, kf);
-#pragma unroll
-        for (int g = 0; g < G; ++g) {
-            double qv[EPL];
-            qq.get(g, seg, D, qv);
-            double p = 0.0;
-#pragma unroll
-            for (int e = 0; e < EPL; ++e) p = fma(qv[e], (double)kf[e], p);
-#pragma unroll
-            for (int o = 1; o < LPR; o <<= 1) p += __shfl_xor(p, o, 64);
-            C[g] = p * scale;
-            lsum[g] = 0.0;
-        }
-    }
-    double* part_w = part + wave * PART;
-
-    // ---- pass 1 (D1): logits of all slots, exp(logit - C) into LDS ---------------------
-    // Fast path (every token slot occupied): tiles are double-buffered in registers, the loads
-    // of the wave's next tile (or of its first V tile) are in flight while it works on this one.
-    const int ntiles = (ntok + R - 1) / R;
-    Raw<T, EPL> bufA[UT], bufB[UT];
-    if (full) {
-        int t = wave;
-        if (t < ntiles) tile_load<T, UT, D, EPL, LPR, RPL>(bufA, Kt, t * R, ntok, lane);
-        while (t < ntiles) {
-            const int tn = t + NW;
-            prio_from_progress(t, 2 * ntiles);
-            if (tn < ntiles) tile_load<T, UT, D, EPL, LPR, RPL>(bufB, Kt, tn * R, ntok, lane);
-            else tile_load<T, UT, D, EPL, LPR, RPL>(bufB, Vt, wave * R, ntok, lane);   // wave < ntiles here
-            k_compute<T, UT, false, D, G, EPL, LPR, RPL, QLDS>(bufA, t * R, ntok, Br, nullptr, nullptr, alpha, scale, qq,
-                                                               C, lsum, et, Bz, part_w, lane);
-#pragma unroll
-            for (int u = 0; u < UT; ++u) bufA[u] = bufB[u];
-            t = tn;
-        }
-    } else {
-        for (int t = wave; t * RPL < ntok; t += NW)
-            k_tile_masked<T, 1, D, G, EPL, LPR, RPL, QLDS>(Kt, t * RPL, ntok, Br, pos + Br, nullptr, alpha, scale, qq, C,
-                                                           lsum, et, Bz, part_w, lane);
-    }
-    // residual slots (fp32 rows, log-count term) and the incoming token itself
-    for (int t = wave; t * RPL < Br; t += NW)
-        k_tile_masked<float, 1, D, G, EPL, LPR, RPL, QLDS>(Kr, t * RPL, Br, 0, nullptr, w, alpha, scale, qq, C, lsum, et,
-                                                           Bz, part_w, lane);
-    if (wave == NW - 1)
-        k_tile_masked<T, 1, D, G, EPL, LPR, RPL, QLDS>(knew, 0, 1, B, nullptr, nullptr, alpha, scale, qq, C, lsum, et, Bz,
-                                                       part_w, lane);
-#pragma unroll
-    for (int g = 0; g < G; ++g) {
-        const double t = wave_sum(lsum[g]);
-        if (lane == 0) red64[wave * G + g] = t;
-    }
-    __syncthreads();
-    double rL[G];
-#pragma unroll
-    for (int g = 0; g < G; ++g) {
-        double t = 0.0;
-#pragma unroll
-        for (int x = 0; x < NW; ++x) t += red64[x * G + g];
-        rL[g] = 1.0 / t;
-    }
-
-    // ---- pass 2 (D2): out = sum p * v --------------------------------------------------
-    float acc[G][EPL];
-#pragma unroll
-    for (int g = 0; g < G; ++g)
-#pragma unroll
-        for (int e = 0; e < EPL; ++e) acc[g][e] = 0.f;
-    if (full) {
-        int t = wave;   // bufA already holds this wave's first V tile
-        while (t < ntiles) {
-            const int tn = t + NW;
-            prio_from_progress(ntiles + t, 2 * ntiles);
-            if (tn < ntiles) tile_load<T, UT, D, EPL, LPR, RPL>(bufB, Vt, tn * R, ntok, lane);
-            v_compute<T, UT, D, G, EPL, LPR, RPL>(bufA, t * R, ntok, Br, rL, acc, et, Bz, lane);
-#pragma unroll
-            for (int u = 0; u < UT; ++u) bufA[u] = bufB[u];
-            t = tn;
-        }
-    } else {
-        for (int t = wave; t * RPL < ntok; t += NW)
-            v_tile_masked<T, 1, D, G, EPL, LPR, RPL>(Vt, t * RPL, ntok, Br, rL, acc, et, Bz, lane);
-    }
-    __builtin_amdgcn_s_setprio(0);
-    for (int t = wave; t * RPL < Br; t += NW)
-        v_tile_masked<float, 1, D, G, EPL, LPR, RPL>(Vr, t * RPL, Br, 0, rL, acc, et, Bz, lane);
-    if (wave == NW - 1)
-        v_tile_masked<T, 1, D, G, EPL, LPR, RPL>(vnew, 0, 1, B, rL, acc, et, Bz, lane);
-
-    // Scores and positions of this thread's first batch of slots: requested now, used after the
-    // output has been combined, so that their latency is hidden.
-    constexpr int MCH = 8;
-    int pj[MCH];
-    float sj[MCH];
-#pragma unroll
-    for (int k = 0; k < MCH; ++k) {
-        const int j = k * NT + tid;
-        pj[k] = j < B ? pos[j] : -1;
-        sj[k] = j < B ? s[j] : 0.f;
-    }
-    // ---- combine the waves' partial outputs -> out -------------------------------------
-#pragma unroll
-    for (int g = 0; g < G; ++g) {
-#pragma unroll
-        for (int e = 0; e < EPL; ++e) {
-            float v = acc[g][e];
-#pragma unroll
-            for (int o = LPR; o < 64; o <<= 1) v += __shfl_xor(v, o, 64);
-            if (grp == 0) accw[(wave * G + g) * D + seg * EPL + e] = v;
-        }
-    }
-    __syncthreads();
-    for (int idx = tid; idx < G * D; idx += NT) {
-        float o = 0.f;
-#pragma unroll
-        for (int x = 0; x < NW; ++x) o += accw[x * G * D + idx];
-        a.out[(size_t)lu * G * D + idx] = o;
-    }
-
+    T* Kt = u.Kt; T* Vt = u.Vt;
+    float* Kr = u.Kr; float* Vr = u.Vr;
+    float* s = u.s; int32_t* pos = u.pos; int32_t* w = u.w;
+    const T* knew = u.knew; const T* vnew = u.vnew;
     // ---- D3: score update (Eq. 3) and D4: eviction choice ------------------------------
     const double lam = (double)cv.lambda;
     const long long cand_hi = Tseen - Bp;   // evictable: position <= T - B_p (outside the latest B_p)
@@ -533,6 +379,192 @@ __global__ __launch_bounds__(NW * 64, (G == 1 ? 4 : 2)) void decode_kernel(Decod
         if (a.evicted_pos) a.evicted_pos[lu] = ev_pos;
         if (a.merged_slot) a.merged_slot[lu] = merged;
     }
+}
+
+// Occupancy target: 4 waves per SIMD for G = 1 (four workgroups per compute unit, LDS permitting);
+// the per-head state of grouped queries needs more registers and its LDS footprint caps the
+// residency anyway.
+template <typename T, int D, int G, int NW>
+__global__ __launch_bounds__(NW * 64, (G == 1 ? 4 : 2)) void decode_kernel(DecodeArgs a) {
+    using Sh = DecodeShape<T, D, G, NW>;
+    constexpr int EPL = Sh::EPL, LPR = Sh::LPR, RPL = Sh::RPL, R = Sh::R, PART = Sh::PART, NT = Sh::NT, UT = Sh::UT;
+    constexpr bool QLDS = Sh::QLDS;
+    const CacheView& cv = a.cv;
+    const int lu = blockIdx.x;
+    const int ug = a.unit0 + lu;
+    const int b = (ug / cv.H) % cv.S;
+    const int Bp = cv.Bp[b], Bc = cv.Bc[b], Br = cv.Br;
+    const int ntok = Bp + Bc, B = ntok + Br;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int grp = lane / LPR, seg = lane % LPR;
+
+    extern __shared__ __align__(16) unsigned char smem[];
+    const int Bz = cv.cap + 1;
+    double* et = reinterpret_cast<double*>(smem);                 // [G][Bz] exp(logit - C) per slot
+    double* part = et + (size_t)G * Bz;                           // [NW][PART]
+    double* red64 = part + NW * PART;                             // [NW][G]
+    double* qlds = red64 + NW * G;                                // [G][D] (QLDS only)
+    unsigned long long* keyw = reinterpret_cast<unsigned long long*>(qlds + (QLDS ? G * D : 0));   // [NW]
+    double* dotw = reinterpret_cast<double*>(keyw + NW);          // [NW]
+    float* accw = reinterpret_cast<float*>(dotw + NW);            // [NW][G][D]
+    int* misc = reinterpret_cast<int*>(accw + NW * G * D);        // [4 + NW]
+
+    T* Kt = reinterpret_cast<T*>(cv.Kt) + (size_t)ug * cv.cap_tok * D;
+    T* Vt = reinterpret_cast<T*>(cv.Vt) + (size_t)ug * cv.cap_tok * D;
+    float* Kr = cv.Kr + (size_t)ug * Br * D;
+    float* Vr = cv.Vr + (size_t)ug * Br * D;
+    float* s = cv.s + (size_t)ug * cv.cap;
+    int32_t* pos = cv.pos + (size_t)ug * cv.cap;
+    int32_t* w = cv.w + (size_t)ug * cv.cap;
+    const T* qp = reinterpret_cast<const T*>(a.q) + (size_t)lu * G * D;
+    const T* knew = reinterpret_cast<const T*>(a.k_new) + (size_t)lu * D;
+    const T* vnew = reinterpret_cast<const T*>(a.v_new) + (size_t)lu * D;
+    const long long Tseen = cv.n_seen[ug];
+    const int nocc = cv.n_occ[ug];
+    const bool full = nocc == ntok;
+    const double scale = cv.scale;
+    const double alpha = (double)cv.alpha;
+
+    if (tid == 0) misc[0] = -1;
+    Query<G, EPL, QLDS> qq;
+    qq.lds = qlds;
+    if (QLDS) {
+        for (int i = tid; i < G * D; i += NT) qlds[i] = (double)to_float(qp[i]);
+        __syncthreads();
+    } else {
+#pragma unroll
+        for (int g = 0; g < (QLDS ? 1 : G); ++g) {
+            float qf[EPL];
+            load_seg<EPL>(qp + g * D + seg * EPL, qf);
+#pragma unroll
+            for (int e = 0; e < EPL; ++e) qq.r[g][e] = (double)qf[e];
+        }
+    }
+    // reference logit C[g]: the incoming token against itself (every lane of every wave)
+    double C[G], lsum[G];
+    {
+        float kf[EPL];
+        load_seg<EPL>(knew + seg * EPL, kf);
+#pragma unroll
+        for (int g = 0; g < G; ++g) {
+            double qv[EPL];
+            qq.get(g, seg, D, qv);
+            double p = 0.0;
+#pragma unroll
+            for (int e = 0; e < EPL; ++e) p = fma(qv[e], (double)kf[e], p);
+#pragma unroll
+            for (int o = 1; o < LPR; o <<= 1) p += __shfl_xor(p, o, 64);
+            C[g] = p * scale;
+            lsum[g] = 0.0;
+        }
+    }
+    double* part_w = part + wave * PART;
+
+    // ---- pass 1 (D1): logits of all slots, exp(logit - C) into LDS ---------------------
+    // Fast path (every token slot occupied): tiles are double-buffered in registers, the loads
+    // of the wave's next tile (or of its first V tile) are in flight while it works on this one.
+    const int ntiles = (ntok + R - 1) / R;
+    Raw<T, EPL> bufA[UT], bufB[UT];
+    if (full) {
+        int t = wave;
+        if (t < ntiles) tile_load<T, UT, D, EPL, LPR, RPL>(bufA, Kt, t * R, ntok, lane);
+        while (t < ntiles) {
+            const int tn = t + NW;
+            prio_from_progress(t, 2 * ntiles);
+            if (tn < ntiles) tile_load<T, UT, D, EPL, LPR, RPL>(bufB, Kt, tn * R, ntok, lane);
+            else tile_load<T, UT, D, EPL, LPR, RPL>(bufB, Vt, wave * R, ntok, lane);   // wave < ntiles here
+            k_compute<T, UT, false, D, G, EPL, LPR, RPL, QLDS>(bufA, t * R, ntok, Br, nullptr, nullptr, alpha, scale, qq,
+                                                               C, lsum, nullptr, et, Bz, part_w, lane);
+#pragma unroll
+            for (int u = 0; u < UT; ++u) bufA[u] = bufB[u];
+            t = tn;
+        }
+    } else {
+        for (int t = wave; t * RPL < ntok; t += NW)
+            k_tile_masked<T, 1, D, G, EPL, LPR, RPL, QLDS>(Kt, t * RPL, ntok, Br, pos + Br, nullptr, alpha, scale, qq, C,
+                                                           lsum, nullptr, et, Bz, part_w, lane);
+    }
+    // residual slots (fp32 rows, log-count term) and the incoming token itself
+    for (int t = wave; t * RPL < Br; t += NW)
+        k_tile_masked<float, 1, D, G, EPL, LPR, RPL, QLDS>(Kr, t * RPL, Br, 0, nullptr, w, alpha, scale, qq, C, lsum,
+                                                           nullptr, et, Bz, part_w, lane);
+    if (wave == NW - 1)
+        k_tile_masked<T, 1, D, G, EPL, LPR, RPL, QLDS>(knew, 0, 1, B, nullptr, nullptr, alpha, scale, qq, C, lsum, nullptr,
+                                                       et, Bz, part_w, lane);
+#pragma unroll
+    for (int g = 0; g < G; ++g) {
+        const double t = wave_sum(lsum[g]);
+        if (lane == 0) red64[wave * G + g] = t;
+    }
+    __syncthreads();
+    double rL[G];
+#pragma unroll
+    for (int g = 0; g < G; ++g) {
+        double t = 0.0;
+#pragma unroll
+        for (int x = 0; x < NW; ++x) t += red64[x * G + g];
+        rL[g] = 1.0 / t;
+    }
+
+    // ---- pass 2 (D2): out = sum p * v --------------------------------------------------
+    float acc[G][EPL];
+#pragma unroll
+    for (int g = 0; g < G; ++g)
+#pragma unroll
+        for (int e = 0; e < EPL; ++e) acc[g][e] = 0.f;
+    if (full) {
+        int t = wave;   // bufA already holds this wave's first V tile
+        while (t < ntiles) {
+            const int tn = t + NW;
+            prio_from_progress(ntiles + t, 2 * ntiles);
+            if (tn < ntiles) tile_load<T, UT, D, EPL, LPR, RPL>(bufB, Vt, tn * R, ntok, lane);
+            v_compute<T, UT, D, G, EPL, LPR, RPL>(bufA, t * R, ntok, Br, rL, acc, et, Bz, lane);
+#pragma unroll
+            for (int u = 0; u < UT; ++u) bufA[u] = bufB[u];
+            t = tn;
+        }
+    } else {
+        for (int t = wave; t * RPL < ntok; t += NW)
+            v_tile_masked<T, 1, D, G, EPL, LPR, RPL>(Vt, t * RPL, ntok, Br, rL, acc, et, Bz, lane);
+    }
+    __builtin_amdgcn_s_setprio(0);
+    for (int t = wave; t * RPL < Br; t += NW)
+        v_tile_masked<float, 1, D, G, EPL, LPR, RPL>(Vr, t * RPL, Br, 0, rL, acc, et, Bz, lane);
+    if (wave == NW - 1)
+        v_tile_masked<T, 1, D, G, EPL, LPR, RPL>(vnew, 0, 1, B, rL, acc, et, Bz, lane);
+
+    // Scores and positions of this thread's first batch of slots: requested now, used after the
+    // output has been combined, so that their latency is hidden.
+    constexpr int MCH = DECODE_MCH;
+    int pj[MCH];
+    float sj[MCH];
+#pragma unroll
+    for (int k = 0; k < MCH; ++k) {
+        const int j = k * NT + tid;
+        pj[k] = j < B ? pos[j] : -1;
+        sj[k] = j < B ? s[j] : 0.f;
+    }
+    // ---- combine the waves' partial outputs -> out -------------------------------------
+#pragma unroll
+    for (int g = 0; g < G; ++g) {
+#pragma unroll
+        for (int e = 0; e < EPL; ++e) {
+            float v = acc[g][e];
+#pragma unroll
+            for (int o = LPR; o < 64; o <<= 1) v += __shfl_xor(v, o, 64);
+            if (grp == 0) accw[(wave * G + g) * D + seg * EPL + e] = v;
+        }
+    }
+    __syncthreads();
+    for (int idx = tid; idx < G * D; idx += NT) {
+        float o = 0.f;
+#pragma unroll
+        for (int x = 0; x < NW; ++x) o += accw[x * G * D + idx];
+        a.out[(size_t)lu * G * D + idx] = o;
+    }
+
+    UnitRefs<T> u{Kt, Vt, Kr, Vr, s, pos, w, knew, vnew};
+    decode_finish<T, D, G, NW>(a, cv, u, lu, ug, Bp, Br, B, Tseen, nocc, full, et, Bz, rL, pj, sj, keyw, dotw, misc);
 }
 
 // Host side: pick the instantiation for (D, G) and launch one workgroup per unit.
