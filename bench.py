@@ -104,6 +104,8 @@ def main():
     ap.add_argument("--layers-per-launch", type=int, default=0,
                     help="0 = all layers of the workload in one launch (the headline configuration); N = one launch "
                          "per N layers, as a model that runs its layers one after the other would call it")
+    ap.add_argument("--decode-parts", type=int, default=0,
+                    help="workgroups per unit in the decode step: 0 = the library's choice per launch, 1 = never split, n = n")
     ap.add_argument("--n-residual", type=int, default=None,
                     help="override the workload's number of residual slots B_r (B stays the same, B_c shrinks)")
     ap.add_argument("--pmc-calibration", action="store_true",
@@ -179,6 +181,8 @@ def main():
     setup_s = time.perf_counter() - t_setup
 
     lpl = args.layers_per_launch if args.layers_per_launch > 0 else L
+    cache.set_decode_parts(args.decode_parts)
+    parts = cache.decode_parts(0, lpl)
 
     def step(i):
         for l0 in range(0, L, lpl):
@@ -231,7 +235,8 @@ def main():
         "config": {"workload": f"cfg{args.workload} {wl.name}: {L} layers x {S} seq x {H} KV heads = {units} units, G={G}, d={d}, "
                                f"{wl.dtype} KV, prompt {wl.prompt_len} tokens -> B={wl.slot_capacity} slots "
                                f"(B_p={bp[0]}, B_c={bc[0]}, B_r={br}), "
-                               + ("all layers in one launch" if lpl >= L else f"{lpl} layer(s) per launch"),
+                               + ("all layers in one launch" if lpl >= L else f"{lpl} layer(s) per launch")
+                               + (f", {parts} workgroups per unit" if parts > 1 else ", one workgroup per unit"),
                    "units": units, "slots_per_unit": wl.slot_capacity},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
                      "traffic": traffic, "kernel": "zsm::decode_kernel", "kernel_ms": kernel_ms,

@@ -58,7 +58,8 @@ typedef struct {
     float scale;            /* logit scale; 0 selects 1/sqrt(d) (Eq. 1)                 */
 } zsm_config_t;
 
-/* Bytes of device memory a cache of this shape needs (0 if the config is invalid). */
+/* Bytes of device memory a cache of this shape needs, the decode step's scratch area
+ * included (0 if the config is invalid). */
 size_t zsm_cache_bytes(const zsm_config_t* cfg);
 
 /*
@@ -127,13 +128,36 @@ int zsm_prefill_compress(zsm_cache_t* cache, int32_t layer, const void* Q, int32
  *   write_slot   device int32 [Ln, S, H] or NULL: slot that received the token
  *   evicted_pos  device int32 [Ln, S, H] or NULL: position of the evicted token, -1 if none
  *   merged_slot  device int32 [Ln, S, H] or NULL: residual slot that absorbed it, -1 if none
- * Limit: (slot_capacity + 1) * G * 8 bytes of per-unit logits must fit the 160 KB LDS
- * together with ~24 KB of staging, else ZSM_E_SHAPE.
+ * Launch shape: one workgroup per unit when the launch has many units; a launch of few
+ * units (one layer of a single sequence, say) is cut into several workgroups per unit,
+ * each sweeping a share of the slots, so that it still fills the chip.  The share's
+ * partial softmax sums and outputs meet in a scratch area inside the cache buffer; the
+ * result does not depend on the cut beyond fp32 rounding of the output (scores, choices
+ * and merged rows are formed in fp64 from the same per-slot values either way).
+ * Limit: the per-slot values of one workgroup, (slots + 1) * G * 8 bytes, must fit the
+ * 160 KB LDS together with ~24 KB of staging; a capacity too large for one workgroup is
+ * split automatically where the launch is small enough to be split (at most 1024 units),
+ * else ZSM_E_SHAPE.
  */
 int zsm_decode_step(zsm_cache_t* cache, int32_t layer_begin, int32_t layer_end,
                     const void* q, const void* k_new, const void* v_new, float* out,
                     int32_t* write_slot, int32_t* evicted_pos, int32_t* merged_slot,
                     void* stream);
+
+/*
+ * zsm_cache_set_decode_parts - how many workgroups share one unit in zsm_decode_step
+ * (split of the slot sweep, motivated by the paper's observation that overhead dominates
+ * short, small-batch settings, appendix on experimental details, text before the latency table): 0 = chosen per launch from
+ * the number of units (the default), 1 = never split, 2..64 = this many where the launch
+ * allows it (at most 1024 units and 8192 workgroups; fewer parts are used beyond that).
+ * ZSM_E_RANGE for other values.
+ */
+int zsm_cache_set_decode_parts(zsm_cache_t* cache, int32_t parts);
+
+/* Workgroups per unit that zsm_decode_step would use for layers [layer_begin, layer_end)
+ * with the current setting (>= 1), or a negative zsm_status (ZSM_E_SHAPE: no permitted
+ * cut fits the LDS).  Host-only, launches nothing. */
+int zsm_decode_parts(const zsm_cache_t* cache, int32_t layer_begin, int32_t layer_end);
 
 /*
  * zsm_cache_export / zsm_cache_import - copy one layer's state out of / into the cache

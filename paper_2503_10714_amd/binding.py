@@ -23,7 +23,8 @@ CODE_TORCH = {ZSM_F32: torch.float32, ZSM_F16: torch.float16, ZSM_BF16: torch.bf
 
 EXPORTS = [
     "zsm_cache_bytes", "zsm_cache_alloc", "zsm_cache_free", "zsm_prefill_workspace_bytes",
-    "zsm_prefill_compress", "zsm_decode_step", "zsm_cache_export", "zsm_cache_import",
+    "zsm_prefill_compress", "zsm_decode_step", "zsm_cache_set_decode_parts", "zsm_decode_parts",
+    "zsm_cache_export", "zsm_cache_import",
     "zsm_stream_read", "zsm_stream_copy", "zsm_strerror",
 ]
 
@@ -64,6 +65,10 @@ def lib() -> C.CDLL:
         L.zsm_prefill_compress.argtypes = [vp, i32, vp, i32, vp, vp, vp, i32, vp, sz, vp]
         L.zsm_decode_step.restype = C.c_int
         L.zsm_decode_step.argtypes = [vp, i32, i32, vp, vp, vp, vp, vp, vp, vp, vp]
+        L.zsm_cache_set_decode_parts.restype = C.c_int
+        L.zsm_cache_set_decode_parts.argtypes = [vp, i32]
+        L.zsm_decode_parts.restype = C.c_int
+        L.zsm_decode_parts.argtypes = [vp, i32, i32]
         L.zsm_cache_export.restype = C.c_int
         L.zsm_cache_export.argtypes = [vp, i32] + [vp] * 8 + [vp]
         L.zsm_cache_import.restype = C.c_int
@@ -144,6 +149,17 @@ def zsm_decode_step(handle, layer_begin, layer_end, q, k_new, v_new, out, write_
     rc = lib().zsm_decode_step(handle, layer_begin, layer_end, _ptr(q), _ptr(k_new), _ptr(v_new), _ptr(out),
                                _ptr(write_slot), _ptr(evicted_pos), _ptr(merged_slot), _stream(stream))
     _check(rc, "zsm_decode_step")
+
+
+def zsm_cache_set_decode_parts(handle, parts: int) -> None:
+    _check(lib().zsm_cache_set_decode_parts(handle, int(parts)), "zsm_cache_set_decode_parts")
+
+
+def zsm_decode_parts(handle, layer_begin: int, layer_end: int) -> int:
+    rc = int(lib().zsm_decode_parts(handle, int(layer_begin), int(layer_end)))
+    if rc < 0:
+        raise ZsmError(rc, "zsm_decode_parts")
+    return rc
 
 
 def zsm_cache_export(handle, layer, K=None, V=None, Kr=None, Vr=None, s=None, pos=None, w=None, n_seen=None, stream=None):
@@ -247,6 +263,12 @@ class Cache:
         with torch.cuda.device(self.device):
             zsm_decode_step(self.handle, layer_begin, layer_end, q, k_new, v_new, out, ws, ep, ms)
         return out, info
+
+    def set_decode_parts(self, parts: int) -> None:
+        zsm_cache_set_decode_parts(self.handle, parts)
+
+    def decode_parts(self, layer_begin=0, layer_end=None) -> int:
+        return zsm_decode_parts(self.handle, layer_begin, self.L if layer_end is None else layer_end)
 
     def export_layer(self, layer: int) -> dict:
         S, H, d, cap, Br = self.S, self.H, self.d, self.cap, self.B_r

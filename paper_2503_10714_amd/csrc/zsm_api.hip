@@ -21,6 +21,7 @@ struct zsm_cache {
     std::vector<int32_t> Bp, Bc;
     size_t bytes;
     int max_btok;   // max over sequences of B_p + B_c
+    int parts;      // workgroups per unit in the decode step: 0 = chosen per launch, 1 = never split, n = n
 };
 
 namespace {
@@ -48,9 +49,17 @@ bool config_ok(const zsm_config_t* c) {
     return true;
 }
 
+// Launches of the decode step that may be split over several workgroups per unit: at most
+// SP_MAX_UNITS units and SP_MAX_WGS workgroups (their partial results live in the cache buffer).
+constexpr int SP_MAX_UNITS = 1024;
+constexpr int SP_MAX_WGS = 8192;
+constexpr int SP_MAX_PARTS = 64;
+constexpr int SP_TARGET_WGS = 512;    // what an automatically split launch aims at (2 per compute unit: measured best)
+
 // Section offsets inside the caller's buffer.
 struct Layout {
-    size_t Bp, Bc, n_seen, n_occ, s, pos, w, Kr, Vr, Kt, Vt, total;
+    size_t Bp, Bc, n_seen, n_occ, s, pos, w, Kr, Vr, Kt, Vt, sp_L, sp_acc, sp_E, total;
+    int sp_max_units, sp_max_wgs;
 };
 
 Layout make_layout(const zsm_config_t& c) {
@@ -69,6 +78,12 @@ Layout make_layout(const zsm_config_t& c) {
     l.Vr = o; o += up256(sizeof(float) * units * Br * D);
     l.Kt = o; o += up256(esize(c.kv_dtype) * units * (cap - Br) * D);
     l.Vt = o; o += up256(esize(c.kv_dtype) * units * (cap - Br) * D);
+    l.sp_max_units = (int)(units < (size_t)SP_MAX_UNITS ? units : (size_t)SP_MAX_UNITS);
+    l.sp_max_wgs = l.sp_max_units * SP_MAX_PARTS < SP_MAX_WGS ? l.sp_max_units * SP_MAX_PARTS : SP_MAX_WGS;
+    const size_t G = c.q_per_kv;
+    l.sp_L = o; o += up256(sizeof(double) * l.sp_max_wgs * G);
+    l.sp_acc = o; o += up256(sizeof(float) * l.sp_max_wgs * G * D);
+    l.sp_E = o; o += up256(sizeof(double) * l.sp_max_units * G * (cap + 1));
     l.total = o;
     return l;
 }
@@ -108,6 +123,42 @@ __global__ __launch_bounds__(256) void stream_read_kernel(const uint4* __restric
 __global__ __launch_bounds__(256) void stream_copy_kernel(uint4* __restrict__ dst, const uint4* __restrict__ src, size_t n16) {
     const size_t stride = (size_t)gridDim.x * blockDim.x;
     for (size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x; i < n16; i += stride) dst[i] = src[i];
+}
+
+// Workgroups per unit for a decode launch of n_units units (and the token rows one part's LDS
+// must hold), or a negative status when no permitted cut fits the LDS.
+int choose_parts(const zsm_cache_t* cache, int n_units, int* part_rows) {
+    const CacheView& v = cache->cv;
+    auto lds_of = [&](int nz) {
+        switch (v.dtype) {
+            case ZSM_F32: return decode_lds_f32(v.D, v.G, nz);
+            case ZSM_F16: return decode_lds_f16(v.D, v.G, nz);
+            default: return decode_lds_bf16(v.D, v.G, nz);
+        }
+    };
+    // a launch of few units is cut into parts so that it still fills the chip
+    const int R = decode_tile_rows(v.D, (int)esize(v.dtype));
+    const int ntiles = (cache->max_btok + R - 1) / R;
+    const bool can_split = n_units <= v.sp_max_units;
+    int hi = can_split ? v.sp_max_wgs / n_units : 1;              // most parts this launch may have
+    hi = hi < SP_MAX_PARTS ? hi : SP_MAX_PARTS;
+    hi = hi < ntiles ? hi : ntiles;
+    hi = hi > 1 ? hi : 1;
+    int parts = cache->parts;
+    if (parts == 0) {
+        parts = SP_TARGET_WGS / n_units;
+        const int by_work = ntiles / (2 * DECODE_NW);             // at least two tiles per wave and part
+        parts = parts < by_work ? parts : by_work;
+    }
+    parts = parts < hi ? parts : hi;
+    parts = parts > 1 ? parts : 1;
+    auto rows_of = [&](int p) { return (ntiles + p - 1) / p * R; };
+    auto lds_need = [&](int p) { return p > 1 ? lds_of(rows_of(p) + v.Br + 1) : lds_of(v.cap + 1); };
+    if (cache->parts == 0)                                       // a capacity one workgroup's LDS cannot hold: more parts
+        while (lds_need(parts) > 160 * 1024 && parts < hi) ++parts;
+    if (lds_need(parts) > 160 * 1024) return ZSM_E_SHAPE;
+    *part_rows = parts > 1 ? rows_of(parts) : 0;
+    return parts;
 }
 
 int check_layer(const zsm_cache_t* c, int layer) {
@@ -164,6 +215,11 @@ int zsm_cache_alloc(const zsm_config_t* cfg, const int32_t* B_p, const int32_t* 
     v.Vr = reinterpret_cast<float*>(base + lay.Vr);
     v.Kt = base + lay.Kt;
     v.Vt = base + lay.Vt;
+    v.sp_max_units = lay.sp_max_units; v.sp_max_wgs = lay.sp_max_wgs;
+    v.sp_L = reinterpret_cast<double*>(base + lay.sp_L);
+    v.sp_acc = reinterpret_cast<float*>(base + lay.sp_acc);
+    v.sp_E = reinterpret_cast<double*>(base + lay.sp_E);
+    c->parts = 0;
 
     hipStream_t st = static_cast<hipStream_t>(stream);
     const size_t units = (size_t)v.L * v.S * v.H;
@@ -176,7 +232,7 @@ int zsm_cache_alloc(const zsm_config_t* cfg, const int32_t* B_p, const int32_t* 
     const size_t n_zero_words = (lay.pos - lay.n_seen) / 4;   // n_seen, n_occ, s
     hipLaunchKernelGGL(fill_i32_kernel, dim3(1024), dim3(256), 0, st, reinterpret_cast<int32_t*>(base + lay.n_seen), n_zero_words, 0);
     hipLaunchKernelGGL(fill_i32_kernel, dim3(1024), dim3(256), 0, st, v.pos, units * v.cap, -1);
-    const size_t n_rest_words = (lay.total - lay.w) / 4;      // w, Kr, Vr, Kt, Vt
+    const size_t n_rest_words = (lay.total - lay.w) / 4;      // w, Kr, Vr, Kt, Vt, split scratch
     hipLaunchKernelGGL(fill_i32_kernel, dim3(1024), dim3(256), 0, st, v.w, n_rest_words, 0);
     e = hipGetLastError();
     if (e != hipSuccess) { delete c; return hip_fail(e, "zsm_cache_alloc init"); }
@@ -197,17 +253,16 @@ int zsm_decode_step(zsm_cache_t* cache, int32_t layer_begin, int32_t layer_end, 
     if (layer_begin < 0 || layer_end > cache->cfg.n_layers || layer_begin >= layer_end) return ZSM_E_RANGE;
     if (!aligned16(q) || !aligned16(k_new) || !aligned16(v_new) || !aligned16(out)) return ZSM_E_ALIGN;
     const CacheView& v = cache->cv;
-    size_t lds;
-    switch (v.dtype) {
-        case ZSM_F32: lds = decode_lds_f32(v.D, v.G, v.cap); break;
-        case ZSM_F16: lds = decode_lds_f16(v.D, v.G, v.cap); break;
-        default: lds = decode_lds_bf16(v.D, v.G, v.cap); break;
-    }
-    if (lds > 160 * 1024) return ZSM_E_SHAPE;
+    const int n_units = (layer_end - layer_begin) * v.S * v.H;
+    int part_rows = 0;
+    const int parts = choose_parts(cache, n_units, &part_rows);
+    if (parts < 0) return parts;
     DecodeArgs a;
     a.cv = v;
     a.unit0 = layer_begin * v.S * v.H;
-    a.n_units = (layer_end - layer_begin) * v.S * v.H;
+    a.n_units = n_units;
+    a.parts = parts;
+    a.part_rows = part_rows;
     a.q = q; a.k_new = k_new; a.v_new = v_new; a.out = out;
     a.write_slot = write_slot; a.evicted_pos = evicted_pos; a.merged_slot = merged_slot;
     hipStream_t st = static_cast<hipStream_t>(stream);
@@ -219,6 +274,20 @@ int zsm_decode_step(zsm_cache_t* cache, int32_t layer_begin, int32_t layer_end, 
     }
     if (e != hipSuccess) return hip_fail(e, "zsm_decode_step launch");
     return ZSM_OK;
+}
+
+int zsm_cache_set_decode_parts(zsm_cache_t* cache, int32_t parts) {
+    if (!cache) return ZSM_E_NULL;
+    if (parts < 0 || parts > SP_MAX_PARTS) return ZSM_E_RANGE;
+    cache->parts = parts;
+    return ZSM_OK;
+}
+
+int zsm_decode_parts(const zsm_cache_t* cache, int32_t layer_begin, int32_t layer_end) {
+    if (!cache) return ZSM_E_NULL;
+    if (layer_begin < 0 || layer_end > cache->cfg.n_layers || layer_begin >= layer_end) return ZSM_E_RANGE;
+    int part_rows = 0;
+    return choose_parts(cache, (layer_end - layer_begin) * cache->cv.S * cache->cv.H, &part_rows);
 }
 
 size_t zsm_prefill_workspace_bytes(const zsm_cache_t* cache, int32_t T_max, int32_t W) {

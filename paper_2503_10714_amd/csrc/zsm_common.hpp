@@ -30,13 +30,11 @@ struct CacheView {
     float* Vr;
     void* Kt;           // [units][cap_tok][D] in kv dtype
     void* Vt;
-    // scratch of the split decode step (several workgroups per unit), indexed by the unit's
-    // number inside the launch; sp_max_units / sp_max_wgs bound the launches that may use it
+    // scratch of the split decode step (several workgroups per unit), indexed by the workgroup's
+    // or the unit's number inside the launch; sp_max_units / sp_max_wgs bound the launches that may use it
     int32_t sp_max_units, sp_max_wgs;
-    int32_t* sp_counter;   // [sp_max_units]          parts of the unit that have finished (0 between calls)
-    double* sp_L;          // [sp_max_wgs][G]         partial softmax denominators
-    float* sp_m;           // [sp_max_wgs][G]         partial maxima of logit - C
-    float* sp_acc;         // [sp_max_wgs][G][D]      partial outputs
+    double* sp_L;          // [sp_max_wgs][G]         the parts' softmax denominators
+    float* sp_acc;         // [sp_max_wgs][G][D]      the parts' outputs, each normalised by its own denominator
     double* sp_E;          // [sp_max_units][G][cap+1] exp(logit - C) of every slot
 };
 

@@ -35,6 +35,8 @@ struct DecodeArgs {
     int32_t* write_slot;
     int32_t* evicted_pos;
     int32_t* merged_slot;
+    int32_t parts;      // workgroups per unit (1: the whole unit in one workgroup)
+    int32_t part_rows;  // parts > 1: token rows the LDS of one part holds (a whole number of wave tiles)
 };
 
 template <typename T, int D, int G, int NW>
@@ -50,10 +52,10 @@ struct DecodeShape {
     static constexpr bool QLDS = G > 2;          // queries live in LDS instead of registers
     static_assert(LPR >= 1 && LPR <= 64 && 64 % LPR == 0, "row must split over a wave");
 
-    // dynamic LDS bytes for a slot capacity `cap` (same formula on host and device)
-    __host__ __device__ static size_t lds_bytes(int cap) {
+    // dynamic LDS bytes when `nz` slots (the incoming token counted) keep their exp(logit - C) in LDS
+    __host__ __device__ static size_t lds_bytes(int nz) {
         size_t n = 0;
-        n += sizeof(double) * G * (size_t)(cap + 1);   // et
+        n += sizeof(double) * G * (size_t)nz;          // et
         n += sizeof(double) * NW * PART;               // part
         n += sizeof(double) * NW * G;                  // red64
         n += sizeof(double) * (QLDS ? G * D : 0);      // qlds
@@ -103,14 +105,13 @@ __device__ __forceinline__ void tile_load(Raw<KT, EPL>* dst, const KT* __restric
 
 // Pass 1 on UU loaded wave-wide loads of K rows [row0, row0 + UU*RPL); rows >= nrows do not
 // exist.  For every existing row the holder lane stores exp(logit - C) (0 for an empty row) at
-// et[g][zidx0 + row] and adds it to lsum[g] (and, when mz is given, keeps the largest logit - C
-// in mz[g]).  posb / wb (MASKED only) mark empty rows (pos < 0, w == 0); wb also adds
+// et[g][zidx0 + row] and adds it to lsum[g].  posb / wb (MASKED only) mark empty rows (pos < 0, w == 0); wb also adds
 // alpha*log(w) to the logit (Eq. 4).
 template <typename KT, int UU, bool MASKED, int D, int G, int EPL, int LPR, int RPL, bool QLDS>
 __device__ __forceinline__ void k_compute(const Raw<KT, EPL>* kr, int row0, int nrows, int zidx0,
                                           const int32_t* __restrict__ posb, const int32_t* __restrict__ wb,
                                           double alpha, double scale, const Query<G, EPL, QLDS>& qq,
-                                          const double* C, double* lsum, float* mz, double* et, int Bz,
+                                          const double* C, double* lsum, double* et, int Bz,
                                           double* part_w, int lane) {
     constexpr int UH = UU < 4 ? UU : 4;
     const int grp = lane / LPR, seg = lane % LPR;
@@ -150,7 +151,6 @@ __device__ __forceinline__ void k_compute(const Raw<KT, EPL>* kr, int row0, int 
                     const double z = a * scale + addend;
                     ev = exp(fmin(z - C[g], 690.0));
                     lsum[g] += ev;
-                    if (mz) mz[g] = fmaxf(mz[g], (float)(z - C[g]));
                 }
                 et[(size_t)g * Bz + zidx0 + hr] = ev;
             }
@@ -165,7 +165,7 @@ template <typename KT, int UU, int D, int G, int EPL, int LPR, int RPL, bool QLD
 __device__ __forceinline__ void k_tile_masked(const KT* __restrict__ Kb, int row0, int nrows, int zidx0,
                                               const int32_t* __restrict__ posb, const int32_t* __restrict__ wb,
                                               double alpha, double scale, const Query<G, EPL, QLDS>& qq,
-                                              const double* C, double* lsum, float* mz, double* et, int Bz,
+                                              const double* C, double* lsum, double* et, int Bz,
                                               double* part_w, int lane) {
     const int grp = lane / LPR, seg = lane % LPR;
     Raw<KT, EPL> kr[UU];
@@ -177,8 +177,8 @@ __device__ __forceinline__ void k_tile_masked(const KT* __restrict__ Kb, int row
         else
             kr[u].zero();
     }
-    k_compute<KT, UU, true, D, G, EPL, LPR, RPL, QLDS>(kr, row0, nrows, zidx0, posb, wb, alpha, scale, qq, C, lsum, mz,
-                                                       et, Bz, part_w, lane);
+    k_compute<KT, UU, true, D, G, EPL, LPR, RPL, QLDS>(kr, row0, nrows, zidx0, posb, wb, alpha, scale, qq, C, lsum, et,
+                                                       Bz, part_w, lane);
 }
 
 // Pass 2 on UU loaded wave-wide loads of V rows: acc[g] += p * v with p = et * rL (fp32).
@@ -244,21 +244,74 @@ struct UnitRefs {
 
 constexpr int DECODE_MCH = 8;   // slots per thread whose score and position are requested ahead
 
+// What the end of a step reads that does not depend on its decisions.  The caller requests it
+// early (load()), so that the only memory round trip left between the eviction choice and the
+// stores is the read of the evicted row.
+template <typename T, int D, int NW, int GE = 0>
+struct FinishPre {
+    static constexpr int NT = NW * 64;
+    int pj[DECODE_MCH];      // positions and scores of slots k*NT + tid
+    float sj[DECODE_MCH];
+    double ej[GE > 0 ? DECODE_MCH : 1][GE > 0 ? GE : 1];   // GE = G: their exp(logit - C) too (values that live in global memory)
+    int wres;                // fusion count of residual slot tid (tid < B_r), else 1
+    T kn, vn;                // channel tid of the incoming token (tid < D)
+    float kr0, vr0;          // B_r = 1: channel tid of the only residual slot
+    int w0;                  // B_r = 1: its fusion count
+    __device__ __forceinline__ void load(const UnitRefs<T>& u, int cap, int Br, const double* et = nullptr, int Bz = 0) {
+        const int tid = threadIdx.x;
+        if (GE > 0) {
+#pragma unroll
+            for (int k = 0; k < DECODE_MCH; ++k) {
+                const int j = k * NT + tid;
+#pragma unroll
+                for (int g = 0; g < (GE > 0 ? GE : 1); ++g) ej[k][g] = j < cap ? et[(size_t)g * Bz + j] : 0.0;
+            }
+        }
+        // slots between the unit's B and the slot stride are empty by construction (pos = -1)
+#pragma unroll
+        for (int k = 0; k < DECODE_MCH; ++k) {
+            const int j = k * NT + tid;
+            pj[k] = j < cap ? u.pos[j] : -1;
+            sj[k] = j < cap ? u.s[j] : 0.f;
+        }
+        wres = tid < Br ? u.w[tid] : 1;
+        if (tid < D) { kn = u.knew[tid]; vn = u.vnew[tid]; }
+        w0 = 1; kr0 = 0.f; vr0 = 0.f;
+        if (Br == 1) {
+            w0 = u.w[0];
+            if (tid < D) { kr0 = u.Kr[tid]; vr0 = u.Vr[tid]; }
+        }
+    }
+};
+
 // D3-D6 of one unit, by the whole workgroup: score update (Eq. 3) from the per-slot
 // exp(logit - C) values in `et` (stride Bz per query head; LDS or global) and 1/L in rL,
 // eviction choice, residual absorption (Eq. 5, Eq. 6) and the write of the incoming token.
-// pj / sj hold the positions and scores of slots k*NT + tid, k < DECODE_MCH, loaded by the caller.
-template <typename T, int D, int G, int NW>
+// misc[0] must hold -1 and misc[2] 0x7fffffff (set before a barrier the caller has passed).
+template <typename T, int D, int G, int NW, int GE>
 __device__ __forceinline__ void decode_finish(const DecodeArgs& a, const CacheView& cv, const UnitRefs<T>& u, int lu,
                                               int ug, int Bp, int Br, int B, long long Tseen, int nocc, bool full,
-                                              const double* et, int Bz, const double* rL, int* pj, float* sj,
+                                              const double* et, int Bz, const double* rL, FinishPre<T, D, NW, GE>& pre,
                                               unsigned long long* keyw, double* dotw, int* misc) {
     constexpr int NT = NW * 64, MCH = DECODE_MCH;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     T* Kt = u.Kt; T* Vt = u.Vt;
     float* Kr = u.Kr; float* Vr = u.Vr;
     float* s = u.s; int32_t* pos = u.pos; int32_t* w = u.w;
-    const T* knew = u.knew; const T* vnew = u.vnew;
+    // the incoming token's own exp value (thread 0 needs it at the very end)
+    double e_new[G];
+    if (tid == 0) {
+#pragma unroll
+        for (int g = 0; g < G; ++g) e_new[g] = et[(size_t)g * Bz + B];
+    }
+    // lowest unused residual slot (they are opened in index order, Alg. 1) -> misc[2]
+    if (full && Br > 0) {
+        for (int r0 = 0; r0 < Br; r0 += NT) {
+            const int wv = r0 == 0 ? pre.wres : (r0 + tid < Br ? w[r0 + tid] : 1);
+            const unsigned long long m = __ballot(wv == 0);
+            if (m != 0ull && lane == 0) atomicMin(&misc[2], r0 + wave * 64 + (int)__builtin_ctzll(m));
+        }
+    }
     // ---- D3: score update (Eq. 3) and D4: eviction choice ------------------------------
     const double lam = (double)cv.lambda;
     const long long cand_hi = Tseen - Bp;   // evictable: position <= T - B_p (outside the latest B_p)
@@ -269,23 +322,24 @@ __device__ __forceinline__ void decode_finish(const DecodeArgs& a, const CacheVi
 #pragma unroll
             for (int k = 0; k < MCH; ++k) {
                 const int j = base + k * NT + tid;
-                pj[k] = j < B ? pos[j] : -1;
-                sj[k] = j < B ? s[j] : 0.f;
+                pre.pj[k] = j < B ? pos[j] : -1;
+                pre.sj[k] = j < B ? s[j] : 0.f;
             }
         }
 #pragma unroll
         for (int k = 0; k < MCH; ++k) {
             const int j = base + k * NT + tid;
             if (j >= B) continue;
-            if (pj[k] >= 0) {   // occupied (a residual slot carries the position of its first token)
+            if (pre.pj[k] >= 0) {   // occupied (a residual slot carries the position of its first token)
                 double pm = 0.0;
 #pragma unroll
-                for (int g = 0; g < G; ++g) pm += et[(size_t)g * Bz + j] * rL[g];
+                for (int g = 0; g < G; ++g)
+                    pm += ((GE > 0 && base == 0) ? pre.ej[GE > 0 ? k : 0][GE > 0 ? g : 0] : et[(size_t)g * Bz + j]) * rL[g];
                 pm /= (double)G;
-                const float sn = (float)(lam * (double)sj[k] + pm);
+                const float sn = (float)(lam * (double)pre.sj[k] + pm);
                 s[j] = sn;
-                if (full && j >= Br && (long long)pj[k] <= cand_hi) {
-                    const unsigned long long key = ((unsigned long long)__float_as_uint(sn) << 32) | (uint32_t)pj[k];
+                if (full && j >= Br && (long long)pre.pj[k] <= cand_hi) {
+                    const unsigned long long key = ((unsigned long long)__float_as_uint(sn) << 32) | (uint32_t)pre.pj[k];
                     if (key < best) { best = key; best_slot = j; }
                 }
             } else if (!full && j >= Br) {
@@ -312,63 +366,64 @@ __device__ __forceinline__ void decode_finish(const DecodeArgs& a, const CacheVi
 
     // ---- D5: absorb the evicted token into the residual set (Eq. 5, Eq. 6) ------------
     int merged = -1;
-    int r_empty = -1;
     if (full && Br > 0) {
-        for (int r = 0; r < Br; ++r)
-            if (w[r] == 0) { r_empty = r; break; }
-    }
-    __syncthreads();   // every thread has taken its view of w before anyone changes it
-    if (full && Br > 0) {
+        const int r_empty = misc[2] < Br ? misc[2] : -1;
+        float ke = 0.f, ve = 0.f;   // channel tid of the evicted token
+        if (tid < D) {
+            ke = to_float(Kt[(size_t)ct * D + tid]);
+            ve = to_float(Vt[(size_t)ct * D + tid]);
+        }
         if (r_empty >= 0) {
-            if (tid < D) {
-                Kr[r_empty * D + tid] = to_float(Kt[(size_t)ct * D + tid]);
-                Vr[r_empty * D + tid] = to_float(Vt[(size_t)ct * D + tid]);
-            }
+            if (tid < D) { Kr[r_empty * D + tid] = ke; Vr[r_empty * D + tid] = ve; }
             if (tid == 0) { w[r_empty] = 1; pos[r_empty] = ev_pos; s[r_empty] = ev_s; }
             merged = r_empty;
         } else {
-            double bd = -INFINITY;
-            int br = 0x7fffffff;
-            for (int r = wave; r < Br; r += NW) {
-                double p = 0.0;
-                for (int ch = lane; ch < D; ch += 64)
-                    p = fma((double)Kr[r * D + ch], (double)to_float(Kt[(size_t)ct * D + ch]), p);
-                p = wave_sum(p);
-                if (p > bd) { bd = p; br = r; }
-            }
-            if (lane == 0) { dotw[wave] = bd; misc[4 + wave] = br; }
-            __syncthreads();
-            bd = -INFINITY; br = 0x7fffffff;
+            int br = 0, wv = pre.w0;
+            float k0 = pre.kr0, v0 = pre.vr0;
+            if (Br > 1) {
+                // Eq. 5: the residual key with the largest dot product, lowest index on ties
+                double bd = -INFINITY;
+                br = 0x7fffffff;
+                for (int r = wave; r < Br; r += NW) {
+                    double p = 0.0;
+                    for (int ch = lane; ch < D; ch += 64)
+                        p = fma((double)Kr[r * D + ch], (double)to_float(Kt[(size_t)ct * D + ch]), p);
+                    p = wave_sum(p);
+                    if (p > bd) { bd = p; br = r; }
+                }
+                if (lane == 0) { dotw[wave] = bd; misc[4 + wave] = br; }
+                __syncthreads();
+                bd = -INFINITY; br = 0x7fffffff;
 #pragma unroll
-            for (int x = 0; x < NW; ++x) {
-                const double dx = dotw[x];
-                const int rx = misc[4 + x];
-                if (rx != 0x7fffffff && (br == 0x7fffffff || dx > bd || (dx == bd && rx < br))) { bd = dx; br = rx; }
+                for (int x = 0; x < NW; ++x) {
+                    const double dx = dotw[x];
+                    const int rx = misc[4 + x];
+                    if (rx != 0x7fffffff && (br == 0x7fffffff || dx > bd || (dx == bd && rx < br))) { bd = dx; br = rx; }
+                }
+                wv = w[br];
+                if (tid < D) { k0 = Kr[br * D + tid]; v0 = Vr[br * D + tid]; }
+                __syncthreads();   // every thread has read w[br] before thread 0 changes it
             }
             merged = br;
-            const int wv = w[br];
             if (tid < D) {
                 const double wd = (double)wv;
-                const double ke = (double)to_float(Kt[(size_t)ct * D + tid]);
-                const double ve = (double)to_float(Vt[(size_t)ct * D + tid]);
-                Kr[br * D + tid] = (float)((wd * (double)Kr[br * D + tid] + ke) / (wd + 1.0));
-                Vr[br * D + tid] = (float)((wd * (double)Vr[br * D + tid] + ve) / (wd + 1.0));
+                Kr[br * D + tid] = (float)((wd * (double)k0 + (double)ke) / (wd + 1.0));
+                Vr[br * D + tid] = (float)((wd * (double)v0 + (double)ve) / (wd + 1.0));
             }
-            __syncthreads();
             if (tid == 0) w[br] = wv + 1;
         }
+        __syncthreads();   // the evicted row has been read by everyone who needs it
     }
-    __syncthreads();   // the evicted row has been read by everyone who needs it
 
     // ---- D6: the incoming token takes the freed slot ----------------------------------
     if (tid < D) {
-        Kt[(size_t)ct * D + tid] = knew[tid];
-        Vt[(size_t)ct * D + tid] = vnew[tid];
+        Kt[(size_t)ct * D + tid] = pre.kn;
+        Vt[(size_t)ct * D + tid] = pre.vn;
     }
     if (tid == 0) {
         double pm = 0.0;
 #pragma unroll
-        for (int g = 0; g < G; ++g) pm += et[(size_t)g * Bz + B] * rL[g];
+        for (int g = 0; g < G; ++g) pm += e_new[g] * rL[g];
         pm /= (double)G;
         pos[c] = (int32_t)Tseen;
         w[c] = 1;
@@ -384,13 +439,23 @@ __device__ __forceinline__ void decode_finish(const DecodeArgs& a, const CacheVi
 // Occupancy target: 4 waves per SIMD for G = 1 (four workgroups per compute unit, LDS permitting);
 // the per-head state of grouped queries needs more registers and its LDS footprint caps the
 // residency anyway.
-template <typename T, int D, int G, int NW>
+//
+// SPLIT = false: one workgroup per unit does everything.
+// SPLIT = true: a.parts workgroups per unit.  Part p sweeps a contiguous range of the token
+//   slots' wave tiles (part 0 also takes the residual slots and the incoming token), normalises
+//   by its own denominator L_p and leaves L_p, its output share and the exp(logit - C) of its
+//   slots in the cache's scratch area; C is the same for every part, so no maxima are exchanged.
+//   decode_combine_kernel, launched behind it, finishes every unit from there (the kernel
+//   boundary is what makes one workgroup's scratch visible to another: fences inside one
+//   kernel cost more here than the whole sweep of a small launch).
+template <typename T, int D, int G, int NW, bool SPLIT>
 __global__ __launch_bounds__(NW * 64, (G == 1 ? 4 : 2)) void decode_kernel(DecodeArgs a) {
     using Sh = DecodeShape<T, D, G, NW>;
     constexpr int EPL = Sh::EPL, LPR = Sh::LPR, RPL = Sh::RPL, R = Sh::R, PART = Sh::PART, NT = Sh::NT, UT = Sh::UT;
     constexpr bool QLDS = Sh::QLDS;
     const CacheView& cv = a.cv;
-    const int lu = blockIdx.x;
+    const int lu = SPLIT ? (int)blockIdx.x / a.parts : (int)blockIdx.x;
+    const int part = SPLIT ? (int)blockIdx.x % a.parts : 0;
     const int ug = a.unit0 + lu;
     const int b = (ug / cv.H) % cv.S;
     const int Bp = cv.Bp[b], Bc = cv.Bc[b], Br = cv.Br;
@@ -398,11 +463,24 @@ __global__ __launch_bounds__(NW * 64, (G == 1 ? 4 : 2)) void decode_kernel(Decod
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int grp = lane / LPR, seg = lane % LPR;
 
+    // this workgroup's wave tiles [tb, te) = token rows [row_b, row_e)
+    const int ntiles = (ntok + R - 1) / R;
+    int tb = 0, te = ntiles;
+    if (SPLIT) {
+        const int tpp = (ntiles + a.parts - 1) / a.parts;
+        tb = part * tpp < ntiles ? part * tpp : ntiles;
+        te = tb + tpp < ntiles ? tb + tpp : ntiles;
+    }
+    const int row_b = tb * R, row_e = te * R < ntok ? te * R : ntok;
+    // LDS index of a slot's exp value: residual slot r -> r, token row x -> zt + x, incoming token -> znew
+    const int Bz = SPLIT ? a.part_rows + Br + 1 : cv.cap + 1;
+    const int zt = Br - row_b;
+    const int znew = Br + (row_e - row_b);   // used where row_b = 0 and row_e = ntok (SPLIT: part 0 only, any row_e)
+
     extern __shared__ __align__(16) unsigned char smem[];
-    const int Bz = cv.cap + 1;
     double* et = reinterpret_cast<double*>(smem);                 // [G][Bz] exp(logit - C) per slot
-    double* part = et + (size_t)G * Bz;                           // [NW][PART]
-    double* red64 = part + NW * PART;                             // [NW][G]
+    double* part_s = et + (size_t)G * Bz;                         // [NW][PART]
+    double* red64 = part_s + NW * PART;                           // [NW][G]
     double* qlds = red64 + NW * G;                                // [G][D] (QLDS only)
     unsigned long long* keyw = reinterpret_cast<unsigned long long*>(qlds + (QLDS ? G * D : 0));   // [NW]
     double* dotw = reinterpret_cast<double*>(keyw + NW);          // [NW]
@@ -416,6 +494,11 @@ __global__ __launch_bounds__(NW * 64, (G == 1 ? 4 : 2)) void decode_kernel(Decod
     float* s = cv.s + (size_t)ug * cv.cap;
     int32_t* pos = cv.pos + (size_t)ug * cv.cap;
     int32_t* w = cv.w + (size_t)ug * cv.cap;
+    // The wave's first K tile is requested before anything else when its rows are known without
+    // the budgets (one workgroup per unit: tile `wave`); rows past the unit's budget exist up to
+    // the slot stride and are discarded by the compute step.
+    Raw<T, EPL> bufA[UT], bufB[UT];
+    if (!SPLIT) tile_load<T, UT, D, EPL, LPR, RPL>(bufA, Kt, wave * R, cv.cap_tok, lane);
     const T* qp = reinterpret_cast<const T*>(a.q) + (size_t)lu * G * D;
     const T* knew = reinterpret_cast<const T*>(a.k_new) + (size_t)lu * D;
     const T* vnew = reinterpret_cast<const T*>(a.v_new) + (size_t)lu * D;
@@ -425,7 +508,7 @@ __global__ __launch_bounds__(NW * 64, (G == 1 ? 4 : 2)) void decode_kernel(Decod
     const double scale = cv.scale;
     const double alpha = (double)cv.alpha;
 
-    if (tid == 0) misc[0] = -1;
+    if (tid == 0) { misc[0] = -1; misc[2] = 0x7fffffff; }
     Query<G, EPL, QLDS> qq;
     qq.lds = qlds;
     if (QLDS) {
@@ -458,93 +541,89 @@ __global__ __launch_bounds__(NW * 64, (G == 1 ? 4 : 2)) void decode_kernel(Decod
             lsum[g] = 0.0;
         }
     }
-    double* part_w = part + wave * PART;
+    double* part_w = part_s + wave * PART;
 
-    // ---- pass 1 (D1): logits of all slots, exp(logit - C) into LDS ---------------------
+    // ---- pass 1 (D1): logits of this workgroup's slots, exp(logit - C) into LDS ---------
     // Fast path (every token slot occupied): tiles are double-buffered in registers, the loads
     // of the wave's next tile (or of its first V tile) are in flight while it works on this one.
-    const int ntiles = (ntok + R - 1) / R;
-    Raw<T, EPL> bufA[UT], bufB[UT];
     if (full) {
-        int t = wave;
-        if (t < ntiles) tile_load<T, UT, D, EPL, LPR, RPL>(bufA, Kt, t * R, ntok, lane);
-        while (t < ntiles) {
+        int t = tb + wave;
+        if (SPLIT && t < te) tile_load<T, UT, D, EPL, LPR, RPL>(bufA, Kt, t * R, ntok, lane);
+        while (t < te) {
             const int tn = t + NW;
-            prio_from_progress(t, 2 * ntiles);
-            if (tn < ntiles) tile_load<T, UT, D, EPL, LPR, RPL>(bufB, Kt, tn * R, ntok, lane);
-            else tile_load<T, UT, D, EPL, LPR, RPL>(bufB, Vt, wave * R, ntok, lane);   // wave < ntiles here
-            k_compute<T, UT, false, D, G, EPL, LPR, RPL, QLDS>(bufA, t * R, ntok, Br, nullptr, nullptr, alpha, scale, qq,
-                                                               C, lsum, nullptr, et, Bz, part_w, lane);
+            prio_from_progress(t - tb, 2 * (te - tb));
+            if (tn < te) tile_load<T, UT, D, EPL, LPR, RPL>(bufB, Kt, tn * R, ntok, lane);
+            else tile_load<T, UT, D, EPL, LPR, RPL>(bufB, Vt, (tb + wave) * R, ntok, lane);   // tb + wave < te here
+            k_compute<T, UT, false, D, G, EPL, LPR, RPL, QLDS>(bufA, t * R, row_e, zt, nullptr, nullptr, alpha, scale, qq,
+                                                               C, lsum, et, Bz, part_w, lane);
 #pragma unroll
             for (int u = 0; u < UT; ++u) bufA[u] = bufB[u];
             t = tn;
         }
     } else {
-        for (int t = wave; t * RPL < ntok; t += NW)
-            k_tile_masked<T, 1, D, G, EPL, LPR, RPL, QLDS>(Kt, t * RPL, ntok, Br, pos + Br, nullptr, alpha, scale, qq, C,
-                                                           lsum, nullptr, et, Bz, part_w, lane);
+        for (int r0 = row_b + wave * RPL; r0 < row_e; r0 += NW * RPL)
+            k_tile_masked<T, 1, D, G, EPL, LPR, RPL, QLDS>(Kt, r0, row_e, zt, pos + Br, nullptr, alpha, scale, qq, C, lsum,
+                                                           et, Bz, part_w, lane);
     }
     // residual slots (fp32 rows, log-count term) and the incoming token itself
-    for (int t = wave; t * RPL < Br; t += NW)
-        k_tile_masked<float, 1, D, G, EPL, LPR, RPL, QLDS>(Kr, t * RPL, Br, 0, nullptr, w, alpha, scale, qq, C, lsum,
-                                                           nullptr, et, Bz, part_w, lane);
-    if (wave == NW - 1)
-        k_tile_masked<T, 1, D, G, EPL, LPR, RPL, QLDS>(knew, 0, 1, B, nullptr, nullptr, alpha, scale, qq, C, lsum, nullptr,
-                                                       et, Bz, part_w, lane);
+    if (part == 0) {
+        for (int t = wave; t * RPL < Br; t += NW)
+            k_tile_masked<float, 1, D, G, EPL, LPR, RPL, QLDS>(Kr, t * RPL, Br, 0, nullptr, w, alpha, scale, qq, C, lsum,
+                                                               et, Bz, part_w, lane);
+        if (wave == NW - 1)
+            k_tile_masked<T, 1, D, G, EPL, LPR, RPL, QLDS>(knew, 0, 1, znew, nullptr, nullptr, alpha, scale, qq, C, lsum,
+                                                           et, Bz, part_w, lane);
+    }
 #pragma unroll
     for (int g = 0; g < G; ++g) {
         const double t = wave_sum(lsum[g]);
         if (lane == 0) red64[wave * G + g] = t;
     }
     __syncthreads();
-    double rL[G];
+    double rL[G];   // 1 / (this workgroup's softmax denominator)
 #pragma unroll
     for (int g = 0; g < G; ++g) {
         double t = 0.0;
 #pragma unroll
         for (int x = 0; x < NW; ++x) t += red64[x * G + g];
-        rL[g] = 1.0 / t;
+        rL[g] = SPLIT ? (t > 0.0 ? 1.0 / t : 0.0) : 1.0 / t;   // the unit's own denominator counts the incoming token: >= 1
     }
 
-    // ---- pass 2 (D2): out = sum p * v --------------------------------------------------
+    // ---- pass 2 (D2): sum p * v over this workgroup's slots ------------------------------
     float acc[G][EPL];
 #pragma unroll
     for (int g = 0; g < G; ++g)
 #pragma unroll
         for (int e = 0; e < EPL; ++e) acc[g][e] = 0.f;
     if (full) {
-        int t = wave;   // bufA already holds this wave's first V tile
-        while (t < ntiles) {
+        int t = tb + wave;   // bufA already holds this wave's first V tile
+        while (t < te) {
             const int tn = t + NW;
-            prio_from_progress(ntiles + t, 2 * ntiles);
-            if (tn < ntiles) tile_load<T, UT, D, EPL, LPR, RPL>(bufB, Vt, tn * R, ntok, lane);
-            v_compute<T, UT, D, G, EPL, LPR, RPL>(bufA, t * R, ntok, Br, rL, acc, et, Bz, lane);
+            prio_from_progress(te - tb + t - tb, 2 * (te - tb));
+            if (tn < te) tile_load<T, UT, D, EPL, LPR, RPL>(bufB, Vt, tn * R, ntok, lane);
+            v_compute<T, UT, D, G, EPL, LPR, RPL>(bufA, t * R, row_e, zt, rL, acc, et, Bz, lane);
 #pragma unroll
             for (int u = 0; u < UT; ++u) bufA[u] = bufB[u];
             t = tn;
         }
     } else {
-        for (int t = wave; t * RPL < ntok; t += NW)
-            v_tile_masked<T, 1, D, G, EPL, LPR, RPL>(Vt, t * RPL, ntok, Br, rL, acc, et, Bz, lane);
+        for (int r0 = row_b + wave * RPL; r0 < row_e; r0 += NW * RPL)
+            v_tile_masked<T, 1, D, G, EPL, LPR, RPL>(Vt, r0, row_e, zt, rL, acc, et, Bz, lane);
     }
     __builtin_amdgcn_s_setprio(0);
-    for (int t = wave; t * RPL < Br; t += NW)
-        v_tile_masked<float, 1, D, G, EPL, LPR, RPL>(Vr, t * RPL, Br, 0, rL, acc, et, Bz, lane);
-    if (wave == NW - 1)
-        v_tile_masked<T, 1, D, G, EPL, LPR, RPL>(vnew, 0, 1, B, rL, acc, et, Bz, lane);
-
-    // Scores and positions of this thread's first batch of slots: requested now, used after the
-    // output has been combined, so that their latency is hidden.
-    constexpr int MCH = DECODE_MCH;
-    int pj[MCH];
-    float sj[MCH];
-#pragma unroll
-    for (int k = 0; k < MCH; ++k) {
-        const int j = k * NT + tid;
-        pj[k] = j < B ? pos[j] : -1;
-        sj[k] = j < B ? s[j] : 0.f;
+    if (part == 0) {
+        for (int t = wave; t * RPL < Br; t += NW)
+            v_tile_masked<float, 1, D, G, EPL, LPR, RPL>(Vr, t * RPL, Br, 0, rL, acc, et, Bz, lane);
+        if (wave == NW - 1)
+            v_tile_masked<T, 1, D, G, EPL, LPR, RPL>(vnew, 0, 1, znew, rL, acc, et, Bz, lane);
     }
-    // ---- combine the waves' partial outputs -> out -------------------------------------
+
+    // What the end of the step reads regardless of its decisions: requested now, used after the
+    // output has been combined, so that the latency is hidden.
+    UnitRefs<T> u{Kt, Vt, Kr, Vr, s, pos, w, knew, vnew};
+    FinishPre<T, D, NW> pre;
+    if (!SPLIT) pre.load(u, cv.cap, Br);
+    // ---- combine the waves' partial outputs ----------------------------------------------
 #pragma unroll
     for (int g = 0; g < G; ++g) {
 #pragma unroll
@@ -556,25 +635,136 @@ __global__ __launch_bounds__(NW * 64, (G == 1 ? 4 : 2)) void decode_kernel(Decod
         }
     }
     __syncthreads();
+    if (!SPLIT) {
+        for (int idx = tid; idx < G * D; idx += NT) {
+            float o = 0.f;
+#pragma unroll
+            for (int x = 0; x < NW; ++x) o += accw[x * G * D + idx];
+            a.out[(size_t)lu * G * D + idx] = o;
+        }
+        decode_finish<T, D, G, NW, 0>(a, cv, u, lu, ug, Bp, Br, B, Tseen, nocc, full, et, Bz, rL, pre, keyw, dotw, misc);
+        return;
+    }
+
+    // ---- SPLIT: leave this part's share in scratch for decode_combine_kernel
+    const int wg = blockIdx.x;
+    const int BzG = cv.cap + 1;
+    double* Eu = cv.sp_E + (size_t)lu * G * BzG;   // [G][cap + 1], indexed by slot (incoming token at B)
     for (int idx = tid; idx < G * D; idx += NT) {
         float o = 0.f;
 #pragma unroll
         for (int x = 0; x < NW; ++x) o += accw[x * G * D + idx];
-        a.out[(size_t)lu * G * D + idx] = o;
+        cv.sp_acc[(size_t)wg * G * D + idx] = o;
     }
-
-    UnitRefs<T> u{Kt, Vt, Kr, Vr, s, pos, w, knew, vnew};
-    decode_finish<T, D, G, NW>(a, cv, u, lu, ug, Bp, Br, B, Tseen, nocc, full, et, Bz, rL, pj, sj, keyw, dotw, misc);
+    if (tid < G) {
+        double t = 0.0;
+#pragma unroll
+        for (int x = 0; x < NW; ++x) t += red64[x * G + tid];
+        cv.sp_L[(size_t)wg * G + tid] = t;
+    }
+    for (int g = 0; g < G; ++g) {
+        for (int i = tid; i < row_e - row_b; i += NT) Eu[(size_t)g * BzG + Br + row_b + i] = et[(size_t)g * Bz + Br + i];
+        if (part == 0) {
+            for (int i = tid; i < Br; i += NT) Eu[(size_t)g * BzG + i] = et[(size_t)g * Bz + i];
+            if (tid == 0) Eu[(size_t)g * BzG + B] = et[(size_t)g * Bz + znew];
+        }
+    }
 }
 
-// Host side: pick the instantiation for (D, G) and launch one workgroup per unit.
+// Second kernel of a split step, one workgroup per unit: adds the parts' output shares up with
+// weights L_p / L, writes the output and runs the score update, eviction, merge and token write
+// from the per-slot values the parts left in scratch.  Latency-bound (a few dependent memory
+// round trips), so everything whose address is known up front is requested up front.
+template <typename T, int D, int G, int NW>
+__global__ __launch_bounds__(NW * 64) void decode_combine_kernel(DecodeArgs a) {
+    constexpr int NT = NW * 64;
+    constexpr int MAXP = 64;   // parts per unit (the host never asks for more)
+    const CacheView& cv = a.cv;
+    const int lu = blockIdx.x;
+    const int ug = a.unit0 + lu;
+    const int b = (ug / cv.H) % cv.S;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int Br = cv.Br, P = a.parts;
+    __shared__ unsigned long long keyw[NW];
+    __shared__ double dotw[NW];
+    __shared__ int misc[4 + NW];
+    __shared__ double Lp[MAXP][G];
+    __shared__ double Lsum[G];
+    T* Kt = reinterpret_cast<T*>(cv.Kt) + (size_t)ug * cv.cap_tok * D;
+    T* Vt = reinterpret_cast<T*>(cv.Vt) + (size_t)ug * cv.cap_tok * D;
+    UnitRefs<T> u{Kt, Vt, cv.Kr + (size_t)ug * Br * D, cv.Vr + (size_t)ug * Br * D, cv.s + (size_t)ug * cv.cap,
+                  cv.pos + (size_t)ug * cv.cap, cv.w + (size_t)ug * cv.cap,
+                  reinterpret_cast<const T*>(a.k_new) + (size_t)lu * D, reinterpret_cast<const T*>(a.v_new) + (size_t)lu * D};
+    const int BzG = cv.cap + 1;
+    const double* Eu = cv.sp_E + (size_t)lu * G * BzG;
+    FinishPre<T, D, NW, G> pre;
+    pre.load(u, cv.cap, Br, Eu, BzG);
+    const int wg0 = lu * P;
+    // the parts' denominators: wave 0, lane p
+    double lp[G];
+#pragma unroll
+    for (int g = 0; g < G; ++g) lp[g] = (wave == 0 && lane < P) ? cv.sp_L[(size_t)(wg0 + lane) * G + g] : 0.0;
+    // the first parts' output shares of this thread's first channel (the rest after the barrier)
+    constexpr int OPT = (G * D + NT - 1) / NT;   // outputs per thread
+    constexpr int PPRE = 16;
+    float vpre[PPRE];
+#pragma unroll
+    for (int p = 0; p < PPRE; ++p) vpre[p] = (p < P && tid < G * D) ? cv.sp_acc[(size_t)(wg0 + p) * G * D + tid] : 0.f;
+    const int Bp = cv.Bp[b], Bc = cv.Bc[b];
+    const int ntok = Bp + Bc, B = ntok + Br;
+    const long long Tseen = cv.n_seen[ug];
+    const int nocc = cv.n_occ[ug];
+    const bool full = nocc == ntok;
+    if (tid == 0) { misc[0] = -1; misc[2] = 0x7fffffff; }
+    if (wave == 0) {
+#pragma unroll
+        for (int g = 0; g < G; ++g) {
+            if (lane < P) Lp[lane][g] = lp[g];
+            const double t = wave_sum(lp[g]);
+            if (lane == 0) Lsum[g] = t;
+        }
+    }
+    __syncthreads();
+    double rL[G];
+#pragma unroll
+    for (int g = 0; g < G; ++g) rL[g] = 1.0 / Lsum[g];   // part 0 counted the incoming token: the sum is >= 1
+#pragma unroll
+    for (int x = 0; x < OPT; ++x) {
+        const int idx = x * NT + tid;
+        if (idx >= G * D) break;
+        const int g = idx / D;
+        double rl = 0.0;
+#pragma unroll
+        for (int gg = 0; gg < G; ++gg) rl = gg == g ? rL[gg] : rl;
+        float o = 0.f;
+        int p = 0;
+        if (x == 0) {
+#pragma unroll
+            for (int y = 0; y < PPRE; ++y)
+                if (y < P) o = fmaf((float)(Lp[y][g] * rl), vpre[y], o);
+            p = P < PPRE ? P : PPRE;
+        }
+        for (; p + 4 <= P; p += 4) {
+            float v[4];
+#pragma unroll
+            for (int y = 0; y < 4; ++y) v[y] = cv.sp_acc[(size_t)(wg0 + p + y) * G * D + idx];
+#pragma unroll
+            for (int y = 0; y < 4; ++y) o = fmaf((float)(Lp[p + y][g] * rl), v[y], o);
+        }
+        for (; p < P; ++p) o = fmaf((float)(Lp[p][g] * rl), cv.sp_acc[(size_t)(wg0 + p) * G * D + idx], o);
+        a.out[(size_t)lu * G * D + idx] = o;
+    }
+    decode_finish<T, D, G, NW, G>(a, cv, u, lu, ug, Bp, Br, B, Tseen, nocc, full, Eu, BzG, rL, pre, keyw, dotw, misc);
+}
+
+// Host side: pick the instantiation for (D, G) and launch.
 constexpr int DECODE_NW = 4;
 
-template <typename T, int D, int G>
-inline hipError_t launch_decode_dg(const DecodeArgs& a, hipStream_t stream) {
+template <typename T, int D, int G, bool SPLIT>
+inline hipError_t launch_decode_dgs(const DecodeArgs& a, hipStream_t stream) {
     using Sh = DecodeShape<T, D, G, DECODE_NW>;
-    const size_t lds = Sh::lds_bytes(a.cv.cap);
-    auto kern = decode_kernel<T, D, G, DECODE_NW>;
+    const size_t lds = Sh::lds_bytes(SPLIT ? a.part_rows + a.cv.Br + 1 : a.cv.cap + 1);
+    auto kern = decode_kernel<T, D, G, DECODE_NW, SPLIT>;
     static bool attr_set = false;
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
@@ -582,12 +772,21 @@ inline hipError_t launch_decode_dg(const DecodeArgs& a, hipStream_t stream) {
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    hipLaunchKernelGGL(kern, dim3(a.n_units), dim3(DECODE_NW * 64), lds, stream, a);
+    hipLaunchKernelGGL(kern, dim3(a.n_units * (SPLIT ? a.parts : 1)), dim3(DECODE_NW * 64), lds, stream, a);
+    if (SPLIT) hipLaunchKernelGGL((decode_combine_kernel<T, D, G, DECODE_NW>), dim3(a.n_units), dim3(DECODE_NW * 64), 0, stream, a);
     return hipGetLastError();
 }
 
 template <typename T, int D, int G>
-inline size_t decode_lds_dg(int cap) { return DecodeShape<T, D, G, DECODE_NW>::lds_bytes(cap); }
+inline hipError_t launch_decode_dg(const DecodeArgs& a, hipStream_t stream) {
+    return a.parts > 1 ? launch_decode_dgs<T, D, G, true>(a, stream) : launch_decode_dgs<T, D, G, false>(a, stream);
+}
+
+template <typename T, int D, int G>
+inline size_t decode_lds_dg(int nz) { return DecodeShape<T, D, G, DECODE_NW>::lds_bytes(nz); }
+
+// rows of one wave tile for a K/V element size (the unit the parts of a split step are cut in)
+inline int decode_tile_rows(int D, int esize) { return DecodeShape<float, 64, 1, DECODE_NW>::UT * (64 / (D * esize / 16)); }
 
 template <typename T>
 inline hipError_t launch_decode_t(const DecodeArgs& a, hipStream_t stream) {
@@ -599,9 +798,10 @@ inline hipError_t launch_decode_t(const DecodeArgs& a, hipStream_t stream) {
     return hipErrorInvalidValue;
 }
 
+// LDS bytes of a launch that keeps `nz` per-slot values per query head in LDS
 template <typename T>
-inline size_t decode_lds_t(int D, int G, int cap) {
-#define ZSM_CASE(DD, GG) if (D == DD && G == GG) return decode_lds_dg<T, DD, GG>(cap);
+inline size_t decode_lds_t(int D, int G, int nz) {
+#define ZSM_CASE(DD, GG) if (D == DD && G == GG) return decode_lds_dg<T, DD, GG>(nz);
     ZSM_CASE(64, 1) ZSM_CASE(64, 2) ZSM_CASE(64, 4) ZSM_CASE(64, 8)
     ZSM_CASE(128, 1) ZSM_CASE(128, 2) ZSM_CASE(128, 4) ZSM_CASE(128, 8)
 #undef ZSM_CASE
@@ -612,8 +812,8 @@ inline size_t decode_lds_t(int D, int G, int cap) {
 hipError_t launch_decode_f32(const DecodeArgs& a, hipStream_t stream);
 hipError_t launch_decode_f16(const DecodeArgs& a, hipStream_t stream);
 hipError_t launch_decode_bf16(const DecodeArgs& a, hipStream_t stream);
-size_t decode_lds_f32(int D, int G, int cap);
-size_t decode_lds_f16(int D, int G, int cap);
-size_t decode_lds_bf16(int D, int G, int cap);
+size_t decode_lds_f32(int D, int G, int nz);
+size_t decode_lds_f16(int D, int G, int nz);
+size_t decode_lds_bf16(int D, int G, int nz);
 
 }  // namespace zsm

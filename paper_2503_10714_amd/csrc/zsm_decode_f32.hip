@@ -3,5 +3,5 @@
 
 namespace zsm {
 hipError_t launch_decode_f32(const DecodeArgs& a, hipStream_t stream) { return launch_decode_t<float>(a, stream); }
-size_t decode_lds_f32(int D, int G, int cap) { return decode_lds_t<float>(D, G, cap); }
+size_t decode_lds_f32(int D, int G, int nz) { return decode_lds_t<float>(D, G, nz); }
 }  // namespace zsm

@@ -182,17 +182,18 @@ def make_cache(wl: synth.Workload, device="cuda:0"):
 
 def run_decode_parity(wl: synth.Workload, cache, units_by_layer: List[List[List[UnitCache]]], n_steps: int,
                       sel: Optional[Sequence[Tuple[int, int, int]]] = None, gen_device="cpu",
-                      state_every: int = 0) -> StepStats:
+                      state_every: int = 0, first_step: int = 0) -> StepStats:
     """Lock-step decode of GPU cache and oracle units; all layers per launch.
 
     sel: (layer, b, h) triples to check (default: all).  state_every: also compare the
-    whole exported state every that many steps (0 = only at the end)."""
+    whole exported state every that many steps (0 = only at the end).  first_step: number of the
+    first decode step (its inputs are a function of the step number)."""
     L, S, H, G, d = wl.n_layers, wl.n_seqs, wl.n_kv_heads, wl.q_per_kv, wl.head_dim
     tol = tol_for(wl.dtype)
     stats = StepStats()
     triples = sel if sel is not None else [(l, b, h) for l in range(L) for b in range(S) for h in range(H)]
     dev = cache.device
-    for step in range(n_steps):
+    for step in range(first_step, first_step + n_steps):
         qs, ks, vs = [], [], []
         for l in range(L):
             q, k, v = synth.decode_inputs(wl, l, step, device=gen_device)
@@ -212,7 +213,7 @@ def run_decode_parity(wl: synth.Workload, cache, units_by_layer: List[List[List[
             assert sel is None, "a near tie in a sampled run cannot be re-synchronised"
             cache.import_layer(l, **pack_states(units_by_layer[l], cache.cap, cache.B_r, d, cache.kv_dtype))
         stats.steps += 1
-        if state_every and (step + 1) % state_every == 0 and step + 1 < n_steps:
+        if state_every and (step + 1) % state_every == 0 and step + 1 < first_step + n_steps:
             compare_all_state(wl, cache, units_by_layer, tol, f"after step {step}", sel)
     compare_all_state(wl, cache, units_by_layer, tol, "final", sel, stats)
     return stats

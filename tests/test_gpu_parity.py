@@ -66,6 +66,52 @@ def test_decode_from_oracle_state(case):
     cache.close()
 
 
+# (case, workgroups per unit): the split step must give the oracle's decisions and outputs whatever the cut
+SPLIT_CASES = [("cfg1", 4), ("cfg1", 13), ("three_residual_f16", 2), ("alpha_half_bf16_gqa4", 3), ("gqa8_f32_d128", 2),
+               ("fills_up", 2), ("empty_start", 3), ("ragged_multi_layer", 5), ("evict_only", 3), ("cfg0", 3)]
+
+
+@pytest.mark.parametrize("case,parts", SPLIT_CASES)
+def test_decode_split_over_workgroups(case, parts):
+    """Decode step cut into several workgroups per unit (partial softmax sums and outputs meet in
+    the cache's scratch area): same parity bar as the one-workgroup step."""
+    wl = DECODE_CASES[case]()
+    print(f"[case] split {case} parts={parts} units={wl.n_units} B={wl.slot_capacity} steps={wl.decode_steps}", flush=True)
+    units = oracle_states(wl)
+    cache = pu.make_cache(wl, DEV)
+    cache.set_decode_parts(parts)
+    used = cache.decode_parts()
+    assert used > 1, f"the launch was not split (parts={used})"
+    for l in range(wl.n_layers):
+        cache.import_layer(l, **pu.pack_states(units[l], cache.cap, cache.B_r, wl.head_dim, cache.kv_dtype))
+    st = pu.run_decode_parity(wl, cache, units, wl.decode_steps, state_every=16)
+    print(f"[done] split {case}: parts used {used} unit-steps={st.unit_steps} evictions={st.evictions} near_ties={st.near_ties} "
+          f"max|out err|={st.max_out_err:.2e} scores bit-equal {st.s_bit_equal}/{st.s_total}", flush=True)
+    assert st.near_ties == 0 or st.near_ties < 0.01 * st.unit_steps
+    cache.close()
+
+
+def test_decode_parts_choice():
+    """Host-side choice of the cut: many units -> one workgroup each; few units -> about 512 workgroups;
+    a capacity that one workgroup's LDS cannot hold -> split where the launch is small, refused otherwise."""
+    from paper_2503_10714_amd import binding as zb
+    c = zb.Cache(32, 1, 32, 1, 128, 1350, 1349, 1, "f16", device=DEV)
+    assert c.decode_parts(0, 32) == 1            # 1024 units
+    assert c.decode_parts(0, 1) == 16            # 32 units
+    assert c.decode_parts(0, 8) == 2             # 256 units
+    assert c.decode_parts(0, 16) == 1            # 512 units
+    c.set_decode_parts(1)
+    assert c.decode_parts(0, 1) == 1
+    c.set_decode_parts(64)
+    assert c.decode_parts(0, 1) == 64 and c.decode_parts(0, 8) == 32 and c.decode_parts(0, 32) == 8
+    with pytest.raises(zb.ZsmError):
+        c.set_decode_parts(65)
+    c.close()
+    big = zb.Cache(1, 1, 1, 8, 128, 2000, 2000, 1, "f16", device=DEV)
+    assert big.decode_parts() == 31              # one unit: cut for parallelism (4001 slots x 8 heads x 8 bytes would not fit one LDS anyway)
+    big.close()
+
+
 PREFILL_CASES = {
     "cfg0": lambda: synth.workload(0),
     "cfg1": lambda: synth.workload(1),
@@ -123,19 +169,29 @@ FULL_CASES = {
     # the paper's recommended residual share (dense ratio 0.02 of B - B_p: 27 slots at B = 2700) on workload 2's shape
     "cfg2_slice_27_residual": (lambda: synth.workload(2).sliced(n_layers=1, n_kv_heads=2, layer0=11, head0=20, n_residual=27), 24),
 }
+# launches of so few units are split over workgroups by default; these cases keep one workgroup per unit
+ONE_WG_CASES = {"cfg2_slice", "cfg4_slice"}
 
 
 @pytest.mark.parametrize("case", list(FULL_CASES))
 def test_prefill_then_decode(case):
-    """The whole path on the device (no import): prefill compression, then decode steps."""
+    """The whole path on the device (no import): prefill compression, then decode steps (in the
+    launch shape the library picks; the second half of the steps of some cases with one workgroup per unit)."""
     mk, steps = FULL_CASES[case]
     wl = mk()
     steps = wl.decode_steps if steps is None else steps
     print(f"[case] full {case} {wl.name} units={wl.n_units} T={wl.prompt_len} B={wl.slot_capacity} steps={steps}", flush=True)
     cache, units = prefill_gpu_and_oracle(wl, gen_device=DEV if wl.prompt_len > 8192 else "cpu")
     pu.compare_all_state(wl, cache, units, pu.tol_for(wl.dtype), "after prefill")
-    print("[step] prefill parity ok", flush=True)
-    st = pu.run_decode_parity(wl, cache, units, steps, state_every=0)
+    print(f"[step] prefill parity ok; decode launch uses {cache.decode_parts()} workgroup(s) per unit", flush=True)
+    if case in ONE_WG_CASES:
+        st0 = pu.run_decode_parity(wl, cache, units, steps // 2, state_every=0)
+        cache.set_decode_parts(1)
+        st = pu.run_decode_parity(wl, cache, units, steps - steps // 2, state_every=0, first_step=steps // 2)
+        st.unit_steps += st0.unit_steps; st.evictions += st0.evictions; st.near_ties += st0.near_ties
+        st.max_out_err = max(st.max_out_err, st0.max_out_err)
+    else:
+        st = pu.run_decode_parity(wl, cache, units, steps, state_every=0)
     print(f"[done] full {case}: unit-steps={st.unit_steps} evictions={st.evictions} near_ties={st.near_ties} "
           f"max|out err|={st.max_out_err:.2e} scores bit-equal {st.s_bit_equal}/{st.s_total}", flush=True)
     assert st.evictions == st.unit_steps or wl.prompt_len + steps <= wl.slot_capacity
@@ -167,8 +223,9 @@ def test_error_paths_on_device():
     # nothing above may have touched the cache
     st = cache.export_layer(0)
     assert (st["pos"] == -1).all() and (st["w"] == 0).all() and (st["n_seen"] == 0).all()
-    # a budget whose logits do not fit the LDS is refused, not launched
+    # a budget whose logits do not fit one workgroup's LDS is refused, not launched, when splitting is off
     big = zb.Cache(1, 1, 1, 8, 128, 2000, 2000, 1, "f16", device=DEV)
+    big.set_decode_parts(1)
     qq = torch.zeros(1, 1, 1, 8, 128, dtype=torch.float16, device=DEV)
     kk = torch.zeros(1, 1, 1, 128, dtype=torch.float16, device=DEV)
     with pytest.raises(zb.ZsmError) as e:
