@@ -49,19 +49,21 @@ struct DecodeShape {
     static constexpr int R = UT * RPL;           // rows per wave tile
     static constexpr int PART = UH * RPL * (LPR + 1);   // doubles of partial-dot staging per wave
     static constexpr int NT = NW * 64;
-    static constexpr bool QLDS = G > 2;          // queries live in LDS instead of registers
+    static constexpr bool QLDS = G > 1;          // queries live in LDS instead of registers
+    // one LDS region serves the partial-dot staging of pass 1 and, after pass 2, the waves' partial outputs
+    static constexpr size_t STAGE_A = sizeof(double) * NW * PART, STAGE_B = sizeof(float) * NW * G * D;
+    static constexpr size_t STAGE = STAGE_A > STAGE_B ? STAGE_A : STAGE_B;
     static_assert(LPR >= 1 && LPR <= 64 && 64 % LPR == 0, "row must split over a wave");
 
     // dynamic LDS bytes when `nz` slots (the incoming token counted) keep their exp(logit - C) in LDS
     __host__ __device__ static size_t lds_bytes(int nz) {
         size_t n = 0;
         n += sizeof(double) * G * (size_t)nz;          // et
-        n += sizeof(double) * NW * PART;               // part
+        n += STAGE;                                    // part (pass 1) / accw (after pass 2)
         n += sizeof(double) * NW * G;                  // red64
         n += sizeof(double) * (QLDS ? G * D : 0);      // qlds
         n += sizeof(unsigned long long) * NW;          // keyw
         n += sizeof(double) * NW;                      // dotw
-        n += sizeof(float) * NW * G * D;               // accw
         n += sizeof(int) * (4 + NW);                   // misc
         return (n + 15) & ~(size_t)15;
     }
@@ -449,7 +451,7 @@ __device__ __forceinline__ void decode_finish(const DecodeArgs& a, const CacheVi
 //   boundary is what makes one workgroup's scratch visible to another: fences inside one
 //   kernel cost more here than the whole sweep of a small launch).
 template <typename T, int D, int G, int NW, bool SPLIT>
-__global__ __launch_bounds__(NW * 64, (G == 1 ? 4 : 2)) void decode_kernel(DecodeArgs a) {
+__global__ __launch_bounds__(NW * 64, (G == 1 ? 4 : (G <= 4 ? 3 : 2))) void decode_kernel(DecodeArgs a) {
     using Sh = DecodeShape<T, D, G, NW>;
     constexpr int EPL = Sh::EPL, LPR = Sh::LPR, RPL = Sh::RPL, R = Sh::R, PART = Sh::PART, NT = Sh::NT, UT = Sh::UT;
     constexpr bool QLDS = Sh::QLDS;
@@ -479,13 +481,13 @@ __global__ __launch_bounds__(NW * 64, (G == 1 ? 4 : 2)) void decode_kernel(Decod
 
     extern __shared__ __align__(16) unsigned char smem[];
     double* et = reinterpret_cast<double*>(smem);                 // [G][Bz] exp(logit - C) per slot
-    double* part_s = et + (size_t)G * Bz;                         // [NW][PART]
-    double* red64 = part_s + NW * PART;                           // [NW][G]
+    double* part_s = et + (size_t)G * Bz;                         // [NW][PART], pass 1 only
+    float* accw = reinterpret_cast<float*>(part_s);               // [NW][G][D], after pass 2 (same memory)
+    double* red64 = reinterpret_cast<double*>(reinterpret_cast<unsigned char*>(part_s) + Sh::STAGE);   // [NW][G]
     double* qlds = red64 + NW * G;                                // [G][D] (QLDS only)
     unsigned long long* keyw = reinterpret_cast<unsigned long long*>(qlds + (QLDS ? G * D : 0));   // [NW]
     double* dotw = reinterpret_cast<double*>(keyw + NW);          // [NW]
-    float* accw = reinterpret_cast<float*>(dotw + NW);            // [NW][G][D]
-    int* misc = reinterpret_cast<int*>(accw + NW * G * D);        // [4 + NW]
+    int* misc = reinterpret_cast<int*>(dotw + NW);                // [4 + NW]
 
     T* Kt = reinterpret_cast<T*>(cv.Kt) + (size_t)ug * cv.cap_tok * D;
     T* Vt = reinterpret_cast<T*>(cv.Vt) + (size_t)ug * cv.cap_tok * D;
