@@ -57,100 +57,197 @@ __global__ __launch_bounds__(64) void pf_self_logit(PrefillArgs a, PrefillWs ws)
     if (lane == 0) reinterpret_cast<double*>(a.ws + ws.rowm)[((size_t)lu * G + g) * ws.Wp + r] = p * cv.scale;
 }
 
-// ---- P1 / P2: logits of the window queries against the keys ------------------------------
-// One thread per key; the query rows are wave-uniform and come through scalar loads.
-// MODE 0: l_i = sum over keys t <= i of exp(z_it - C_i) (the softmax denominator of Eq. 1);
-//         a workgroup covers PF_KCH passes of PF_TK keys, keeps per-thread partial sums and
-//         reduces them once; the partial per (row, workgroup) goes to the workspace.
-// MODE 1: s_t = sum over rows of roww_i * exp(z_it - C_i)  (Eq. 3 unrolled over the window).
-// The workspace arrays come as separate restrict-qualified arguments: that tells the compiler
-// that the stores of one mode cannot touch the query rows, which keeps their loads scalar.
+// ---- P1 / P2: logits of the window queries against the keys, on the fp64 matrix cores ------
+// D = A x B with v_mfma_f64_16x16x4_f64: A = 16 query rows x 4 channels, B = 4 channels x 16
+// keys, D = 16 x 16 logits accumulated over the D/4 channel steps.  Lane l supplies
+// A[row l%16][channel l/16] and B[channel l/16][key l%16] and receives D[row l/16 + 4r][key l%16]
+// in result register r.  Products of two values of the storage type are exact in fp64, so the
+// logits are fp64 dot products whatever the summation order.
+//   Keys: lane (key j = l%16, quarter q = l/16) loads the 16-byte pieces q, q+4, q+8, ... of its
+//   key row; step c = u*EPL + e uses element e of piece 4u+q, i.e. channel (4u+q)*EPL + e.
+//   Queries: the 32 rows of the pass live in LDS as fp64, permuted to that channel order, one
+//   conflict-free 8-byte read per lane and step.
+// A workgroup owns a range of keys of one unit; its four waves take wave tiles of 16*KB keys.
+// MODE 0: l_i = sum over keys t <= i of exp(z_it - C_i) (the softmax denominator of Eq. 1), partial
+//         per (row, workgroup) to the workspace.
+// MODE 1: s_t = sum over rows of roww_i * exp(z_it - C_i)  (Eq. 3 unrolled over the window); with
+//         one 32-row pass per unit the score is written at once, otherwise the passes add into sacc.
+typedef double d4_t __attribute__((ext_vector_type(4)));
+
 template <typename T, int D, int MODE>
-__global__ __launch_bounds__(PF_TK) void pf_score_kernel(PrefillArgs a, PrefillWs ws, const double* __restrict__ Qd,
-                                                         const double* __restrict__ rowm,
-                                                         const double* __restrict__ roww, double* __restrict__ pl,
-                                                         float* __restrict__ sc) {
+__global__ __launch_bounds__(256, 4) void pf_score_mfma(PrefillArgs a, PrefillWs ws, const double* __restrict__ Qd,
+                                                        const double* __restrict__ rowm,
+                                                        const double* __restrict__ roww, double* __restrict__ pl,
+                                                        double* __restrict__ sacc, float* __restrict__ sc) {
+    constexpr int EPL = 16 / sizeof(T);            // elements per 16-byte piece
+    constexpr int NSTEP = D / 4;                   // matrix steps (4 channels each) per tile
+    constexpr int NLD = NSTEP / EPL;               // 16-byte pieces per lane and key
+    constexpr int KB = sizeof(T) == 4 ? 1 : 2;     // 16-key blocks per wave tile
+    constexpr int RB = PF_MR / 16;                 // 16-row blocks per pass
+    constexpr int TK = 16 * KB;
+    constexpr int NWV = 4;
+    static_assert(PF_KQ % (NWV * 32) == 0, "");
     const CacheView& cv = a.cv;
     const int lu = blockIdx.y;
     const int b = lu / cv.H;
     const int Tb = seq_len_of(a, b);
-    constexpr int NPASS = MODE == 0 ? PF_KCH : 1;
-    const int tile = blockIdx.x;
-    const int tbase = tile * PF_TK * NPASS;
-    if (tbase >= Tb) return;
+    const int chunk = blockIdx.x;
+    const int k0 = chunk * ws.chunk_keys;
+    if (k0 >= Tb) return;
+    const int k1 = k0 + ws.chunk_keys < Tb ? k0 + ws.chunk_keys : Tb;
     const int W = a.W, G = cv.G, Wp = ws.Wp;
     const int nb = W < Tb ? W : Tb;
     const int qpos0 = Tb - nb;                 // position of query row 0
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int j = lane & 15, q = lane >> 4;
     const T* Kbase = reinterpret_cast<const T*>(a.K) + (size_t)lu * a.T_max * D;
     const double scale = cv.scale;
-    constexpr int NWV = PF_TK / 64;
-    __shared__ double red[PF_MR][NWV];
+    __shared__ double Qs[RB * NSTEP * 64];
+    __shared__ double rm[PF_MR], rw[PF_MR];
+    __shared__ double red[NWV][PF_MR];
 
-    double s_acc = 0.0;
     for (int g = 0; g < G; ++g) {
         const size_t head = (size_t)lu * G + g;
         for (int r0 = 0; r0 < nb; r0 += PF_MR) {
             const int rlast = (r0 + PF_MR < nb ? r0 + PF_MR : nb) - 1;
             const size_t rowbase = head * Wp + r0;
-            double lsum[MODE == 0 ? PF_MR : 1];
-            if (MODE == 0) {
-#pragma unroll
-                for (int i = 0; i < PF_MR; ++i) lsum[i] = 0.0;
+            // keys past the last row's position are in the future of every row of this pass
+            const int kend = k1 < qpos0 + rlast + 1 ? k1 : qpos0 + rlast + 1;
+            if (k0 >= kend) {
+                if (MODE == 0 && tid < PF_MR) pl[(rowbase + tid) * ws.nsums + chunk] = 0.0;
+                continue;
             }
-            for (int pass = 0; pass < NPASS; ++pass) {
-                const int t0 = tbase + pass * PF_TK;
-                // every key of this pass in the future of these rows, or past the prompt: nothing to add
-                if (t0 >= Tb || t0 > qpos0 + rlast) break;
-                const int t = t0 + tid;
-                const bool tvalid = t < Tb;
-                const T* krow = Kbase + (size_t)(tvalid ? t : Tb - 1) * D;
-                double acc[PF_MR];
+            __syncthreads();   // the previous pass has finished reading Qs / rm / rw
+            for (int idx = tid; idx < RB * NSTEP * 64; idx += 256) {
+                const int l = idx & 63, c = (idx >> 6) % NSTEP, rb = idx / (64 * NSTEP);
+                const int ch = (4 * (c / EPL) + (l >> 4)) * EPL + c % EPL;
+                Qs[idx] = Qd[(rowbase + 16 * rb + (l & 15)) * D + ch];
+            }
+            if (tid < PF_MR) {
+                rm[tid] = rowm[rowbase + tid];
+                rw[tid] = MODE == 1 ? roww[rowbase + tid] : 0.0;
+            }
+            __syncthreads();
+            double lsum[RB][4];
 #pragma unroll
-                for (int i = 0; i < PF_MR; ++i) acc[i] = 0.0;
-                const double* qb = Qd + rowbase * D;
-                for (int c0 = 0; c0 < D; c0 += 8) {
-                    float kf[8];
-                    load_seg<8>(krow + c0, kf);
-                    double kd[8];
+            for (int rb = 0; rb < RB; ++rb)
 #pragma unroll
-                    for (int e = 0; e < 8; ++e) kd[e] = (double)kf[e];
+                for (int r = 0; r < 4; ++r) lsum[rb][r] = 0.0;
+
+            // this lane's pieces of the wave's current tile; the next tile's pieces replace them one
+            // by one as soon as the last step that needs them has been issued
+            Raw<T, EPL> key[KB][NLD];
+            auto piece = [&](int t0, int kb, int u) {
+                const int t = t0 + 16 * kb + j;
+                return Kbase + (size_t)(t < Tb ? t : Tb - 1) * D + (4 * u + q) * EPL;
+            };
+            int t0 = k0 + wave * TK;
+            if (t0 < kend) {
 #pragma unroll
-                    for (int i = 0; i < PF_MR; ++i) {
+                for (int kb = 0; kb < KB; ++kb)
 #pragma unroll
-                        for (int e = 0; e < 8; ++e) acc[i] = fma(qb[(size_t)i * D + c0 + e], kd[e], acc[i]);
+                    for (int u = 0; u < NLD; ++u) key[kb][u].load(piece(t0, kb, u));
+            }
+            for (; t0 < kend; t0 += NWV * TK) {
+                const int tn = t0 + NWV * TK;
+                d4_t acc[RB][KB];
+#pragma unroll
+                for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+                    for (int kb = 0; kb < KB; ++kb) acc[rb][kb] = d4_t{0.0, 0.0, 0.0, 0.0};
+#pragma unroll
+                for (int u = 0; u < NLD; ++u) {
+#pragma unroll
+                    for (int e = 0; e < EPL; ++e) {
+                        const int c = u * EPL + e;
+                        double av[RB], bv[KB];
+#pragma unroll
+                        for (int rb = 0; rb < RB; ++rb) av[rb] = Qs[(rb * NSTEP + c) * 64 + lane];
+#pragma unroll
+                        for (int kb = 0; kb < KB; ++kb) bv[kb] = (double)key[kb][u].get(e);
+#pragma unroll
+                        for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+                            for (int kb = 0; kb < KB; ++kb)
+                                acc[rb][kb] = __builtin_amdgcn_mfma_f64_16x16x4f64(av[rb], bv[kb], acc[rb][kb], 0, 0, 0);
+                    }
+                    if (tn < kend) {
+#pragma unroll
+                        for (int kb = 0; kb < KB; ++kb) key[kb][u].load(piece(tn, kb, u));
+                    }
+                    // keep each group of steps together: hoisting the later groups' LDS reads and
+                    // conversions above this point costs more registers than there are
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+                // this lane holds the logits of rows 16*rb + q + 4*r against keys t0 + 16*kb + j
+                double sp[KB];
+#pragma unroll
+                for (int kb = 0; kb < KB; ++kb) sp[kb] = 0.0;
+#pragma unroll
+                for (int rb = 0; rb < RB; ++rb) {
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) {
+                        const int i = 16 * rb + q + 4 * r;
+                        const bool valid = r0 + i < nb;
+                        const int qp = qpos0 + r0 + i;     // the row's own position: keys up to it count (Eq. 1)
+                        const double rmv = rm[i], rwv = rw[i];
+#pragma unroll
+                        for (int kb = 0; kb < KB; ++kb) {
+                            const int t = t0 + 16 * kb + j;
+                            const bool ok = valid && t <= qp;
+                            const double ev = exp(fmin(acc[rb][kb][r] * scale - rmv, 690.0));
+                            if (MODE == 0) lsum[rb][r] += ok ? ev : 0.0;
+                            else sp[kb] += ok ? rwv * ev : 0.0;
+                        }
                     }
                 }
+                if (MODE == 1) {
 #pragma unroll
-                for (int i = 0; i < PF_MR; ++i) {
-                    const bool ok = tvalid && (r0 + i) < nb && t <= qpos0 + r0 + i;
-                    if (ok) {
-                        const double e = exp(fmin(acc[i] * scale - rowm[rowbase + i], 690.0));
-                        if (MODE == 0) lsum[i] += e;
-                        else s_acc += roww[rowbase + i] * e;
+                    for (int kb = 0; kb < KB; ++kb) {
+                        double v = sp[kb];
+                        v += shfl_xor_d(v, 16);
+                        v += shfl_xor_d(v, 32);
+                        const int t = t0 + 16 * kb + j;
+                        if (q == 0 && t < kend) {
+                            const size_t o = (size_t)lu * a.T_max + t;
+                            if (ws.multi) sacc[o] += v;     // this wave is the only one that touches key t
+                            else sc[o] = (float)v;
+                        }
                     }
                 }
             }
             if (MODE == 0) {
 #pragma unroll
-                for (int i = 0; i < PF_MR; ++i) {
-                    const double ws_ = wave_sum(lsum[i]);
-                    if (lane == 0) red[i][wave] = ws_;
+                for (int rb = 0; rb < RB; ++rb) {
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) {
+                        double v = lsum[rb][r];
+#pragma unroll
+                        for (int o = 1; o < 16; o <<= 1) v += shfl_xor_d(v, o);
+                        if (j == 0) red[wave][16 * rb + q + 4 * r] = v;
+                    }
                 }
                 __syncthreads();
                 if (tid < PF_MR) {
                     double l = 0.0;
-                    for (int x = 0; x < NWV; ++x) l += red[tid][x];
-                    pl[(rowbase + tid) * ws.nsums + tile] = l;
+                    for (int x = 0; x < NWV; ++x) l += red[x][tid];
+                    pl[(rowbase + tid) * ws.nsums + chunk] = l;
                 }
-                __syncthreads();
             }
         }
     }
-    if (MODE == 1) {
-        const int t = tbase + tid;
-        if (t < Tb) sc[(size_t)lu * a.T_max + t] = (float)s_acc;
-    }
+}
+
+// scores that passed through the fp64 accumulator (more than one pass per unit) -> fp32
+__global__ void pf_sacc_to_sc(PrefillArgs a, const double* __restrict__ sacc, float* __restrict__ sc) {
+    const int lu = blockIdx.y;
+    const int Tb = seq_len_of(a, lu / a.cv.H);
+    for (int t = blockIdx.x * blockDim.x + threadIdx.x; t < Tb; t += gridDim.x * blockDim.x)
+        sc[(size_t)lu * a.T_max + t] = (float)sacc[(size_t)lu * a.T_max + t];
+}
+
+__global__ void pf_fill_f64(double* p, size_t n, double v) {
+    for (size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x) p[i] = v;
 }
 
 // ---- P1b: combine the workgroups' partial denominators per query row ---------------------
@@ -163,7 +260,7 @@ __global__ void pf_row_combine(PrefillArgs a, PrefillWs ws) {
     const int G = cv.G, Wp = ws.Wp;
     const double* pl = reinterpret_cast<const double*>(a.ws + ws.pl);
     double* roww = reinterpret_cast<double*>(a.ws + ws.roww);
-    const int nt = (Tb + PF_TK * PF_KCH - 1) / (PF_TK * PF_KCH);
+    const int nt = (Tb + ws.chunk_keys - 1) / ws.chunk_keys;
     const double lam = (double)cv.lambda;
     for (int idx = threadIdx.x; idx < G * nb; idx += blockDim.x) {
         const int g = idx / nb, r = idx % nb;
@@ -171,6 +268,11 @@ __global__ void pf_row_combine(PrefillArgs a, PrefillWs ws) {
         double L = 0.0;
         for (int x = 0; x < nt; ++x) L += pl[row * ws.nsums + x];
         roww[row] = pow(lam, (double)(nb - 1 - r)) / ((double)G * L);
+    }
+    // rows that pad the last 32-row pass carry no weight
+    for (int idx = threadIdx.x; idx < G * (Wp - nb); idx += blockDim.x) {
+        const int g = idx / (Wp - nb), r = nb + idx % (Wp - nb);
+        roww[((size_t)lu * G + g) * Wp + r] = 0.0;
     }
 }
 
@@ -268,6 +370,141 @@ __global__ __launch_bounds__(SEL_NT) void pf_select(PrefillArgs a, PrefillWs ws)
         if (tid == SEL_NT - 1) carry_sh = base + inc;
         __syncthreads();
     }
+    for (int i = tid; i < Bp; i += SEL_NT) { kept_pos[Bc + i] = N + i; keep[N + i] = 1; }
+    __syncthreads();
+    if (tid == 0) { sel[0] = ntok; sel[1] = first_drop; }
+}
+
+// The same selection for prompts of up to SEL_NT * SEL_NPT candidates, with the scores held in
+// registers (candidate k*SEL_NT + tid in register k): the B_c-th largest bit pattern is found
+// bit by bit (31 counting steps of ballots, no histogram and no memory traffic), the ordered
+// compaction takes one block scan over the (register, wave) ballot counts.
+constexpr int SEL_NPT = 64;
+
+__global__ __launch_bounds__(SEL_NT) void pf_select_reg(PrefillArgs a, PrefillWs ws) {
+    const CacheView& cv = a.cv;
+    const int lu = blockIdx.x;
+    const int b = lu / cv.H;
+    const int Tb = seq_len_of(a, b);
+    const int Bp = cv.Bp[b], Bc = cv.Bc[b];
+    const int ntok = Bp + Bc;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    constexpr int NWV = SEL_NT / 64;
+    const uint32_t* sc = reinterpret_cast<const uint32_t*>(a.ws + ws.sc) + (size_t)lu * a.T_max;
+    unsigned char* keep = reinterpret_cast<unsigned char*>(a.ws + ws.keep) + (size_t)lu * a.T_max;
+    int32_t* kept_pos = reinterpret_cast<int32_t*>(a.ws + ws.kept_pos) + (size_t)lu * cv.cap_tok;
+    int32_t* sel = reinterpret_cast<int32_t*>(a.ws + ws.sel) + (size_t)lu * 4;
+
+    if (Tb <= ntok) {   // short prompt: everything is kept, in position order
+        for (int t = tid; t < Tb; t += SEL_NT) { kept_pos[t] = t; keep[t] = 1; }
+        if (tid == 0) { sel[0] = Tb; sel[1] = -1; }
+        return;
+    }
+    const int N = Tb - Bp;   // candidates for the context set: positions [0, N)
+    const int nk = (N + SEL_NT - 1) / SEL_NT;   // registers in use (<= SEL_NPT, checked by the host)
+    uint32_t v[SEL_NPT];
+#pragma unroll
+    for (int k = 0; k < SEL_NPT; ++k) {
+        // branch-free: a candidate index past the end reads the last candidate and is zeroed
+        const int t = k * SEL_NT + tid;
+        const uint32_t x = sc[min(t, N - 1)];
+        v[k] = x & (uint32_t)((t - N) >> 31);   // all ones where t < N
+        if (k % 16 == 15) __builtin_amdgcn_sched_barrier(0);   // sixteen loads in flight at a time
+    }
+    __shared__ int wcnt[2][NWV];
+    __shared__ unsigned long long cnt2[SEL_NPT * NWV];   // per (register, wave): (greater << 32 | equal), then their exclusive scan
+    __shared__ unsigned long long mgt[SEL_NPT * NWV], meq[SEL_NPT * NWV];   // the ballots themselves
+    __shared__ unsigned long long wsum[NWV];
+    __shared__ int first_drop;
+    if (tid == 0) first_drop = 0x7fffffff;
+
+    // number of candidates whose pattern is >= c (every thread gets the same answer)
+    auto count_ge = [&](uint32_t c, int par) {
+        int n = 0;   // this lane's count; registers past nk and candidates past N hold 0 and are not counted (c > 0)
+#pragma unroll
+        for (int k = 0; k < SEL_NPT; ++k) n += v[k] >= c ? 1 : 0;
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) n += __shfl_xor(n, o, 64);
+        if (lane == 0) wcnt[par][wave] = n;
+        __syncthreads();
+        int tot = 0;
+#pragma unroll
+        for (int x = 0; x < NWV; ++x) tot += wcnt[par][x];
+        return tot;
+    };
+    uint32_t thr = 0xffffffffu;   // B_c = 0: nothing is above or equal
+    int r_eq = 0;
+    if (Bc > 0) {
+        thr = 0;
+        // scores are >= 0: bit 31 is clear, the unsigned order of the patterns is the value order
+        int par = 0;
+        for (int bit = 30; bit >= 0; --bit) {
+            const uint32_t c = thr | (1u << bit);
+            if (count_ge(c, par) >= Bc) thr = c;   // at least B_c candidates reach c: the B_c-th largest does too
+            par ^= 1;
+        }
+        // thr = pattern of the B_c-th largest score; r_eq = how many equal to it are kept
+        const int n_gt = thr == 0xffffffffu ? 0 : count_ge(thr + 1u, par);
+        r_eq = Bc - n_gt;
+    }
+    __syncthreads();
+    // ordered compaction: kept = every score above thr and the first r_eq equal to it, in position order
+#pragma unroll
+    for (int k = 0; k < SEL_NPT; ++k) {
+        if (k < nk) {
+            // registers of candidates past N hold 0: never above thr, and where they equal it (thr = 0)
+            // they come after every real candidate in position order, so none of them is among the r_eq kept
+            const unsigned long long bg = __ballot(v[k] > thr), be = __ballot(v[k] == thr);
+            if (lane == 0) {
+                cnt2[k * NWV + wave] = ((unsigned long long)__popcll(bg) << 32) | (unsigned long long)__popcll(be);
+                mgt[k * NWV + wave] = bg;
+                meq[k * NWV + wave] = be;
+            }
+        }
+        __builtin_amdgcn_sched_barrier(0);   // one pair of ballots at a time: they live in scalar registers
+    }
+    __syncthreads();
+    {   // exclusive scan of the nk * NWV counts in (register, wave) order = position order
+        const int ne = nk * NWV;   // <= SEL_NT
+        const unsigned long long mine = tid < ne ? cnt2[tid] : 0ull;
+        unsigned long long inc = mine;
+#pragma unroll
+        for (int o = 1; o < 64; o <<= 1) {
+            const unsigned long long up = __shfl_up(inc, o, 64);
+            if (lane >= o) inc += up;
+        }
+        if (lane == 63) wsum[wave] = inc;
+        __syncthreads();
+        unsigned long long base = 0;
+        for (int x = 0; x < wave; ++x) base += wsum[x];
+        if (tid < ne) cnt2[tid] = base + inc - mine;
+    }
+    __syncthreads();
+    int my_first_drop = 0x7fffffff;
+    const unsigned long long lt_mask = (1ull << lane) - 1ull;
+    // The compiler would otherwise keep the 64 lane masks of "t < N" from the loads above alive in
+    // scalar registers (and spill them); an opaque copy of N makes it compare again here.
+    int Nv = N;
+    asm volatile("" : "+s"(Nv));
+#pragma unroll
+    for (int k = 0; k < SEL_NPT; ++k) {
+        if (k < nk) {
+            const int t = k * SEL_NT + tid;
+            const unsigned long long bg = mgt[k * NWV + wave], be = meq[k * NWV + wave];   // the ballots taken above
+            const bool gt = (bg >> lane) & 1ull, eq = (be >> lane) & 1ull;
+            const unsigned long long base = cnt2[k * NWV + wave];
+            const int gt_before = (int)(base >> 32) + __popcll(bg & lt_mask);
+            const int eq_before = (int)(base & 0xffffffffull) + __popcll(be & lt_mask);
+            if (t < Nv) {
+                const bool kp = gt || (eq && eq_before < r_eq);
+                keep[t] = kp ? 1 : 0;
+                if (kp) kept_pos[gt_before + (eq_before < r_eq ? eq_before : r_eq)] = t;
+                else my_first_drop = t < my_first_drop ? t : my_first_drop;
+            }
+        }
+        __builtin_amdgcn_sched_barrier(0);
+    }
+    if (my_first_drop != 0x7fffffff) atomicMin(&first_drop, my_first_drop);
     for (int i = tid; i < Bp; i += SEL_NT) { kept_pos[Bc + i] = N + i; keep[N + i] = 1; }
     __syncthreads();
     if (tid == 0) { sel[0] = ntok; sel[1] = first_drop; }
@@ -537,17 +774,21 @@ hipError_t launch_prefill_td(const PrefillArgs& a, hipStream_t st) {
     const size_t n_heads = (size_t)a.n_units * cv.G;
     hipLaunchKernelGGL((pf_convert_q<T>), dim3(1024), dim3(256), 0, st, reinterpret_cast<const T*>(a.Q),
                        reinterpret_cast<double*>(a.ws + ws.Qd), a.W, ws.Wp, D, n_heads);
-    const dim3 gs(ws.ntiles, a.n_units);
+    const dim3 gs(ws.nsums, a.n_units);
     hipLaunchKernelGGL((pf_self_logit<T, D>), dim3(cv.G * ws.Wp, a.n_units), dim3(64), 0, st, a, ws);
     const double* Qd = reinterpret_cast<const double*>(a.ws + ws.Qd);
     const double* rowm = reinterpret_cast<const double*>(a.ws + ws.rowm);
     const double* roww = reinterpret_cast<const double*>(a.ws + ws.roww);
     double* pl = reinterpret_cast<double*>(a.ws + ws.pl);
+    double* sacc = reinterpret_cast<double*>(a.ws + ws.sacc);
     float* sc = reinterpret_cast<float*>(a.ws + ws.sc);
-    hipLaunchKernelGGL((pf_score_kernel<T, D, 0>), dim3(ws.nsums, a.n_units), dim3(PF_TK), 0, st, a, ws, Qd, rowm, roww, pl, sc);
+    hipLaunchKernelGGL((pf_score_mfma<T, D, 0>), gs, dim3(256), 0, st, a, ws, Qd, rowm, roww, pl, sacc, sc);
     hipLaunchKernelGGL(pf_row_combine, dim3(a.n_units), dim3(256), 0, st, a, ws);
-    hipLaunchKernelGGL((pf_score_kernel<T, D, 1>), gs, dim3(PF_TK), 0, st, a, ws, Qd, rowm, roww, pl, sc);
-    hipLaunchKernelGGL(pf_select, dim3(a.n_units), dim3(SEL_NT), 0, st, a, ws);
+    if (ws.multi) hipLaunchKernelGGL(pf_fill_f64, dim3(1024), dim3(256), 0, st, sacc, (size_t)a.n_units * a.T_max, 0.0);
+    hipLaunchKernelGGL((pf_score_mfma<T, D, 1>), gs, dim3(256), 0, st, a, ws, Qd, rowm, roww, pl, sacc, sc);
+    if (ws.multi) hipLaunchKernelGGL(pf_sacc_to_sc, dim3((a.T_max + 255) / 256, a.n_units), dim3(256), 0, st, a, sacc, sc);
+    if (a.T_max <= SEL_NT * SEL_NPT) hipLaunchKernelGGL(pf_select_reg, dim3(a.n_units), dim3(SEL_NT), 0, st, a, ws);
+    else hipLaunchKernelGGL(pf_select, dim3(a.n_units), dim3(SEL_NT), 0, st, a, ws);
     constexpr int EPL = 16 / sizeof(T), LPR = D / EPL, RPB = 256 / LPR;
     const int gblocks = (cv.cap_tok + RPB * 4 - 1) / (RPB * 4);
     hipLaunchKernelGGL((pf_gather<T, D>), dim3(gblocks > 0 ? gblocks : 1, a.n_units), dim3(256), 0, st, a, ws);

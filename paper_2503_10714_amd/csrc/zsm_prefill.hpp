@@ -19,22 +19,29 @@ struct PrefillArgs {
     char* ws;
 };
 
-constexpr int PF_TK = 256;     // keys per workgroup pass in the scoring kernels (one per thread)
-constexpr int PF_KCH = 4;      // key passes per workgroup in the row-sum kernel (PF_TK * PF_KCH keys)
-constexpr int PF_MR = 32;      // query rows per pass
+constexpr int PF_MR = 32;      // query rows per pass of the scoring kernels (two 16-row matrix blocks)
+constexpr int PF_KQ = 128;     // granule of a workgroup's key range in the scoring kernels (4 waves x 32 keys)
+constexpr int PF_SCORE_WGS = 1024;   // scoring launches aim at this many workgroups (4 per compute unit, one round)
 constexpr int PF_RC = 512;     // prompt positions per workgroup in the residual sum
 
 struct PrefillWs {
-    size_t Qd, pl, rowm, roww, sc, keep, kept_pos, sel, rsum, total;
-    int Wp, ntiles, nsums, nchunks;
+    size_t Qd, pl, rowm, roww, sc, sacc, keep, kept_pos, sel, rsum, total;
+    int Wp, nsums, chunk_keys, nchunks;   // nsums key ranges of chunk_keys keys per unit in the scoring kernels
+    int multi;                            // more than one (query head, 32-row block) per unit: scores pass through sacc
 };
 
 inline PrefillWs prefill_ws_layout(const CacheView& cv, int T_max, int W) {
     PrefillWs w{};
     const size_t units = (size_t)cv.S * cv.H;
     w.Wp = (W + PF_MR - 1) / PF_MR * PF_MR;
-    w.ntiles = (T_max + PF_TK - 1) / PF_TK;
-    w.nsums = (T_max + PF_TK * PF_KCH - 1) / (PF_TK * PF_KCH);
+    {
+        int n = PF_SCORE_WGS / (int)(units > 0 ? units : 1);
+        const int most = (T_max + PF_KQ - 1) / PF_KQ;
+        n = n < 1 ? 1 : (n > most ? most : n);
+        w.chunk_keys = ((T_max + n - 1) / n + PF_KQ - 1) / PF_KQ * PF_KQ;
+        w.nsums = (T_max + w.chunk_keys - 1) / w.chunk_keys;
+    }
+    w.multi = cv.G * (w.Wp / PF_MR) > 1;
     w.nchunks = (T_max + PF_RC - 1) / PF_RC;
     auto up = [](size_t x) { return (x + 255) & ~(size_t)255; };
     size_t o = 0;
@@ -43,6 +50,7 @@ inline PrefillWs prefill_ws_layout(const CacheView& cv, int T_max, int W) {
     w.rowm = o; o += up(sizeof(double) * units * cv.G * w.Wp);
     w.roww = o; o += up(sizeof(double) * units * cv.G * w.Wp);
     w.sc = o; o += up(sizeof(float) * units * T_max);
+    w.sacc = o; o += up(w.multi ? sizeof(double) * units * T_max : 0);
     w.keep = o; o += up(units * (size_t)T_max);
     w.kept_pos = o; o += up(sizeof(int32_t) * units * (cv.cap_tok > 0 ? cv.cap_tok : 1));
     w.sel = o; o += up(sizeof(int32_t) * units * 4);
