@@ -581,13 +581,29 @@ __global__ __launch_bounds__(256) void pf_residual_partial(PrefillArgs a, Prefil
         const T* Ksrc = reinterpret_cast<const T*>(a.K) + (size_t)lu * a.T_max * D;
         const T* Vsrc = reinterpret_cast<const T*>(a.V) + (size_t)lu * a.T_max * D;
         const int t1 = t0 + PF_RC < Tb ? t0 + PF_RC : Tb;
-        for (int t = t0 + rg; t < t1; t += RPB) {
-            if (keep[t]) continue;
-            float kf[EPL], vf[EPL];
-            load_seg<EPL>(Ksrc + (size_t)t * D + seg * EPL, kf);
-            load_seg<EPL>(Vsrc + (size_t)t * D + seg * EPL, vf);
+        // Branch-free and four rows deep: most rows are absorbed, so every row is loaded (a row index
+        // past the end reads the last row) and a kept row adds nothing; the loads of four rows are in
+        // flight together.
+        constexpr int UR = 4;
+        for (int tb = t0 + rg; tb < t1; tb += UR * RPB) {
+            Raw<T, EPL> kr[UR], vr[UR];
+            bool use[UR];
 #pragma unroll
-            for (int e = 0; e < EPL; ++e) { ak[e] += (double)kf[e]; av[e] += (double)vf[e]; }
+            for (int x = 0; x < UR; ++x) {
+                const int t = tb + x * RPB;
+                const int tc = t < t1 ? t : t1 - 1;
+                use[x] = t < t1 && keep[tc] == 0;
+                kr[x].load(Ksrc + (size_t)tc * D + seg * EPL);
+                vr[x].load(Vsrc + (size_t)tc * D + seg * EPL);
+            }
+#pragma unroll
+            for (int x = 0; x < UR; ++x) {
+#pragma unroll
+                for (int e = 0; e < EPL; ++e) {
+                    ak[e] += use[x] ? (double)kr[x].get(e) : 0.0;
+                    av[e] += use[x] ? (double)vr[x].get(e) : 0.0;
+                }
+            }
         }
     }
 #pragma unroll
@@ -628,7 +644,15 @@ __global__ __launch_bounds__(256) void pf_residual_final(PrefillArgs a, PrefillW
     const int nch = (Tb + PF_RC - 1) / PF_RC;
     for (int i = tid; i < 2 * D; i += 256) {
         double t = 0.0;
-        for (int c = 0; c < nch; ++c) t += rsum[(size_t)c * 2 * D + i];
+        int c = 0;
+        for (; c + 8 <= nch; c += 8) {   // eight partial sums requested together, added in chunk order
+            double x[8];
+#pragma unroll
+            for (int y = 0; y < 8; ++y) x[y] = rsum[(size_t)(c + y) * 2 * D + i];
+#pragma unroll
+            for (int y = 0; y < 8; ++y) t += x[y];
+        }
+        for (; c < nch; ++c) t += rsum[(size_t)c * 2 * D + i];
         const float m = (float)(t / (double)ndrop);
         if (i < D) Kr[i] = m; else Vr[i - D] = m;
     }

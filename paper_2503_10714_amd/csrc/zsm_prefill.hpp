@@ -22,7 +22,7 @@ struct PrefillArgs {
 constexpr int PF_MR = 32;      // query rows per pass of the scoring kernels (two 16-row matrix blocks)
 constexpr int PF_KQ = 128;     // granule of a workgroup's key range in the scoring kernels (4 waves x 32 keys)
 constexpr int PF_SCORE_WGS = 1024;   // scoring launches aim at this many workgroups (4 per compute unit, one round)
-constexpr int PF_RC = 512;     // prompt positions per workgroup in the residual sum
+constexpr int PF_RC = 1024;    // prompt positions per workgroup in the residual sum
 
 struct PrefillWs {
     size_t Qd, pl, rowm, roww, sc, sacc, keep, kept_pos, sel, rsum, total;
