@@ -106,6 +106,9 @@ def main():
                          "per N layers, as a model that runs its layers one after the other would call it")
     ap.add_argument("--decode-parts", type=int, default=0,
                     help="workgroups per unit in the decode step: 0 = the library's choice per launch, 1 = never split, n = n")
+    ap.add_argument("--window", type=int, default=None,
+                    help="override the number of prompt queries W the prefill scores from (0 = every prompt query: "
+                         "the full-history initialisation)")
     ap.add_argument("--n-residual", type=int, default=None,
                     help="override the workload's number of residual slots B_r (B stays the same, B_c shrinks)")
     ap.add_argument("--pmc-calibration", action="store_true",
@@ -132,6 +135,8 @@ def main():
     wl = synth.workload(args.workload)
     if args.n_residual is not None:
         wl = wl.sliced(n_residual=args.n_residual)
+    if args.window is not None:
+        wl = wl.sliced(window=args.window)
     if wl.ragged is not None:
         print("bench.py: ragged workloads are parity-test cases, not bench lines", file=sys.stderr)
         sys.exit(2)
@@ -245,6 +250,7 @@ def main():
         "tokens_per_s_cache_step_only": value / (L * H) if S == 1 else None,
         "hbm_read_ceiling_GBs": read_ceiling,
         "prefill_compress_ms_all_layers": prefill_ms,
+        "prefill_window": (wl.window if wl.window > 0 else wl.prompt_len),
         "setup_s": setup_s,
     }
     if args.pmc_calibration:
