@@ -244,7 +244,7 @@ struct UnitRefs {
     const T* knew; const T* vnew;
 };
 
-constexpr int DECODE_MCH = 8;   // slots per thread whose score and position are requested ahead
+constexpr int DECODE_MCH = 12;  // slots per thread whose score and position are requested ahead (3072 slots per workgroup)
 
 // What the end of a step reads that does not depend on its decisions.  The caller requests it
 // early (load()), so that the only memory round trip left between the eviction choice and the
@@ -259,23 +259,53 @@ struct FinishPre {
     T kn, vn;                // channel tid of the incoming token (tid < D)
     float kr0, vr0;          // B_r = 1: channel tid of the only residual slot
     int w0;                  // B_r = 1: its fusion count
+    bool vec;                // slots are taken four at a time (16-byte loads and stores): the slot stride allows it
+    // slot of this thread's k-th value, counted from the start of a batch of NT * DECODE_MCH slots
+    __device__ __forceinline__ int slot_of(int k) const {
+        const int tid = threadIdx.x;
+        return vec ? (((k >> 2) * NT + tid) << 2) + (k & 3) : k * NT + tid;
+    }
+    // positions and scores of the batch that starts at slot `base`; slots >= lim read as empty.
+    // Under load every memory instruction of a wave queues behind the other workgroups' sweeps,
+    // so their number matters: four slots per instruction where the layout is 16-byte aligned.
+    __device__ __forceinline__ void load_meta(const UnitRefs<T>& u, int base, int lim) {
+        const int tid = threadIdx.x;
+        if (vec) {
+#pragma unroll
+            for (int kk = 0; kk < DECODE_MCH / 4; ++kk) {
+                const int j = base + ((kk * NT + tid) << 2);
+                int4 p = make_int4(-1, -1, -1, -1);
+                float4 x = make_float4(0.f, 0.f, 0.f, 0.f);
+                if (j < lim) {   // lim is a multiple of 4 here
+                    p = *reinterpret_cast<const int4*>(u.pos + j);
+                    x = *reinterpret_cast<const float4*>(u.s + j);
+                }
+                pj[4 * kk + 0] = p.x; pj[4 * kk + 1] = p.y; pj[4 * kk + 2] = p.z; pj[4 * kk + 3] = p.w;
+                sj[4 * kk + 0] = x.x; sj[4 * kk + 1] = x.y; sj[4 * kk + 2] = x.z; sj[4 * kk + 3] = x.w;
+            }
+        } else {
+#pragma unroll
+            for (int k = 0; k < DECODE_MCH; ++k) {
+                const int j = base + k * NT + tid;
+                pj[k] = j < lim ? u.pos[j] : -1;
+                sj[k] = j < lim ? u.s[j] : 0.f;
+            }
+        }
+    }
     __device__ __forceinline__ void load(const UnitRefs<T>& u, int cap, int Br, const double* et = nullptr, int Bz = 0) {
         const int tid = threadIdx.x;
+        static_assert(DECODE_MCH % 4 == 0, "");
+        vec = (cap & 3) == 0;   // every unit's score and position rows then start on a 16-byte boundary
         if (GE > 0) {
 #pragma unroll
             for (int k = 0; k < DECODE_MCH; ++k) {
-                const int j = k * NT + tid;
+                const int j = slot_of(k);
 #pragma unroll
                 for (int g = 0; g < (GE > 0 ? GE : 1); ++g) ej[k][g] = j < cap ? et[(size_t)g * Bz + j] : 0.0;
             }
         }
         // slots between the unit's B and the slot stride are empty by construction (pos = -1)
-#pragma unroll
-        for (int k = 0; k < DECODE_MCH; ++k) {
-            const int j = k * NT + tid;
-            pj[k] = j < cap ? u.pos[j] : -1;
-            sj[k] = j < cap ? u.s[j] : 0.f;
-        }
+        load_meta(u, 0, cap);
         wres = tid < Br ? u.w[tid] : 1;
         if (tid < D) { kn = u.knew[tid]; vn = u.vnew[tid]; }
         w0 = 1; kr0 = 0.f; vr0 = 0.f;
@@ -320,33 +350,37 @@ __device__ __forceinline__ void decode_finish(const DecodeArgs& a, const CacheVi
     unsigned long long best = ~0ull;
     int best_slot = -1;
     for (int base = 0; base < B; base += NT * MCH) {
-        if (base > 0) {
+        if (base > 0) pre.load_meta(u, base, cv.cap);
 #pragma unroll
-            for (int k = 0; k < MCH; ++k) {
-                const int j = base + k * NT + tid;
-                pre.pj[k] = j < B ? pos[j] : -1;
-                pre.sj[k] = j < B ? s[j] : 0.f;
-            }
-        }
+        for (int kk = 0; kk < MCH / 4; ++kk) {
+            float sn4[4];
 #pragma unroll
-        for (int k = 0; k < MCH; ++k) {
-            const int j = base + k * NT + tid;
-            if (j >= B) continue;
-            if (pre.pj[k] >= 0) {   // occupied (a residual slot carries the position of its first token)
-                double pm = 0.0;
+            for (int c4 = 0; c4 < 4; ++c4) {
+                const int k = 4 * kk + c4;
+                const int j = base + pre.slot_of(k);
+                sn4[c4] = pre.sj[k];
+                if (j >= B) continue;
+                if (pre.pj[k] >= 0) {   // occupied (a residual slot carries the position of its first token)
+                    double pm = 0.0;
 #pragma unroll
-                for (int g = 0; g < G; ++g)
-                    pm += ((GE > 0 && base == 0) ? pre.ej[GE > 0 ? k : 0][GE > 0 ? g : 0] : et[(size_t)g * Bz + j]) * rL[g];
-                pm /= (double)G;
-                const float sn = (float)(lam * (double)pre.sj[k] + pm);
-                s[j] = sn;
-                if (full && j >= Br && (long long)pre.pj[k] <= cand_hi) {
-                    const unsigned long long key = ((unsigned long long)__float_as_uint(sn) << 32) | (uint32_t)pre.pj[k];
+                    for (int g = 0; g < G; ++g)
+                        pm += ((GE > 0 && base == 0) ? pre.ej[GE > 0 ? k : 0][GE > 0 ? g : 0] : et[(size_t)g * Bz + j]) * rL[g];
+                    pm /= (double)G;
+                    const float sn = (float)(lam * (double)pre.sj[k] + pm);
+                    sn4[c4] = sn;
+                    if (!pre.vec) s[j] = sn;
+                    if (full && j >= Br && (long long)pre.pj[k] <= cand_hi) {
+                        const unsigned long long key = ((unsigned long long)__float_as_uint(sn) << 32) | (uint32_t)pre.pj[k];
+                        if (key < best) { best = key; best_slot = j; }
+                    }
+                } else if (!full && j >= Br) {
+                    const unsigned long long key = (unsigned long long)j;   // lowest free token slot
                     if (key < best) { best = key; best_slot = j; }
                 }
-            } else if (!full && j >= Br) {
-                const unsigned long long key = (unsigned long long)j;   // lowest free token slot
-                if (key < best) { best = key; best_slot = j; }
+            }
+            if (pre.vec) {   // four scores per store; a slot that was not updated gets back what was read
+                const int j0 = base + pre.slot_of(4 * kk);
+                if (j0 < B) *reinterpret_cast<float4*>(s + j0) = make_float4(sn4[0], sn4[1], sn4[2], sn4[3]);
             }
         }
     }
@@ -621,7 +655,8 @@ __global__ __launch_bounds__(NW * 64, (G == 1 ? 4 : (G <= 4 ? 3 : 2))) void deco
     }
 
     // What the end of the step reads regardless of its decisions: requested now, used after the
-    // output has been combined, so that the latency is hidden.
+    // output has been combined, so that part of the latency is hidden.  (Requested a pass earlier
+    // the values do not fit the register budget and the spill makes every wave wait for them.)
     UnitRefs<T> u{Kt, Vt, Kr, Vr, s, pos, w, knew, vnew};
     FinishPre<T, D, NW> pre;
     if (!SPLIT) pre.load(u, cv.cap, Br);
