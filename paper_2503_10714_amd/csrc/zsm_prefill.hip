@@ -20,16 +20,24 @@ __device__ __forceinline__ double wave_max_d(double v) {
     return v;
 }
 
-// ---- Q -> fp64, rows padded to a multiple of PF_MR with zeros ----------------------------
+// ---- Q -> fp64 in the order the scoring kernels stage it, rows padded to a multiple of PF_MR with zeros
+// Per (head, 32-row block): [row block rb of 16][matrix step c][lane l] = Q[row 16*rb + l%16][channel
+// (4*(c/EPL) + l/16)*EPL + c%EPL]: lane l's A operand of step c (see pf_score_mfma), so that a workgroup
+// stages a block with one contiguous 16-byte-per-lane copy.
 template <typename T>
 __global__ void pf_convert_q(const T* __restrict__ Q, double* __restrict__ Qd, int W, int Wp, int D, size_t n_heads) {
-    // one (unit, g) pair = "head"; Qd[head][Wp][D]
+    constexpr int EPL = 16 / sizeof(T);
+    const int nstep = D / 4;
     const size_t total = n_heads * Wp * D;
     for (size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x; i < total; i += (size_t)gridDim.x * blockDim.x) {
-        const int c = (int)(i % D);
-        const int r = (int)((i / D) % Wp);
-        const size_t h = i / ((size_t)D * Wp);
-        Qd[i] = r < W ? (double)to_float(Q[(h * W + r) * D + c]) : 0.0;
+        const int l = (int)(i & 63);
+        const int c = (int)((i >> 6) % nstep);
+        const int rb = (int)((i / (64 * (size_t)nstep)) % (PF_MR / 16));
+        const size_t blk = i / ((size_t)PF_MR * D);          // (head, 32-row block), Wp / PF_MR blocks per head
+        const size_t h = blk / (Wp / PF_MR);
+        const int r = (int)(blk % (Wp / PF_MR)) * PF_MR + 16 * rb + (l & 15);
+        const int ch = (4 * (c / EPL) + (l >> 4)) * EPL + c % EPL;
+        Qd[i] = r < W ? (double)to_float(Q[(h * W + r) * D + ch]) : 0.0;
     }
 }
 
@@ -49,10 +57,10 @@ __global__ __launch_bounds__(64) void pf_self_logit(PrefillArgs a, PrefillWs ws)
     const int g = idx / ws.Wp, r = idx % ws.Wp;
     if (g >= G || r >= nb) return;
     const int lane = threadIdx.x;
-    const double* q = reinterpret_cast<const double*>(a.ws + ws.Qd) + (((size_t)lu * G + g) * ws.Wp + r) * D;
+    const T* q = reinterpret_cast<const T*>(a.Q) + (((size_t)lu * G + g) * a.W + r) * D;
     const T* k = reinterpret_cast<const T*>(a.K) + ((size_t)lu * a.T_max + (Tb - nb + r)) * D;
     double p = 0.0;
-    for (int c = lane; c < D; c += 64) p = fma(q[c], (double)to_float(k[c]), p);
+    for (int c = lane; c < D; c += 64) p = fma((double)to_float(q[c]), (double)to_float(k[c]), p);
     p = wave_sum(p);
     if (lane == 0) reinterpret_cast<double*>(a.ws + ws.rowm)[((size_t)lu * G + g) * ws.Wp + r] = p * cv.scale;
 }
@@ -91,10 +99,6 @@ __global__ __launch_bounds__(256, 4) void pf_score_mfma(PrefillArgs a, PrefillWs
     const int lu = blockIdx.y;
     const int b = lu / cv.H;
     const int Tb = seq_len_of(a, b);
-    const int chunk = blockIdx.x;
-    const int k0 = chunk * ws.chunk_keys;
-    if (k0 >= Tb) return;
-    const int k1 = k0 + ws.chunk_keys < Tb ? k0 + ws.chunk_keys : Tb;
     const int W = a.W, G = cv.G, Wp = ws.Wp;
     const int nb = W < Tb ? W : Tb;
     const int qpos0 = Tb - nb;                 // position of query row 0
@@ -106,9 +110,21 @@ __global__ __launch_bounds__(256, 4) void pf_score_mfma(PrefillArgs a, PrefillWs
     __shared__ double rm[PF_MR], rw[PF_MR];
     __shared__ double red[NWV][PF_MR];
 
-    for (int g = 0; g < G; ++g) {
+    // passes = (query head, 32-row block) pairs; this workgroup takes every rz-th one
+    const int nblk = (nb + PF_MR - 1) / PF_MR;
+    double* sacc_z = sacc + (size_t)blockIdx.z * gridDim.y * a.T_max;
+    for (int half = 0; half < (ws.fold ? 2 : 1); ++half) {
+    // key range of this round: x, then (folded launches) its mirror image nsums-1-x
+    const int chunk = half == 0 ? (int)blockIdx.x : ws.nsums - 1 - (int)blockIdx.x;
+    if (half == 1 && chunk <= (int)blockIdx.x) break;
+    const int k0 = chunk * ws.chunk_keys;
+    if (k0 >= Tb) continue;
+    const int k1 = k0 + ws.chunk_keys < Tb ? k0 + ws.chunk_keys : Tb;
+    for (int pass = blockIdx.z; pass < G * nblk; pass += gridDim.z) {
+        const int g = pass / nblk;
         const size_t head = (size_t)lu * G + g;
-        for (int r0 = 0; r0 < nb; r0 += PF_MR) {
+        {
+            const int r0 = (pass % nblk) * PF_MR;
             const int rlast = (r0 + PF_MR < nb ? r0 + PF_MR : nb) - 1;
             const size_t rowbase = head * Wp + r0;
             // keys past the last row's position are in the future of every row of this pass
@@ -118,10 +134,11 @@ __global__ __launch_bounds__(256, 4) void pf_score_mfma(PrefillArgs a, PrefillWs
                 continue;
             }
             __syncthreads();   // the previous pass has finished reading Qs / rm / rw
-            for (int idx = tid; idx < RB * NSTEP * 64; idx += 256) {
-                const int l = idx & 63, c = (idx >> 6) % NSTEP, rb = idx / (64 * NSTEP);
-                const int ch = (4 * (c / EPL) + (l >> 4)) * EPL + c % EPL;
-                Qs[idx] = Qd[(rowbase + 16 * rb + (l & 15)) * D + ch];
+            {   // the block's query operands are stored in staging order: a contiguous copy
+                const double2* src = reinterpret_cast<const double2*>(Qd + rowbase * D);   // rowbase is a multiple of 32
+                double2* dst = reinterpret_cast<double2*>(Qs);
+#pragma unroll
+                for (int x = 0; x < RB * NSTEP * 64 / 2 / 256; ++x) dst[x * 256 + tid] = src[x * 256 + tid];
             }
             if (tid < PF_MR) {
                 rm[tid] = rowm[rowbase + tid];
@@ -210,7 +227,7 @@ __global__ __launch_bounds__(256, 4) void pf_score_mfma(PrefillArgs a, PrefillWs
                         const int t = t0 + 16 * kb + j;
                         if (q == 0 && t < kend) {
                             const size_t o = (size_t)lu * a.T_max + t;
-                            if (ws.multi) sacc[o] += v;     // this wave is the only one that touches key t
+                            if (ws.multi) sacc_z[o] += v;   // this wave is the only one that touches key t in this group's array
                             else sc[o] = (float)v;
                         }
                     }
@@ -236,14 +253,19 @@ __global__ __launch_bounds__(256, 4) void pf_score_mfma(PrefillArgs a, PrefillWs
             }
         }
     }
+    }
 }
 
 // scores that passed through the fp64 accumulator (more than one pass per unit) -> fp32
-__global__ void pf_sacc_to_sc(PrefillArgs a, const double* __restrict__ sacc, float* __restrict__ sc) {
+__global__ void pf_sacc_to_sc(PrefillArgs a, const double* __restrict__ sacc, int rz, float* __restrict__ sc) {
     const int lu = blockIdx.y;
     const int Tb = seq_len_of(a, lu / a.cv.H);
-    for (int t = blockIdx.x * blockDim.x + threadIdx.x; t < Tb; t += gridDim.x * blockDim.x)
-        sc[(size_t)lu * a.T_max + t] = (float)sacc[(size_t)lu * a.T_max + t];
+    const size_t zs = (size_t)gridDim.y * a.T_max;   // stride between the pass groups' arrays
+    for (int t = blockIdx.x * blockDim.x + threadIdx.x; t < Tb; t += gridDim.x * blockDim.x) {
+        double v = 0.0;
+        for (int z = 0; z < rz; ++z) v += sacc[z * zs + (size_t)lu * a.T_max + t];
+        sc[(size_t)lu * a.T_max + t] = (float)v;
+    }
 }
 
 __global__ void pf_fill_f64(double* p, size_t n, double v) {
@@ -798,7 +820,7 @@ hipError_t launch_prefill_td(const PrefillArgs& a, hipStream_t st) {
     const size_t n_heads = (size_t)a.n_units * cv.G;
     hipLaunchKernelGGL((pf_convert_q<T>), dim3(1024), dim3(256), 0, st, reinterpret_cast<const T*>(a.Q),
                        reinterpret_cast<double*>(a.ws + ws.Qd), a.W, ws.Wp, D, n_heads);
-    const dim3 gs(ws.nsums, a.n_units);
+    const dim3 gs(ws.fold ? (ws.nsums + 1) / 2 : ws.nsums, a.n_units, ws.rz);
     hipLaunchKernelGGL((pf_self_logit<T, D>), dim3(cv.G * ws.Wp, a.n_units), dim3(64), 0, st, a, ws);
     const double* Qd = reinterpret_cast<const double*>(a.ws + ws.Qd);
     const double* rowm = reinterpret_cast<const double*>(a.ws + ws.rowm);
@@ -808,9 +830,9 @@ hipError_t launch_prefill_td(const PrefillArgs& a, hipStream_t st) {
     float* sc = reinterpret_cast<float*>(a.ws + ws.sc);
     hipLaunchKernelGGL((pf_score_mfma<T, D, 0>), gs, dim3(256), 0, st, a, ws, Qd, rowm, roww, pl, sacc, sc);
     hipLaunchKernelGGL(pf_row_combine, dim3(a.n_units), dim3(256), 0, st, a, ws);
-    if (ws.multi) hipLaunchKernelGGL(pf_fill_f64, dim3(1024), dim3(256), 0, st, sacc, (size_t)a.n_units * a.T_max, 0.0);
+    if (ws.multi) hipLaunchKernelGGL(pf_fill_f64, dim3(1024), dim3(256), 0, st, sacc, (size_t)ws.rz * a.n_units * a.T_max, 0.0);
     hipLaunchKernelGGL((pf_score_mfma<T, D, 1>), gs, dim3(256), 0, st, a, ws, Qd, rowm, roww, pl, sacc, sc);
-    if (ws.multi) hipLaunchKernelGGL(pf_sacc_to_sc, dim3((a.T_max + 255) / 256, a.n_units), dim3(256), 0, st, a, sacc, sc);
+    if (ws.multi) hipLaunchKernelGGL(pf_sacc_to_sc, dim3((a.T_max + 255) / 256, a.n_units), dim3(256), 0, st, a, sacc, ws.rz, sc);
     if (a.T_max <= SEL_NT * SEL_NPT) hipLaunchKernelGGL(pf_select_reg, dim3(a.n_units), dim3(SEL_NT), 0, st, a, ws);
     else hipLaunchKernelGGL(pf_select, dim3(a.n_units), dim3(SEL_NT), 0, st, a, ws);
     constexpr int EPL = 16 / sizeof(T), LPR = D / EPL, RPB = 256 / LPR;

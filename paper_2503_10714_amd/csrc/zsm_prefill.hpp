@@ -28,6 +28,8 @@ struct PrefillWs {
     size_t Qd, pl, rowm, roww, sc, sacc, keep, kept_pos, sel, rsum, total;
     int Wp, nsums, chunk_keys, nchunks;   // nsums key ranges of chunk_keys keys per unit in the scoring kernels
     int multi;                            // more than one (query head, 32-row block) per unit: scores pass through sacc
+    int rz;                               // groups the passes of a unit are dealt to (grid.z of the scoring launches)
+    int fold;                             // a workgroup takes key ranges x and nsums-1-x
 };
 
 inline PrefillWs prefill_ws_layout(const CacheView& cv, int T_max, int W) {
@@ -35,13 +37,23 @@ inline PrefillWs prefill_ws_layout(const CacheView& cv, int T_max, int W) {
     const size_t units = (size_t)cv.S * cv.H;
     w.Wp = (W + PF_MR - 1) / PF_MR * PF_MR;
     {
-        int n = PF_SCORE_WGS / (int)(units > 0 ? units : 1);
+        // Work of the scoring launches: (unit, key range, group of 32-row passes).  With one pass
+        // per unit the key ranges alone make up about PF_SCORE_WGS workgroups; with many passes
+        // (a long window, grouped queries) the passes are dealt round-robin to up to 8 groups, so
+        // that a key range stays long enough to pay for re-staging the query block every pass.
+        const int npass = cv.G * (w.Wp / PF_MR);
+        w.multi = npass > 1;
+        w.rz = npass >= 8 ? (npass / 4 < 8 ? npass / 4 : 8) : 1;
+        // Rows attend to keys up to their own position only, so with many row blocks the early key
+        // ranges carry far more work than the late ones: a workgroup then takes key range x together
+        // with range nsums-1-x ("fold"), which evens the work out whatever XCD the workgroup lands on.
+        w.fold = w.rz > 1 && 2 * (long long)W >= T_max;   // a short window sits at the end of the prompt: every key range sees all of it
+        int n = PF_SCORE_WGS / (int)((units > 0 ? units : 1) * w.rz) * (w.fold ? 2 : 1);
         const int most = (T_max + PF_KQ - 1) / PF_KQ;
         n = n < 1 ? 1 : (n > most ? most : n);
         w.chunk_keys = ((T_max + n - 1) / n + PF_KQ - 1) / PF_KQ * PF_KQ;
         w.nsums = (T_max + w.chunk_keys - 1) / w.chunk_keys;
     }
-    w.multi = cv.G * (w.Wp / PF_MR) > 1;
     w.nchunks = (T_max + PF_RC - 1) / PF_RC;
     auto up = [](size_t x) { return (x + 255) & ~(size_t)255; };
     size_t o = 0;
@@ -50,7 +62,7 @@ inline PrefillWs prefill_ws_layout(const CacheView& cv, int T_max, int W) {
     w.rowm = o; o += up(sizeof(double) * units * cv.G * w.Wp);
     w.roww = o; o += up(sizeof(double) * units * cv.G * w.Wp);
     w.sc = o; o += up(sizeof(float) * units * T_max);
-    w.sacc = o; o += up(w.multi ? sizeof(double) * units * T_max : 0);
+    w.sacc = o; o += up(w.multi ? sizeof(double) * w.rz * units * T_max : 0);   // [rz][units][T_max]
     w.keep = o; o += up(units * (size_t)T_max);
     w.kept_pos = o; o += up(sizeof(int32_t) * units * (cv.cap_tok > 0 ? cv.cap_tok : 1));
     w.sel = o; o += up(sizeof(int32_t) * units * 4);
