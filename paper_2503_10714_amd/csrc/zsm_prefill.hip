@@ -689,12 +689,18 @@ __global__ __launch_bounds__(256) void pf_residual_final(PrefillArgs a, PrefillW
 // The tokens that were not kept are absorbed in position order: the first B_r open the
 // residual slots, every later one is merged into the slot with the largest key dot product
 // (Eq. 5, lowest index on ties) by the incremental mean of Eq. 6.  Each merge changes a key
-// the next token's choice depends on, so the walk is sequential per unit: one wave per unit,
-// lane r owns residual slot r for the dot products (keys and values live in LDS in their fp32
-// storage form and are rounded to it after every merge), lanes own channels for the merge.
+// the next token's choice depends on, so the walk is sequential per unit: one wave per unit.
+// What keeps the step short:
+//   * the prompt is walked in blocks of 16 positions whose K and V rows and keep flags are
+//     requested a block ahead (registers) and staged in LDS, so no step waits for memory;
+//   * a residual key's dot product is split over LPS = 1, 2 or 4 lanes (64 / the power of two
+//     above B_r), each with four independent fp64 accumulators;
+//   * keys and values live in LDS in their fp32 storage form and are rounded to it after every
+//     merge (so the next choice sees what the stored state would give).
 constexpr int PF_RMAX = 64;   // residual slots the wave can own
+constexpr int PF_GB = 16;     // positions per staged block
 
-template <typename T, int D>
+template <typename T, int D, int LPS>
 __global__ __launch_bounds__(64) void pf_residual_greedy(PrefillArgs a, PrefillWs ws) {
     const CacheView& cv = a.cv;
     const int lu = blockIdx.x;
@@ -705,10 +711,18 @@ __global__ __launch_bounds__(64) void pf_residual_greedy(PrefillArgs a, PrefillW
     const int lane = threadIdx.x;
     constexpr int RS = D + 4;   // padded row stride (floats): lanes reading 16 bytes of different rows hit different banks
     constexpr int CPL = D / 64; // channels per lane in the merge
+    constexpr int EPL = 16 / sizeof(T);
+    constexpr int RL = D / EPL;               // 16-byte pieces per row
+    constexpr int NLD = PF_GB * RL / 64;      // wave-wide loads per block and array
+    static_assert(PF_GB * RL % 64 == 0, "");
     extern __shared__ __align__(16) unsigned char smem[];
     float* Krs = reinterpret_cast<float*>(smem);            // [Br][RS]
     float* Vrs = Krs + (size_t)Br * RS;                      // [Br][RS]
     double* ktok = reinterpret_cast<double*>(Vrs + (size_t)Br * RS);   // [D]
+    double* dots = ktok + D;                                 // [PF_RMAX] the keys' dot products with the token
+    int* wcs = reinterpret_cast<int*>(dots + PF_RMAX);       // [PF_RMAX] fusion counts
+    T* Kst = reinterpret_cast<T*>(wcs + PF_RMAX);            // [PF_GB][D] staged rows of the current block
+    T* Vst = Kst + PF_GB * D;
     float* s = cv.s + (size_t)ug * cv.cap;
     int32_t* pos = cv.pos + (size_t)ug * cv.cap;
     int32_t* w = cv.w + (size_t)ug * cv.cap;
@@ -719,74 +733,108 @@ __global__ __launch_bounds__(64) void pf_residual_greedy(PrefillArgs a, PrefillW
     const T* Ksrc = reinterpret_cast<const T*>(a.K) + (size_t)lu * a.T_max * D;
     const T* Vsrc = reinterpret_cast<const T*>(a.V) + (size_t)lu * a.T_max * D;
 
+    // LPS lanes per residual key (the host picks 64 / the power of two above B_r, at most 4)
+    constexpr int NS = 64 / LPS;              // lanes r, r + NS, ... share key r
+    const int r_own = lane % NS, h_own = lane / NS;
+    const bool dot_lane = r_own < Br;
+    constexpr int CH = D / LPS;               // channels per share
+    const int cbeg = h_own * CH;
+
     for (int i = lane; i < Br * RS; i += 64) { Krs[i] = 0.f; Vrs[i] = 0.f; }
-    int wcnt = 0;          // lane r: fusion count of slot r
+    for (int i = lane; i < PF_RMAX; i += 64) { wcs[i] = 0; dots[i] = -INFINITY; }
     int n_open = 0;        // residual slots opened so far (wave-uniform)
-    wave_sync();
-    // next token's row is requested one step ahead
-    int t = 0;
-    while (t < Tb && keep[t]) ++t;
-    float kc[CPL], vc[CPL];
-    if (t < Tb) {
+
+    // a block's rows and flags, requested one block ahead
+    Raw<T, EPL> kreg[NLD], vreg[NLD];
+    int kflag = 1;
+    auto request = [&](int p0) {   // positions [p0, p0 + PF_GB); rows past the prompt read its last row
 #pragma unroll
-        for (int x = 0; x < CPL; ++x) {
-            kc[x] = to_float(Ksrc[(size_t)t * D + lane + 64 * x]);
-            vc[x] = to_float(Vsrc[(size_t)t * D + lane + 64 * x]);
+        for (int x = 0; x < NLD; ++x) {
+            const int piece = x * 64 + lane;
+            const int row = p0 + piece / RL;
+            const size_t off = (size_t)(row < Tb ? row : Tb - 1) * D + (piece % RL) * EPL;
+            kreg[x].load(Ksrc + off);
+            vreg[x].load(Vsrc + off);
         }
-    }
-    while (t < Tb) {
-        int tn = t + 1;
-        while (tn < Tb && keep[tn]) ++tn;
-        float kn[CPL], vn[CPL];
-        if (tn < Tb) {
+        const int t = p0 + lane;
+        kflag = (lane < PF_GB && t < Tb) ? keep[t] : 1;   // 1 = not to be absorbed
+    };
+    if (Tb > 0) request(0);
+    for (int p0 = 0; p0 < Tb; p0 += PF_GB) {
+        wave_sync();   // the previous block's rows are no longer read
+#pragma unroll
+        for (int x = 0; x < NLD; ++x) {
+            const int piece = x * 64 + lane;
+            *reinterpret_cast<Raw<T, EPL>*>(Kst + (size_t)piece * EPL) = kreg[x];
+            *reinterpret_cast<Raw<T, EPL>*>(Vst + (size_t)piece * EPL) = vreg[x];
+        }
+        unsigned long long todo = __ballot(kflag == 0);   // bit i: position p0 + i is absorbed
+        if (p0 + PF_GB < Tb) request(p0 + PF_GB);
+        wave_sync();
+        while (todo) {
+            const int i = __builtin_ctzll(todo);
+            todo &= todo - 1;
+            const int t = p0 + i;
+            float kc[CPL], vc[CPL];
 #pragma unroll
             for (int x = 0; x < CPL; ++x) {
-                kn[x] = to_float(Ksrc[(size_t)tn * D + lane + 64 * x]);
-                vn[x] = to_float(Vsrc[(size_t)tn * D + lane + 64 * x]);
+                kc[x] = to_float(Kst[i * D + lane + 64 * x]);
+                vc[x] = to_float(Vst[i * D + lane + 64 * x]);
             }
-        }
-        if (n_open < Br) {
-            // Alg. 1: the residual set still has room, the token opens slot n_open
+            if (n_open < Br) {
+                // Alg. 1: the residual set still has room, the token opens slot n_open
 #pragma unroll
-            for (int x = 0; x < CPL; ++x) {
-                Krs[n_open * RS + lane + 64 * x] = kc[x];
-                Vrs[n_open * RS + lane + 64 * x] = vc[x];
+                for (int x = 0; x < CPL; ++x) {
+                    Krs[n_open * RS + lane + 64 * x] = kc[x];
+                    Vrs[n_open * RS + lane + 64 * x] = vc[x];
+                }
+                if (lane == n_open) {
+                    wcs[n_open] = 1;
+                    pos[n_open] = t;
+                    s[n_open] = sc[t];
+                }
+                ++n_open;
+                wave_sync();
+                continue;
             }
-            if (lane == n_open) {
-                wcnt = 1;
-                pos[n_open] = t;
-                s[n_open] = sc[t];
-            }
-            ++n_open;
-            wave_sync();
-        } else {
 #pragma unroll
             for (int x = 0; x < CPL; ++x) ktok[lane + 64 * x] = (double)kc[x];
             wave_sync();
-            // Eq. 5: lane r forms k_r . k_t
-            double dot = -INFINITY;
-            if (lane < Br) {
-                double p = 0.0;
-                const float* kr = Krs + lane * RS;
-#pragma unroll 4
-                for (int c = 0; c < D; c += 4) {
-                    const float4 kv = *reinterpret_cast<const float4*>(kr + c);
-                    p = fma((double)kv.x, ktok[c + 0], p);
-                    p = fma((double)kv.y, ktok[c + 1], p);
-                    p = fma((double)kv.z, ktok[c + 2], p);
-                    p = fma((double)kv.w, ktok[c + 3], p);
-                }
-                dot = p;
-            }
-            int rbest = lane < Br ? lane : 0x7fffffff;
+            // Eq. 5: k_r . k_t, this lane's share of the channels
+            double dot = 0.0;
+            if (dot_lane) {
+                double p0_ = 0.0, p1_ = 0.0, p2_ = 0.0, p3_ = 0.0;
+                const float* kr = Krs + r_own * RS + cbeg;
+                const double* kt = ktok + cbeg;
 #pragma unroll
-            for (int o = 32; o > 0; o >>= 1) {
-                const double d2 = __shfl_xor(dot, o, 64);
-                const int r2 = __shfl_xor(rbest, o, 64);
-                if (r2 != 0x7fffffff && (rbest == 0x7fffffff || d2 > dot || (d2 == dot && r2 < rbest))) { dot = d2; rbest = r2; }
+                for (int c = 0; c < CH; c += 4) {
+                    const float4 kv = *reinterpret_cast<const float4*>(kr + c);
+                    p0_ = fma((double)kv.x, kt[c + 0], p0_);
+                    p1_ = fma((double)kv.y, kt[c + 1], p1_);
+                    p2_ = fma((double)kv.z, kt[c + 2], p2_);
+                    p3_ = fma((double)kv.w, kt[c + 3], p3_);
+                }
+                dot = (p0_ + p1_) + (p2_ + p3_);
             }
+            // the shares of one key meet (lanes r, r + NS, ...); the keys' dot products go to LDS and
+            // every lane finds the largest one itself (lowest index on ties): one LDS round trip
+            // instead of a chain of shuffles
+#pragma unroll
+            for (int o = NS * (LPS >> 1); o >= NS; o >>= 1) dot += __shfl_xor(dot, o, 64);
+            if (lane < Br) dots[lane] = dot;
+            wave_sync();
+            double dv[NS];   // all NS entries are read at once (entries >= B_r hold -inf)
+#pragma unroll
+            for (int r = 0; r < NS; ++r) dv[r] = dots[r];
+            int rbest = 0;
+            double dbest = dv[0];
+#pragma unroll
+            for (int r = 1; r < NS; ++r)
+                if (dv[r] > dbest) { dbest = dv[r]; rbest = r; }
+            rbest = __builtin_amdgcn_readfirstlane(rbest);
             // Eq. 6 on the chosen slot, rounded to the fp32 storage form
-            const double wd = (double)__shfl(wcnt, rbest, 64);
+            const int wi = wcs[rbest];
+            const double wd = (double)wi;
 #pragma unroll
             for (int x = 0; x < CPL; ++x) {
                 const int c = lane + 64 * x;
@@ -794,13 +842,11 @@ __global__ __launch_bounds__(64) void pf_residual_greedy(PrefillArgs a, PrefillW
                 Krs[rbest * RS + c] = (float)(__dadd_rn(__dmul_rn(wd, k0), (double)kc[x]) / (wd + 1.0));
                 Vrs[rbest * RS + c] = (float)(__dadd_rn(__dmul_rn(wd, v0), (double)vc[x]) / (wd + 1.0));
             }
-            if (lane == rbest) ++wcnt;
-            wave_sync();
+            wave_sync();   // every lane has read the count
+            if (lane == 0) wcs[rbest] = wi + 1;
         }
-#pragma unroll
-        for (int x = 0; x < CPL; ++x) { kc[x] = kn[x]; vc[x] = vn[x]; }
-        t = tn;
     }
+    wave_sync();
     // write the residual slots back; slots never opened are empty
     for (int i = lane; i < Br * D; i += 64) {
         const int r = i / D, c = i % D;
@@ -808,6 +854,7 @@ __global__ __launch_bounds__(64) void pf_residual_greedy(PrefillArgs a, PrefillW
         Vr[i] = Vrs[r * RS + c];
     }
     if (lane < Br) {
+        const int wcnt = wcs[lane];
         w[lane] = wcnt;
         if (wcnt == 0) { pos[lane] = -1; s[lane] = 0.f; }
     }
@@ -843,15 +890,13 @@ hipError_t launch_prefill_td(const PrefillArgs& a, hipStream_t st) {
         hipLaunchKernelGGL((pf_residual_partial<T, D>), dim3(ws.nchunks, a.n_units), dim3(256), 0, st, a, ws);
         hipLaunchKernelGGL((pf_residual_final<D>), dim3(a.n_units), dim3(256), 0, st, a, ws);
     } else if (cv.Br > 1) {
-        const size_t lds = sizeof(float) * 2 * (size_t)cv.Br * (D + 4) + sizeof(double) * D;
-        auto kern = pf_residual_greedy<T, D>;
-        static bool attr_set = false;
-        if (!attr_set) {
-            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                               hipFuncAttributeMaxDynamicSharedMemorySize, 96 * 1024);
-            if (e != hipSuccess) return e;
-            attr_set = true;
-        }
+        const size_t lds = sizeof(float) * 2 * (size_t)cv.Br * (D + 4) + sizeof(double) * (D + PF_RMAX) + sizeof(int) * PF_RMAX +
+                           2 * PF_GB * D * sizeof(T);
+        // lanes per residual key: 64 / the power of two above B_r, at most 4
+        void (*kern)(PrefillArgs, PrefillWs) = cv.Br > 32 ? pf_residual_greedy<T, D, 1>
+                                               : (cv.Br > 16 ? pf_residual_greedy<T, D, 2> : pf_residual_greedy<T, D, 4>);
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, 96 * 1024);
+        if (e != hipSuccess) return e;
         hipLaunchKernelGGL(kern, dim3(a.n_units), dim3(64), lds, st, a, ws);
     }
     return hipGetLastError();
