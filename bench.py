@@ -99,7 +99,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", type=int, default=2)
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-units", type=int, default=4)
+    ap.add_argument("--cpu-units", type=int, default=32,
+                    help="units of layer 0 the CPU oracle is timed on (32 = one full layer of workload 2, about 20 s)")
     ap.add_argument("--cpu-steps", type=int, default=512)
     ap.add_argument("--layers-per-launch", type=int, default=0,
                     help="0 = all layers of the workload in one launch (the headline configuration); N = one launch "

@@ -33,6 +33,9 @@ DECODE_CASES = {
                                         prompt_len=300, ragged=(40, 300), budget_ratio=0.2, budget=60, decode_steps=30),
     "tiny_budget": lambda: small("tiny_budget", budget=3, prompt_len=50, decode_steps=30),            # B_p = 1, B_c = 1, B_r = 1
     "no_context": lambda: small("no_context", prompt_len=60, budget=9, prox=8, decode_steps=30, window=8),     # B_c = 0
+    # 4001 slots x 8 query heads x 8 bytes do not fit one workgroup's LDS: the step is cut over workgroups by itself
+    "huge_capacity_gqa8": lambda: small("huge_capacity_gqa8", n_kv_heads=1, q_per_kv=8, head_dim=128, dtype="f16",
+                                        prompt_len=4300, budget=4001, decode_steps=6, window=8, outliers=True),
 }
 
 
@@ -173,6 +176,10 @@ FULL_CASES = {
     "cfg4_slice": (lambda: synth.workload(4).sliced(n_layers=1, n_seqs=2, n_kv_heads=2, layer0=30, seq0=3, head0=6), 24),
     # the paper's recommended residual share (dense ratio 0.02 of B - B_p: 27 slots at B = 2700) on workload 2's shape
     "cfg2_slice_27_residual": (lambda: synth.workload(2).sliced(n_layers=1, n_kv_heads=2, layer0=11, head0=20, n_residual=27), 24),
+    # a batch of prompts between 0 and 5 tokens long (three of the eight are empty), then enough steps to fill
+    # the slots and evict
+    "ragged_with_empty_prompts": (lambda: small("ragged_empty", n_seqs=8, prompt_len=5, ragged=(0, 5), budget=12, window=8,
+                                                 n_residual=2, dtype="f16"), 40),
 }
 # launches of so few units are split over workgroups by default; these cases keep one workgroup per unit
 ONE_WG_CASES = {"cfg2_slice", "cfg4_slice"}
@@ -199,7 +206,10 @@ def test_prefill_then_decode(case):
         st = pu.run_decode_parity(wl, cache, units, steps, state_every=0)
     print(f"[done] full {case}: unit-steps={st.unit_steps} evictions={st.evictions} near_ties={st.near_ties} "
           f"max|out err|={st.max_out_err:.2e} scores bit-equal {st.s_bit_equal}/{st.s_total}", flush=True)
-    assert st.evictions == st.unit_steps or wl.prompt_len + steps <= wl.slot_capacity
+    # a step evicts once every token slot is occupied: after the prefill min(T_b, B_p + B_c) are
+    bp, bc, _ = wl.budgets()
+    expected = sum(max(0, steps - max(0, p + c - min(t, p + c))) for t, p, c in zip(wl.seq_lens(), bp, bc))
+    assert st.evictions == expected * wl.n_layers * wl.n_kv_heads, (st.evictions, expected)
     cache.close()
 
 
