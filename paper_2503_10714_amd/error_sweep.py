@@ -11,7 +11,10 @@ is the sign: merging has the lower error.
 The budgeted path runs through the C ABI (prefill compression + decode steps).  The full
 attention it is compared with is evaluation code (torch, fp64), not part of the product.
 
-    python -m paper_2503_10714_amd.error_sweep [--prompt 4096] [--steps 128] [--heads 32]
+The same harness sweeps the compensation weight alpha of Eq. 4 (the paper's hyper-parameter
+study varies it between 0, the eviction-like end, and 1, the value it fixes).
+
+    python -m paper_2503_10714_amd.error_sweep [--prompt 4096] [--steps 128] [--heads 32] [--alphas 0,0.5,1]
 """
 from __future__ import annotations
 
@@ -67,14 +70,29 @@ def sweep(prompt=4096, steps=128, heads=32, ratios=(0.5, 0.2, 0.1, 0.05), dtype=
     return rows
 
 
+def alpha_sweep(prompt=4096, steps=128, heads=32, ratio=0.05, alphas=(0.0, 0.25, 0.5, 0.75, 1.0), dtype="f16",
+                device="cuda:0"):
+    """Residual merging (B_r = 1) at one budget for several alpha of Eq. 4: mean relative output error."""
+    B = int(math.ceil(ratio * prompt))
+    rows = []
+    for al in alphas:
+        wl = synth.Workload(f"err-alpha-{al}", 1, 1, heads, 1, 128, dtype, prompt, B, steps, 32, True, n_residual=1, alpha=al)
+        rows.append({"budget_ratio": ratio, "B": B, "alpha": al, "rel_err_merge": float(run_policy(wl, device).mean())})
+    return rows
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--prompt", type=int, default=4096)
     ap.add_argument("--steps", type=int, default=128)
     ap.add_argument("--heads", type=int, default=32)
+    ap.add_argument("--alphas", type=str, default="", help="comma-separated alpha values: also sweep Eq. 4's alpha at a 5 % budget")
     args = ap.parse_args()
     for r in sweep(args.prompt, args.steps, args.heads):
         print(json.dumps(r))
+    if args.alphas:
+        for r in alpha_sweep(args.prompt, args.steps, args.heads, alphas=tuple(float(x) for x in args.alphas.split(","))):
+            print(json.dumps(r))
 
 
 if __name__ == "__main__":

@@ -53,3 +53,14 @@ def test_device_error_sweep_matches_oracle_and_trend():
     print(rows, flush=True)
     for r in rows:
         assert r["rel_err_merge"] < r["rel_err_evict"], r
+
+
+@pytest.mark.gpu
+def test_device_alpha_sweep_matches_oracle():
+    """Eq. 4's alpha on the device path against the oracle, at the two ends and in the middle."""
+    from paper_2503_10714_amd import error_sweep as es
+    for al in (0.0, 0.5, 1.0):
+        wl = synth.Workload(f"err-alpha-{al}", 1, 1, 3, 1, 128, "f16", 400, 20, 24, 32, True, n_residual=1, alpha=al)
+        dev = es.run_policy(wl)[:, :, 0].cpu().numpy()
+        ora = oracle_errors(wl)
+        assert np.abs(dev - ora).max() < 1e-4, (al, np.abs(dev - ora).max())
