@@ -161,6 +161,87 @@ __device__ __forceinline__ void k_compute(const Raw<KT, EPL>* kr, int row0, int 
     }
 }
 
+// ---- pass 1 for grouped queries (G >= 2), full tiles only --------------------------------
+// With G query heads a lane holds 4*G partial dot products per tile (4 rows x G heads), and the
+// LPR lanes of a row group have to add theirs up.  Instead of staging them in LDS head by head
+// (G rounds of writes, reads by a quarter of the lanes, and an exp at a quarter of the lanes),
+// the lanes of the group exchange halves: at every step a lane keeps one half of its values,
+// sends the other half to the lane whose number differs in one bit, and adds what it receives.
+// After log2(LPR) steps every (row, head) sum sits in exactly one lane (or in LPR/(4G) lanes when
+// there are fewer sums than lanes), so one exp per lane serves all heads at full width.
+constexpr int ilog2_c(int x) { return x <= 1 ? 0 : 1 + ilog2_c(x / 2); }
+
+template <int NV, int DD>
+__device__ __forceinline__ void lane_group_reduce(double* pp, int seg) {
+    if constexpr (DD >= 1) {
+        const bool hi = (seg & DD) != 0;
+        if constexpr (NV > 1) {
+            constexpr int H = NV / 2;
+#pragma unroll
+            for (int i = 0; i < H; ++i) {
+                const double keep = hi ? pp[i + H] : pp[i];
+                const double send = hi ? pp[i] : pp[i + H];
+                pp[i] = keep + __shfl_xor(send, DD, 64);
+            }
+            lane_group_reduce<H, DD / 2>(pp, seg);
+        } else {
+            pp[0] += __shfl_xor(pp[0], DD, 64);
+            lane_group_reduce<1, DD / 2>(pp, seg);
+        }
+    }
+}
+
+// Which sums a lane ends up with: values are numbered v = g*4 + u (head g, wave-wide load u).
+template <int G, int LPR>
+struct GqOwn {
+    static constexpr int UH = 4, V = UH * G;
+    static constexpr int NVF = V >= LPR ? V / LPR : 1;        // sums per lane at the end
+    static constexpr int REP = V >= LPR ? 1 : LPR / V;        // lanes that hold the same sum
+    static constexpr int K = ilog2_c(V / NVF), LB = ilog2_c(LPR);
+    static_assert(NVF <= UH, "a lane's sums must belong to one head");
+    __device__ static int first_value(int seg) { return (seg >> (LB - K)) * NVF; }
+    __device__ static int head(int seg) { return first_value(seg) / UH; }
+    __device__ static bool writes(int seg) { return (seg & (REP - 1)) == 0; }
+};
+
+// One full tile (4 wave-wide loads, every row occupied): exp(logit - C) of this lane's (row, head)
+// sums into et, their total into lsum_own.  c_own = C[GqOwn::head(seg)].
+template <typename KT, int D, int G, int EPL, int LPR, int RPL, bool QLDS>
+__device__ __forceinline__ void k_compute_gq(const Raw<KT, EPL>* kr, int row0, int nrows, int zidx0, double scale,
+                                             const Query<G, EPL, QLDS>& qq, double c_own, double& lsum_own,
+                                             double* et, int Bz, int lane) {
+    using Own = GqOwn<G, LPR>;
+    constexpr int UH = Own::UH;
+    const int grp = lane / LPR, seg = lane % LPR;
+    double pp[Own::V];
+#pragma unroll
+    for (int g = 0; g < G; ++g) {
+        double qv[EPL];
+        qq.get(g, seg, D, qv);
+#pragma unroll
+        for (int u = 0; u < UH; ++u) {
+            double p = 0.0;
+#pragma unroll
+            for (int e = 0; e < EPL; ++e) p = fma(qv[e], (double)kr[u].get(e), p);
+            pp[g * UH + u] = p;
+        }
+    }
+    lane_group_reduce<Own::V, LPR / 2>(pp, seg);
+    const int v0 = Own::first_value(seg);
+    const int g_own = v0 / UH;
+    if (Own::writes(seg)) {
+#pragma unroll
+        for (int i = 0; i < Own::NVF; ++i) {
+            const int row = row0 + ((v0 + i) % UH) * RPL + grp;
+            if (row < nrows) {
+                const double ev = exp(fmin(pp[i] * scale - c_own, 690.0));
+                lsum_own += ev;
+                et[(size_t)g_own * Bz + zidx0 + row] = ev;
+            }
+        }
+    }
+}
+
 // Pass 1 for rows that may be empty: load only the occupied ones (an empty slot may hold any
 // bit pattern), then k_compute.
 template <typename KT, int UU, int D, int G, int EPL, int LPR, int RPL, bool QLDS>
@@ -578,6 +659,11 @@ __global__ __launch_bounds__(NW * 64, (G == 1 ? 4 : (G <= 4 ? 3 : 2))) void deco
         }
     }
     double* part_w = part_s + wave * PART;
+    // grouped queries: the head whose sums this lane finishes in full tiles, its reference, its total
+    const int g_own = GqOwn<G, LPR>::head(seg);
+    double c_own = C[0], lsum_own = 0.0;
+#pragma unroll
+    for (int g = 1; g < G; ++g) c_own = g == g_own ? C[g] : c_own;
 
     // ---- pass 1 (D1): logits of this workgroup's slots, exp(logit - C) into LDS ---------
     // Fast path (every token slot occupied): tiles are double-buffered in registers, the loads
@@ -590,8 +676,11 @@ __global__ __launch_bounds__(NW * 64, (G == 1 ? 4 : (G <= 4 ? 3 : 2))) void deco
             prio_from_progress(t - tb, 2 * (te - tb));
             if (tn < te) tile_load<T, UT, D, EPL, LPR, RPL>(bufB, Kt, tn * R, ntok, lane);
             else tile_load<T, UT, D, EPL, LPR, RPL>(bufB, Vt, (tb + wave) * R, ntok, lane);   // tb + wave < te here
-            k_compute<T, UT, false, D, G, EPL, LPR, RPL, QLDS>(bufA, t * R, row_e, zt, nullptr, nullptr, alpha, scale, qq,
-                                                               C, lsum, et, Bz, part_w, lane);
+            if constexpr (G >= 2)
+                k_compute_gq<T, D, G, EPL, LPR, RPL, QLDS>(bufA, t * R, row_e, zt, scale, qq, c_own, lsum_own, et, Bz, lane);
+            else
+                k_compute<T, UT, false, D, G, EPL, LPR, RPL, QLDS>(bufA, t * R, row_e, zt, nullptr, nullptr, alpha, scale, qq,
+                                                                   C, lsum, et, Bz, part_w, lane);
 #pragma unroll
             for (int u = 0; u < UT; ++u) bufA[u] = bufB[u];
             t = tn;
@@ -612,7 +701,7 @@ __global__ __launch_bounds__(NW * 64, (G == 1 ? 4 : (G <= 4 ? 3 : 2))) void deco
     }
 #pragma unroll
     for (int g = 0; g < G; ++g) {
-        const double t = wave_sum(lsum[g]);
+        const double t = wave_sum(lsum[g] + (G >= 2 && g == g_own ? lsum_own : 0.0));
         if (lane == 0) red64[wave * G + g] = t;
     }
     __syncthreads();
