@@ -171,9 +171,9 @@ FULL_CASES = {
     "cfg0": (lambda: synth.workload(0), None),
     "cfg1": (lambda: synth.workload(1), None),
     # the deep / wide workloads at their true per-unit shape, fewer layers, sequences and heads
-    "cfg2_slice": (lambda: synth.workload(2).sliced(n_layers=2, n_kv_heads=3, layer0=7, head0=5), 24),
-    "cfg3_slice": (lambda: synth.workload(3).sliced(n_layers=1, n_seqs=3, n_kv_heads=2, layer0=3, seq0=11, head0=9), 24),
-    "cfg4_slice": (lambda: synth.workload(4).sliced(n_layers=1, n_seqs=2, n_kv_heads=2, layer0=30, seq0=3, head0=6), 24),
+    "cfg2_slice": (lambda: synth.workload(2).sliced(n_layers=2, n_kv_heads=3, layer0=7, head0=5), 160),
+    "cfg3_slice": (lambda: synth.workload(3).sliced(n_layers=1, n_seqs=3, n_kv_heads=2, layer0=3, seq0=11, head0=9), 64),
+    "cfg4_slice": (lambda: synth.workload(4).sliced(n_layers=1, n_seqs=2, n_kv_heads=2, layer0=30, seq0=3, head0=6), 96),
     # the paper's recommended residual share (dense ratio 0.02 of B - B_p: 27 slots at B = 2700) on workload 2's shape
     "cfg2_slice_27_residual": (lambda: synth.workload(2).sliced(n_layers=1, n_kv_heads=2, layer0=11, head0=20, n_residual=27), 24),
     # a batch of prompts between 0 and 5 tokens long (three of the eight are empty), then enough steps to fill
