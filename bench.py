@@ -54,6 +54,25 @@ def read_traffic_from_profiles(name: str):
     return float(m.group(1)) if m else None
 
 
+def device_info():
+    """Name, compute units and (via rocm-smi, when it answers) performance level and memory clock."""
+    import subprocess
+    import torch
+    p = torch.cuda.get_device_properties(0)
+    info = {"name": p.name, "compute_units": p.multi_processor_count, "memory_GiB": round(p.total_memory / 2 ** 30, 1)}
+    try:
+        out = subprocess.run(["rocm-smi", "--showperflevel", "--showclocks"], capture_output=True, text=True, timeout=15).stdout
+        m = re.search(r"Performance Level:\s*(\w+)", out)
+        if m:
+            info["perf_level"] = m.group(1)
+        m = re.search(r"mclk clock level:\s*\d+:\s*\((\d+)Mhz\)", out)
+        if m:
+            info["mclk_MHz"] = int(m.group(1))
+    except Exception:
+        pass
+    return info
+
+
 def cpu_baseline(wl, n_units: int, n_steps: int):
     """The CPU oracle, as it stands, on a bounded sample of the same workload: `n_units`
     units (layer 0, heads 0..) through their own prefill, then `n_steps` timed decode steps."""
@@ -138,8 +157,9 @@ def main():
         wl = wl.sliced(n_residual=args.n_residual)
     if args.window is not None:
         wl = wl.sliced(window=args.window)
-    if wl.ragged is not None:
-        print("bench.py: ragged workloads are parity-test cases, not bench lines", file=sys.stderr)
+    if wl.ragged is not None and not args.skip_prefill:
+        print("bench.py: a ragged workload is a parity-test case; its decode step can be timed with --skip-prefill "
+              "(slots filled by import, inputs of all sequences drawn at the same positions)", file=sys.stderr)
         sys.exit(2)
     L, S, H, G, d = wl.n_layers, wl.n_seqs, wl.n_kv_heads, wl.q_per_kv, wl.head_dim
     bp, bc, br = wl.budgets()
@@ -166,21 +186,26 @@ def main():
         cache.release_workspace()
     else:
         # every slot filled with synthetic rows: the decode kernel's traffic does not depend on how
+        # (a sequence with a smaller budget fills its own B_p + B_c token slots; the rest stay empty)
+        n = wl.slot_capacity - br
+        ntok_b = torch.tensor([p + c for p, c in zip(bp, bc)], dtype=torch.int32, device=dev)
+        occ = torch.arange(n, dtype=torch.int32, device=dev)[None, :] < ntok_b[:, None]          # [S, n]
+        lens_b = torch.tensor(wl.seq_lens(), dtype=torch.int64, device=dev)
         for l in range(L):
-            K, V = synth.kv_rows(wl, l, torch.arange(wl.slot_capacity - br), device=dev)
-            n = wl.slot_capacity - br
+            K, V = synth.kv_rows(wl, l, torch.arange(n), device=dev)
             pos = torch.full((S, H, wl.slot_capacity), -1, dtype=torch.int32, device=dev)
-            pos[..., br:] = torch.arange(n, dtype=torch.int32, device=dev) + (wl.prompt_len - n)
+            pos_tok = (lens_b[:, None] - ntok_b[:, None] + torch.arange(n, device=dev)[None, :]).to(torch.int32)   # latest tokens
+            pos[..., br:] = torch.where(occ, pos_tok, torch.full_like(pos_tok, -1))[:, None, :]
             w = torch.zeros(S, H, wl.slot_capacity, dtype=torch.int32, device=dev)
-            w[..., br:] = 1
+            w[..., br:] = occ[:, None, :].to(torch.int32)
             s = torch.rand(S, H, wl.slot_capacity, device=dev) * 0.01
-            cache.import_layer(l, K=K, V=V, s=s, pos=pos, w=w,
-                               n_seen=torch.full((S, H), wl.prompt_len, dtype=torch.int64, device=dev))
+            cache.import_layer(l, K=K, V=V, s=s, pos=pos, w=w, n_seen=lens_b[:, None].expand(S, H).contiguous())
+            del K, V
     torch.cuda.empty_cache()
 
     # ---- decode inputs for all steps, resident before the timed region -------------------
     n_total = args.warmup + args.steps
-    q_all, k_all, v_all = synth.decode_inputs_uniform(wl, list(range(L)), list(range(n_total)), device=dev)
+    q_all, k_all, v_all = synth.decode_inputs_uniform(wl.sliced(ragged=None), list(range(L)), list(range(n_total)), device=dev)
     out = torch.empty(L, S, H, G, d, dtype=torch.float32, device=dev)
     info = tuple(torch.empty(L, S, H, dtype=torch.int32, device=dev) for _ in range(3))
     torch.cuda.synchronize()
@@ -214,8 +239,8 @@ def main():
     units = wl.n_units
     value = units * args.steps / wall
 
-    bytes_unit = algorithmic_bytes_per_unit_step(bp[0] + bc[0], br, d, e, G)
-    bytes_launch = bytes_unit * units / ((L + lpl - 1) // lpl)
+    bytes_step = sum(algorithmic_bytes_per_unit_step(p + c, br, d, e, G) for p, c in zip(bp, bc)) * L * H   # all units
+    bytes_launch = bytes_step / ((L + lpl - 1) // lpl)
     achieved = bytes_launch / (kernel_ms * 1e-3) / 1e9
     traffic = read_traffic_from_profiles(f"decode_step_cfg{args.workload}_pmc.md")
 
@@ -240,7 +265,9 @@ def main():
         "dtype": wl.dtype, "data": "synthetic",
         "config": {"workload": f"cfg{args.workload} {wl.name}: {L} layers x {S} seq x {H} KV heads = {units} units, G={G}, d={d}, "
                                f"{wl.dtype} KV, prompt {wl.prompt_len} tokens -> B={wl.slot_capacity} slots "
-                               f"(B_p={bp[0]}, B_c={bc[0]}, B_r={br}), "
+                               + (f"(B_p={bp[0]}, B_c={bc[0]}, B_r={br}), " if wl.ragged is None else
+                                  f"at most (prompts of {min(wl.seq_lens())}..{max(wl.seq_lens())} tokens, B = {min(p + c for p, c in zip(bp, bc)) + br}.."
+                                  f"{max(p + c for p, c in zip(bp, bc)) + br} per sequence, B_r={br}), ")
                                + ("all layers in one launch" if lpl >= L else f"{lpl} layer(s) per launch")
                                + (f", {parts} workgroups per unit" if parts > 1 else ", one workgroup per unit"),
                    "units": units, "slots_per_unit": wl.slot_capacity},
@@ -253,6 +280,7 @@ def main():
         "prefill_compress_ms_all_layers": prefill_ms,
         "prefill_window": (wl.window if wl.window > 0 else wl.prompt_len),
         "setup_s": setup_s,
+        "device": device_info(),
     }
     if args.pmc_calibration:
         src = torch.ones(1 << 30, dtype=torch.uint8, device=dev)
