@@ -694,11 +694,30 @@ __global__ __launch_bounds__(256) void pf_residual_final(PrefillArgs a, PrefillW
 //   * the prompt is walked in blocks of 16 positions whose K and V rows and keep flags are
 //     requested a block ahead (registers) and staged in LDS, so no step waits for memory;
 //   * a residual key's dot product is split over LPS = 1, 2 or 4 lanes (64 / the power of two
-//     above B_r), each with four independent fp64 accumulators;
+//     above B_r), each with four independent fp64 accumulators; the arg-max over the keys is a
+//     DPP reduction inside 16-lane rows plus scalar reads of the row winners;
 //   * keys and values live in LDS in their fp32 storage form and are rounded to it after every
 //     merge (so the next choice sees what the stored state would give).
 constexpr int PF_RMAX = 64;   // residual slots the wave can own
 constexpr int PF_GB = 16;     // positions per staged block
+
+// Arg-max of (value, index) over the lanes of each 16-lane row by four DPP exchanges (lane pairs
+// i^1, i^2, i <-> 7-i, i <-> 15-i: after them every lane of a row holds the row's winner), ties to
+// the lower index; no LDS round trip and no compare chain.
+template <int CTRL>
+__device__ __forceinline__ void dpp_argmax_step(double& v, int& idx) {
+    const int lo = __builtin_amdgcn_update_dpp(0, __double2loint(v), CTRL, 0xf, 0xf, false);
+    const int hi = __builtin_amdgcn_update_dpp(0, __double2hiint(v), CTRL, 0xf, 0xf, false);
+    const int i2 = __builtin_amdgcn_update_dpp(0, idx, CTRL, 0xf, 0xf, false);
+    const double v2 = __hiloint2double(hi, lo);
+    if (v2 > v || (v2 == v && i2 < idx)) { v = v2; idx = i2; }
+}
+__device__ __forceinline__ void row_argmax(double& v, int& idx) {
+    dpp_argmax_step<0xB1>(v, idx);    // quad_perm [1,0,3,2]
+    dpp_argmax_step<0x4E>(v, idx);    // quad_perm [2,3,0,1]
+    dpp_argmax_step<0x141>(v, idx);   // row_half_mirror
+    dpp_argmax_step<0x140>(v, idx);   // row_mirror
+}
 
 template <typename T, int D, int LPS>
 __global__ __launch_bounds__(64) void pf_residual_greedy(PrefillArgs a, PrefillWs ws) {
@@ -719,8 +738,7 @@ __global__ __launch_bounds__(64) void pf_residual_greedy(PrefillArgs a, PrefillW
     float* Krs = reinterpret_cast<float*>(smem);            // [Br][RS]
     float* Vrs = Krs + (size_t)Br * RS;                      // [Br][RS]
     double* ktok = reinterpret_cast<double*>(Vrs + (size_t)Br * RS);   // [D]
-    double* dots = ktok + D;                                 // [PF_RMAX] the keys' dot products with the token
-    int* wcs = reinterpret_cast<int*>(dots + PF_RMAX);       // [PF_RMAX] fusion counts
+    int* wcs = reinterpret_cast<int*>(ktok + D);             // [PF_RMAX] fusion counts
     T* Kst = reinterpret_cast<T*>(wcs + PF_RMAX);            // [PF_GB][D] staged rows of the current block
     T* Vst = Kst + PF_GB * D;
     float* s = cv.s + (size_t)ug * cv.cap;
@@ -741,7 +759,7 @@ __global__ __launch_bounds__(64) void pf_residual_greedy(PrefillArgs a, PrefillW
     const int cbeg = h_own * CH;
 
     for (int i = lane; i < Br * RS; i += 64) { Krs[i] = 0.f; Vrs[i] = 0.f; }
-    for (int i = lane; i < PF_RMAX; i += 64) { wcs[i] = 0; dots[i] = -INFINITY; }
+    for (int i = lane; i < PF_RMAX; i += 64) wcs[i] = 0;
     int n_open = 0;        // residual slots opened so far (wave-uniform)
 
     // a block's rows and flags, requested one block ahead
@@ -816,23 +834,27 @@ __global__ __launch_bounds__(64) void pf_residual_greedy(PrefillArgs a, PrefillW
                 }
                 dot = (p0_ + p1_) + (p2_ + p3_);
             }
-            // the shares of one key meet (lanes r, r + NS, ...); the keys' dot products go to LDS and
-            // every lane finds the largest one itself (lowest index on ties): one LDS round trip
-            // instead of a chain of shuffles
+            // the shares of one key meet (lanes r, r + NS, ...); then the arg-max over the keys: lanes
+            // 0 .. NS-1 hold one key's dot product each (-inf past B_r), rows of 16 lanes reduce by DPP,
+            // the row winners meet through scalar reads
 #pragma unroll
             for (int o = NS * (LPS >> 1); o >= NS; o >>= 1) dot += __shfl_xor(dot, o, 64);
-            if (lane < Br) dots[lane] = dot;
-            wave_sync();
-            double dv[NS];   // all NS entries are read at once (entries >= B_r hold -inf)
+            double dv = lane < Br ? dot : -INFINITY;
+            int rbest = lane;
+            row_argmax(dv, rbest);
 #pragma unroll
-            for (int r = 0; r < NS; ++r) dv[r] = dots[r];
-            int rbest = 0;
-            double dbest = dv[0];
-#pragma unroll
-            for (int r = 1; r < NS; ++r)
-                if (dv[r] > dbest) { dbest = dv[r]; rbest = r; }
+            for (int row = 1; row < NS / 16; ++row) {
+                const double d2 = __hiloint2double(__builtin_amdgcn_readlane(__double2hiint(dv), 16 * row),
+                                                   __builtin_amdgcn_readlane(__double2loint(dv), 16 * row));
+                const int r2 = __builtin_amdgcn_readlane(rbest, 16 * row);
+                const double d0 = __hiloint2double(__builtin_amdgcn_readlane(__double2hiint(dv), 0),
+                                                   __builtin_amdgcn_readlane(__double2loint(dv), 0));
+                const int r0 = __builtin_amdgcn_readlane(rbest, 0);
+                // row 0 accumulates the winner (its indices are lower: a tie stays with it)
+                const bool take = d2 > d0;
+                if (lane < 16) { dv = take ? d2 : dv; rbest = take ? r2 : rbest; }
+            }
             rbest = __builtin_amdgcn_readfirstlane(rbest);
-            // Eq. 6 on the chosen slot, rounded to the fp32 storage form
             const int wi = wcs[rbest];
             const double wd = (double)wi;
 #pragma unroll
@@ -890,7 +912,7 @@ hipError_t launch_prefill_td(const PrefillArgs& a, hipStream_t st) {
         hipLaunchKernelGGL((pf_residual_partial<T, D>), dim3(ws.nchunks, a.n_units), dim3(256), 0, st, a, ws);
         hipLaunchKernelGGL((pf_residual_final<D>), dim3(a.n_units), dim3(256), 0, st, a, ws);
     } else if (cv.Br > 1) {
-        const size_t lds = sizeof(float) * 2 * (size_t)cv.Br * (D + 4) + sizeof(double) * (D + PF_RMAX) + sizeof(int) * PF_RMAX +
+        const size_t lds = sizeof(float) * 2 * (size_t)cv.Br * (D + 4) + sizeof(double) * D + sizeof(int) * PF_RMAX +
                            2 * PF_GB * D * sizeof(T);
         // lanes per residual key: 64 / the power of two above B_r, at most 4
         void (*kern)(PrefillArgs, PrefillWs) = cv.Br > 32 ? pf_residual_greedy<T, D, 1>
