@@ -281,3 +281,32 @@ def test_workload2_full_size_sampled_units():
         n_seen = cache.export_layer(l)["n_seen"]
         assert (n_seen == wl.prompt_len + 8).all()
     cache.close()
+
+
+@pytest.mark.parametrize("w,sample", [(3, [(0, 0, 0), (0, 17, 9), (0, 40, 31), (0, 63, 12)]),
+                                      (4, [(0, 0, 0), (0, 7, 3), (0, 15, 7)])])
+def test_full_layer_sampled_units(w, sample):
+    """One whole layer of the batched workloads (workload 3: 64 ragged sequences x 32 heads = 2048 units; workload 4:
+    16 sequences x 8 KV heads x 4 query heads) at full per-layer size: prefill and decode on the device, a sample of
+    units recomputed by the oracle from the bytes the device read; every unit's token count checked."""
+    wl = synth.workload(w).sliced(n_layers=1, layer0=5)
+    print(f"[case] workload {w}, one full layer ({wl.n_units} units), sampled units {sample}", flush=True)
+    cache = pu.make_cache(wl, DEV)
+    Q, K, V, lens = synth.prompt(wl, 0, device=DEV)
+    cache.prefill_compress(0, Q, K, V, lens)
+    torch.cuda.synchronize()
+    pairs = [(b, h) for (_, b, h) in sample]
+    units = [pu.oracle_prefill_layer(wl, Q, K, V, lens, sel=pairs)]
+    del Q, K, V
+    cache.release_workspace()
+    pu.compare_all_state(wl, cache, units, pu.tol_for(wl.dtype), "after prefill", sample)
+    st0 = cache.export_layer(0)
+    assert (st0["w"].sum(-1).cpu() == torch.tensor(lens)[:, None]).all()      # merged-slot weights sum to tokens seen
+    print("[step] prefill parity ok on the sampled units", flush=True)
+    st = pu.run_decode_parity(wl, cache, units, 6, sel=sample, gen_device=DEV)
+    print(f"[done] workload {w} full layer: unit-steps={st.unit_steps} evictions={st.evictions} near_ties={st.near_ties} "
+          f"max|out err|={st.max_out_err:.2e} scores bit-equal {st.s_bit_equal}/{st.s_total}", flush=True)
+    assert st.evictions == st.unit_steps
+    n_seen = cache.export_layer(0)["n_seen"].cpu()
+    assert (n_seen == torch.tensor(lens)[:, None] + 6).all()
+    cache.close()
