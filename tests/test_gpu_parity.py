@@ -310,3 +310,62 @@ def test_full_layer_sampled_units(w, sample):
     n_seen = cache.export_layer(0)["n_seen"].cpu()
     assert (n_seen == torch.tensor(lens)[:, None] + 6).all()
     cache.close()
+
+
+def test_decode_steps_replayed_from_a_hip_graph():
+    """Per-layer decode calls (split over workgroups) captured once in a HIP graph and replayed with new inputs:
+    every replay must give what the same calls give eagerly on a twin cache (the calls only enqueue kernels: no
+    allocation, no memset, no synchronisation)."""
+    from paper_2503_10714_amd import binding as zb
+    wl = small("graph", n_layers=3, n_kv_heads=4, dtype="f16", head_dim=128, prompt_len=700, budget=300, decode_steps=6,
+               window=16, outliers=True)
+    units = oracle_states(wl)
+    caches = [pu.make_cache(wl, DEV) for _ in range(2)]
+    for c in caches:
+        c.set_decode_parts(3)
+        for l in range(wl.n_layers):
+            c.import_layer(l, **pu.pack_states(units[l], c.cap, c.B_r, wl.head_dim, c.kv_dtype))
+    eager, graphed = caches
+    L, S, H, G, d = wl.n_layers, wl.n_seqs, wl.n_kv_heads, wl.q_per_kv, wl.head_dim
+    q = torch.zeros(L, S, H, G, d, dtype=torch.float16, device=DEV)
+    k = torch.zeros(L, S, H, d, dtype=torch.float16, device=DEV)
+    v = torch.zeros_like(k)
+    out_g = torch.zeros(L, S, H, G, d, dtype=torch.float32, device=DEV)
+    info_g = tuple(torch.zeros(L, S, H, dtype=torch.int32, device=DEV) for _ in range(3))
+
+    def calls(cache, out, info):
+        for l in range(L):
+            zb.zsm_decode_step(cache.handle, l, l + 1, q[l:l + 1], k[l:l + 1], v[l:l + 1], out[l:l + 1],
+                               info[0][l:l + 1], info[1][l:l + 1], info[2][l:l + 1])
+
+    def load_inputs(step):
+        for l in range(L):
+            qq, kk, vv = synth.decode_inputs(wl, l, step, device=DEV)
+            q[l].copy_(qq); k[l].copy_(kk); v[l].copy_(vv)
+
+    # one eager step on both caches first (sets the kernels' attributes outside the capture)
+    load_inputs(0)
+    out_e = torch.zeros_like(out_g)
+    info_e = tuple(torch.zeros_like(t) for t in info_g)
+    calls(eager, out_e, info_e); calls(graphed, out_g, info_g)
+    torch.cuda.synchronize()
+    load_inputs(1)
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        calls(graphed, out_g, info_g)
+    # the capture itself runs nothing: the twin has to take step 1 eagerly before the replays are compared
+    for step in range(1, wl.decode_steps):
+        load_inputs(step)
+        torch.cuda.synchronize()
+        g.replay()
+        calls(eager, out_e, info_e)
+        torch.cuda.synchronize()
+        assert torch.equal(out_g, out_e), f"replay of step {step}: outputs differ"
+        for a_, b_ in zip(info_g, info_e):
+            assert torch.equal(a_, b_), f"replay of step {step}: decisions differ"
+    for l in range(L):
+        sg, se = graphed.export_layer(l), eager.export_layer(l)
+        for key in sg:
+            assert torch.equal(sg[key], se[key]), f"layer {l}: {key} differs after the replays"
+    for c in caches:
+        c.close()
