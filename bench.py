@@ -55,21 +55,23 @@ def read_traffic_from_profiles(name: str):
 
 
 def device_info():
-    """Name, compute units and (via rocm-smi, when it answers) performance level and memory clock."""
-    import subprocess
+    """Name, compute units and (from the driver's sysfs files, when readable) performance level and
+    memory clock.  Files only: a process that has touched the GPU starts no other program."""
+    import glob
     import torch
     p = torch.cuda.get_device_properties(0)
     info = {"name": p.name, "compute_units": p.multi_processor_count, "memory_GiB": round(p.total_memory / 2 ** 30, 1)}
-    try:
-        out = subprocess.run(["rocm-smi", "--showperflevel", "--showclocks"], capture_output=True, text=True, timeout=15).stdout
-        m = re.search(r"Performance Level:\s*(\w+)", out)
-        if m:
-            info["perf_level"] = m.group(1)
-        m = re.search(r"mclk clock level:\s*\d+:\s*\((\d+)Mhz\)", out)
+    for dev in sorted(glob.glob("/sys/class/drm/card[0-9]*/device")):
+        try:
+            level = open(os.path.join(dev, "power_dpm_force_performance_level")).read().strip()
+            mclk = open(os.path.join(dev, "pp_dpm_mclk")).read()
+        except OSError:
+            continue
+        info["perf_level"] = level
+        m = re.search(r"(\d+)\s*Mhz\s*\*", mclk, re.I)
         if m:
             info["mclk_MHz"] = int(m.group(1))
-    except Exception:
-        pass
+        break
     return info
 
 

@@ -171,22 +171,61 @@ __device__ __forceinline__ void k_compute(const Raw<KT, EPL>* kr, int row0, int 
 // there are fewer sums than lanes), so one exp per lane serves all heads at full width.
 constexpr int ilog2_c(int x) { return x <= 1 ? 0 : 1 + ilog2_c(x / 2); }
 
-template <int NV, int DD>
+// Lane numbering of that pass.  The two steps that move the most values should cross lane bits
+// 5 and 4, where the exchange is a register swap between the wave's halves or between
+// neighbouring 16-lane rows, so the two top bits of a lane's segment number come from lane bits
+// 5 and 4, the other segment bits from the lowest lane bits, and the row group from the bits in
+// between.  A wave-wide load still covers the same RPL whole rows, whatever lane reads which piece.
+template <int LPR>
+struct GqLane {
+    static constexpr int LB = ilog2_c(LPR), LOW = LB - 2;
+    static_assert(LB >= 2 && LB <= 5, "");
+    __device__ static int seg(int lane) { return (((lane >> 4) & 3) << LOW) | (lane & ((1 << LOW) - 1)); }
+    __device__ static int grp(int lane) { return (lane >> LOW) & (64 / LPR - 1); }
+    // the number tile_load() takes: row group * LPR + segment
+    __device__ static int as_row_major(int lane) { return grp(lane) * LPR + seg(lane); }
+};
+
+// a (kept by the lower lane of a pair, sent by the upper) and b (the reverse) -> own + received,
+// the pair being lanes l and l ^ 32 (FAR) or l and l ^ 16
+template <bool FAR>
+__device__ __forceinline__ double swap_add(double a, double b) {
+    const uint32_t al = (uint32_t)__double2loint(a), ah = (uint32_t)__double2hiint(a);
+    const uint32_t bl = (uint32_t)__double2loint(b), bh = (uint32_t)__double2hiint(b);
+    if constexpr (FAR) {
+        const auto lo = __builtin_amdgcn_permlane32_swap(al, bl, false, false);
+        const auto hi = __builtin_amdgcn_permlane32_swap(ah, bh, false, false);
+        return __hiloint2double((int)hi[0], (int)lo[0]) + __hiloint2double((int)hi[1], (int)lo[1]);
+    } else {
+        const auto lo = __builtin_amdgcn_permlane16_swap(al, bl, false, false);
+        const auto hi = __builtin_amdgcn_permlane16_swap(ah, bh, false, false);
+        return __hiloint2double((int)hi[0], (int)lo[0]) + __hiloint2double((int)hi[1], (int)lo[1]);
+    }
+}
+
+// DD: the segment bit of this step (LPR / 2 first); NV values per lane before it.
+template <int NV, int DD, int LPR>
 __device__ __forceinline__ void lane_group_reduce(double* pp, int seg) {
     if constexpr (DD >= 1) {
-        const bool hi = (seg & DD) != 0;
+        constexpr int DIST = DD == LPR / 2 ? 32 : (DD == LPR / 4 ? 16 : DD);   // lane distance of the pair
         if constexpr (NV > 1) {
             constexpr int H = NV / 2;
+            if constexpr (DIST >= 16) {
 #pragma unroll
-            for (int i = 0; i < H; ++i) {
-                const double keep = hi ? pp[i + H] : pp[i];
-                const double send = hi ? pp[i] : pp[i + H];
-                pp[i] = keep + __shfl_xor(send, DD, 64);
+                for (int i = 0; i < H; ++i) pp[i] = swap_add<DIST == 32>(pp[i], pp[i + H]);
+            } else {
+                const bool hi = (seg & DD) != 0;
+#pragma unroll
+                for (int i = 0; i < H; ++i) {
+                    const double keep = hi ? pp[i + H] : pp[i];
+                    const double send = hi ? pp[i] : pp[i + H];
+                    pp[i] = keep + __shfl_xor(send, DIST, 64);
+                }
             }
-            lane_group_reduce<H, DD / 2>(pp, seg);
+            lane_group_reduce<H, DD / 2, LPR>(pp, seg);
         } else {
-            pp[0] += __shfl_xor(pp[0], DD, 64);
-            lane_group_reduce<1, DD / 2>(pp, seg);
+            pp[0] += __shfl_xor(pp[0], DIST, 64);
+            lane_group_reduce<1, DD / 2, LPR>(pp, seg);
         }
     }
 }
@@ -212,7 +251,7 @@ __device__ __forceinline__ void k_compute_gq(const Raw<KT, EPL>* kr, int row0, i
                                              double* et, int Bz, int lane) {
     using Own = GqOwn<G, LPR>;
     constexpr int UH = Own::UH;
-    const int grp = lane / LPR, seg = lane % LPR;
+    const int grp = GqLane<LPR>::grp(lane), seg = GqLane<LPR>::seg(lane);   // kr was loaded in this numbering
     double pp[Own::V];
 #pragma unroll
     for (int g = 0; g < G; ++g) {
@@ -226,7 +265,7 @@ __device__ __forceinline__ void k_compute_gq(const Raw<KT, EPL>* kr, int row0, i
             pp[g * UH + u] = p;
         }
     }
-    lane_group_reduce<Own::V, LPR / 2>(pp, seg);
+    lane_group_reduce<Own::V, LPR / 2, LPR>(pp, seg);
     const int v0 = Own::first_value(seg);
     const int g_own = v0 / UH;
     if (Own::writes(seg)) {
@@ -270,6 +309,19 @@ __device__ __forceinline__ void v_compute(const Raw<KT, EPL>* vr, int row0, int 
                                           const double* rL, float (*acc)[EPL], const double* et, int Bz,
                                           int lane) {
     const int grp = lane / LPR;
+    if (row0 + UU * RPL <= nrows) {   // every row of the tile exists: no per-row test
+#pragma unroll
+        for (int u = 0; u < UU; ++u) {
+            const int r = row0 + u * RPL + grp;
+#pragma unroll
+            for (int g = 0; g < G; ++g) {
+                const float p = (float)(et[(size_t)g * Bz + zidx0 + r] * rL[g]);
+#pragma unroll
+                for (int e = 0; e < EPL; ++e) acc[g][e] = fmaf(p, vr[u].get(e), acc[g][e]);
+            }
+        }
+        return;
+    }
 #pragma unroll
     for (int u = 0; u < UU; ++u) {
         const int r = row0 + u * RPL + grp;
@@ -309,10 +361,10 @@ __device__ __forceinline__ void v_tile_masked(const KT* __restrict__ Vb, int row
 // then advance together instead of oldest-first, which keeps all of them streaming to the
 // end of the sweep.  `done` of `total` work items are finished.
 __device__ __forceinline__ void prio_from_progress(int done, int total) {
-    const int q = (4 * done) / (total > 0 ? total : 1);
-    if (q >= 3) __builtin_amdgcn_s_setprio(0);
-    else if (q == 2) __builtin_amdgcn_s_setprio(1);
-    else if (q == 1) __builtin_amdgcn_s_setprio(2);
+    const int d4 = 4 * done;   // quarter of the way = floor(4 * done / total), by comparisons (both are wave-uniform)
+    if (d4 >= 3 * total) __builtin_amdgcn_s_setprio(0);
+    else if (d4 >= 2 * total) __builtin_amdgcn_s_setprio(1);
+    else if (d4 >= total) __builtin_amdgcn_s_setprio(2);
     else __builtin_amdgcn_s_setprio(3);
 }
 
@@ -566,7 +618,7 @@ __device__ __forceinline__ void decode_finish(const DecodeArgs& a, const CacheVi
 //   boundary is what makes one workgroup's scratch visible to another: fences inside one
 //   kernel cost more here than the whole sweep of a small launch).
 template <typename T, int D, int G, int NW, bool SPLIT>
-__global__ __launch_bounds__(NW * 64, (G == 1 ? 4 : (G <= 4 ? 3 : 2))) void decode_kernel(DecodeArgs a) {
+__global__ __launch_bounds__(NW * 64, (G == 1 ? 4 : (G <= 2 ? 3 : 2))) void decode_kernel(DecodeArgs a) {
     using Sh = DecodeShape<T, D, G, NW>;
     constexpr int EPL = Sh::EPL, LPR = Sh::LPR, RPL = Sh::RPL, R = Sh::R, PART = Sh::PART, NT = Sh::NT, UT = Sh::UT;
     constexpr bool QLDS = Sh::QLDS;
@@ -577,7 +629,8 @@ __global__ __launch_bounds__(NW * 64, (G == 1 ? 4 : (G <= 4 ? 3 : 2))) void deco
     const int b = (ug / cv.H) % cv.S;
     const int Bp = cv.Bp[b], Bc = cv.Bc[b], Br = cv.Br;
     const int ntok = Bp + Bc, B = ntok + Br;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // uniform: loop counters and tile numbers stay in scalar registers
     const int grp = lane / LPR, seg = lane % LPR;
 
     // this workgroup's wave tiles [tb, te) = token rows [row_b, row_e)
@@ -615,7 +668,9 @@ __global__ __launch_bounds__(NW * 64, (G == 1 ? 4 : (G <= 4 ? 3 : 2))) void deco
     // the budgets (one workgroup per unit: tile `wave`); rows past the unit's budget exist up to
     // the slot stride and are discarded by the compute step.
     Raw<T, EPL> bufA[UT], bufB[UT];
-    if (!SPLIT) tile_load<T, UT, D, EPL, LPR, RPL>(bufA, Kt, wave * R, cv.cap_tok, lane);
+    // K tiles of the full-tile path: grouped queries read them in the lane numbering of their exchange
+    const int klane = G >= 2 ? GqLane<LPR>::as_row_major(lane) : lane;
+    if (!SPLIT) tile_load<T, UT, D, EPL, LPR, RPL>(bufA, Kt, wave * R, cv.cap_tok, klane);
     const T* qp = reinterpret_cast<const T*>(a.q) + (size_t)lu * G * D;
     const T* knew = reinterpret_cast<const T*>(a.k_new) + (size_t)lu * D;
     const T* vnew = reinterpret_cast<const T*>(a.v_new) + (size_t)lu * D;
@@ -660,7 +715,7 @@ __global__ __launch_bounds__(NW * 64, (G == 1 ? 4 : (G <= 4 ? 3 : 2))) void deco
     }
     double* part_w = part_s + wave * PART;
     // grouped queries: the head whose sums this lane finishes in full tiles, its reference, its total
-    const int g_own = GqOwn<G, LPR>::head(seg);
+    const int g_own = GqOwn<G, LPR>::head(GqLane<LPR>::seg(lane));
     double c_own = C[0], lsum_own = 0.0;
 #pragma unroll
     for (int g = 1; g < G; ++g) c_own = g == g_own ? C[g] : c_own;
@@ -670,11 +725,11 @@ __global__ __launch_bounds__(NW * 64, (G == 1 ? 4 : (G <= 4 ? 3 : 2))) void deco
     // of the wave's next tile (or of its first V tile) are in flight while it works on this one.
     if (full) {
         int t = tb + wave;
-        if (SPLIT && t < te) tile_load<T, UT, D, EPL, LPR, RPL>(bufA, Kt, t * R, ntok, lane);
+        if (SPLIT && t < te) tile_load<T, UT, D, EPL, LPR, RPL>(bufA, Kt, t * R, ntok, klane);
         while (t < te) {
             const int tn = t + NW;
             prio_from_progress(t - tb, 2 * (te - tb));
-            if (tn < te) tile_load<T, UT, D, EPL, LPR, RPL>(bufB, Kt, tn * R, ntok, lane);
+            if (tn < te) tile_load<T, UT, D, EPL, LPR, RPL>(bufB, Kt, tn * R, ntok, klane);
             else tile_load<T, UT, D, EPL, LPR, RPL>(bufB, Vt, (tb + wave) * R, ntok, lane);   // tb + wave < te here
             if constexpr (G >= 2)
                 k_compute_gq<T, D, G, EPL, LPR, RPL, QLDS>(bufA, t * R, row_e, zt, scale, qq, c_own, lsum_own, et, Bz, lane);
