@@ -49,7 +49,7 @@ struct DecodeShape {
     static constexpr int R = UT * RPL;           // rows per wave tile
     static constexpr int PART = UH * RPL * (LPR + 1);   // doubles of partial-dot staging per wave
     static constexpr int NT = NW * 64;
-    static constexpr bool QLDS = G > 1;          // queries live in LDS instead of registers
+    static constexpr bool QLDS = G > 4;          // queries live in LDS instead of registers (G * EPL doubles per lane)
     // one LDS region serves the partial-dot staging of pass 1 and, after pass 2, the waves' partial outputs
     static constexpr size_t STAGE_A = sizeof(double) * NW * PART, STAGE_B = sizeof(float) * NW * G * D;
     static constexpr size_t STAGE = STAGE_A > STAGE_B ? STAGE_A : STAGE_B;
@@ -184,6 +184,14 @@ struct GqLane {
     __device__ static int grp(int lane) { return (lane >> LOW) & (64 / LPR - 1); }
     // the number tile_load() takes: row group * LPR + segment
     __device__ static int as_row_major(int lane) { return grp(lane) * LPR + seg(lane); }
+    // sum over the LPR lanes of a row group, left in all of them
+    __device__ static double group_sum(double p) {
+#pragma unroll
+        for (int o = 1; o < (1 << LOW); o <<= 1) p += __shfl_xor(p, o, 64);
+        p += __shfl_xor(p, 16, 64);
+        p += __shfl_xor(p, 32, 64);
+        return p;
+    }
 };
 
 // a (kept by the lower lane of a pair, sent by the upper) and b (the reverse) -> own + received,
@@ -631,7 +639,12 @@ __global__ __launch_bounds__(NW * 64, (G == 1 ? 4 : (G <= 2 ? 3 : 2))) void deco
     const int ntok = Bp + Bc, B = ntok + Br;
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // uniform: loop counters and tile numbers stay in scalar registers
+    // Pass 1 of grouped queries numbers the lanes for its exchange (GqLane); every part of that pass
+    // (queries in registers, masked tiles, the reference logit) uses the same numbering.  Pass 2 and
+    // the output use the plain one.
+    const int klane = G >= 2 ? GqLane<LPR>::as_row_major(lane) : lane;
     const int grp = lane / LPR, seg = lane % LPR;
+    const int kseg = klane % LPR;
 
     // this workgroup's wave tiles [tb, te) = token rows [row_b, row_e)
     const int ntiles = (ntok + R - 1) / R;
@@ -668,8 +681,6 @@ __global__ __launch_bounds__(NW * 64, (G == 1 ? 4 : (G <= 2 ? 3 : 2))) void deco
     // the budgets (one workgroup per unit: tile `wave`); rows past the unit's budget exist up to
     // the slot stride and are discarded by the compute step.
     Raw<T, EPL> bufA[UT], bufB[UT];
-    // K tiles of the full-tile path: grouped queries read them in the lane numbering of their exchange
-    const int klane = G >= 2 ? GqLane<LPR>::as_row_major(lane) : lane;
     if (!SPLIT) tile_load<T, UT, D, EPL, LPR, RPL>(bufA, Kt, wave * R, cv.cap_tok, klane);
     const T* qp = reinterpret_cast<const T*>(a.q) + (size_t)lu * G * D;
     const T* knew = reinterpret_cast<const T*>(a.k_new) + (size_t)lu * D;
@@ -690,7 +701,7 @@ __global__ __launch_bounds__(NW * 64, (G == 1 ? 4 : (G <= 2 ? 3 : 2))) void deco
 #pragma unroll
         for (int g = 0; g < (QLDS ? 1 : G); ++g) {
             float qf[EPL];
-            load_seg<EPL>(qp + g * D + seg * EPL, qf);
+            load_seg<EPL>(qp + g * D + kseg * EPL, qf);
 #pragma unroll
             for (int e = 0; e < EPL; ++e) qq.r[g][e] = (double)qf[e];
         }
@@ -699,16 +710,20 @@ __global__ __launch_bounds__(NW * 64, (G == 1 ? 4 : (G <= 2 ? 3 : 2))) void deco
     double C[G], lsum[G];
     {
         float kf[EPL];
-        load_seg<EPL>(knew + seg * EPL, kf);
+        load_seg<EPL>(knew + kseg * EPL, kf);
 #pragma unroll
         for (int g = 0; g < G; ++g) {
             double qv[EPL];
-            qq.get(g, seg, D, qv);
+            qq.get(g, kseg, D, qv);
             double p = 0.0;
 #pragma unroll
             for (int e = 0; e < EPL; ++e) p = fma(qv[e], (double)kf[e], p);
+            if constexpr (G >= 2) {
+                p = GqLane<LPR>::group_sum(p);
+            } else {
 #pragma unroll
-            for (int o = 1; o < LPR; o <<= 1) p += __shfl_xor(p, o, 64);
+                for (int o = 1; o < LPR; o <<= 1) p += __shfl_xor(p, o, 64);
+            }
             C[g] = p * scale;
             lsum[g] = 0.0;
         }
@@ -731,6 +746,7 @@ __global__ __launch_bounds__(NW * 64, (G == 1 ? 4 : (G <= 2 ? 3 : 2))) void deco
             prio_from_progress(t - tb, 2 * (te - tb));
             if (tn < te) tile_load<T, UT, D, EPL, LPR, RPL>(bufB, Kt, tn * R, ntok, klane);
             else tile_load<T, UT, D, EPL, LPR, RPL>(bufB, Vt, (tb + wave) * R, ntok, lane);   // tb + wave < te here
+            if constexpr (G >= 2) __builtin_amdgcn_sched_barrier(0);   // the requests stay ahead of the tile's arithmetic
             if constexpr (G >= 2)
                 k_compute_gq<T, D, G, EPL, LPR, RPL, QLDS>(bufA, t * R, row_e, zt, scale, qq, c_own, lsum_own, et, Bz, lane);
             else
@@ -743,16 +759,16 @@ __global__ __launch_bounds__(NW * 64, (G == 1 ? 4 : (G <= 2 ? 3 : 2))) void deco
     } else {
         for (int r0 = row_b + wave * RPL; r0 < row_e; r0 += NW * RPL)
             k_tile_masked<T, 1, D, G, EPL, LPR, RPL, QLDS>(Kt, r0, row_e, zt, pos + Br, nullptr, alpha, scale, qq, C, lsum,
-                                                           et, Bz, part_w, lane);
+                                                           et, Bz, part_w, klane);
     }
     // residual slots (fp32 rows, log-count term) and the incoming token itself
     if (part == 0) {
         for (int t = wave; t * RPL < Br; t += NW)
             k_tile_masked<float, 1, D, G, EPL, LPR, RPL, QLDS>(Kr, t * RPL, Br, 0, nullptr, w, alpha, scale, qq, C, lsum,
-                                                               et, Bz, part_w, lane);
+                                                               et, Bz, part_w, klane);
         if (wave == NW - 1)
             k_tile_masked<T, 1, D, G, EPL, LPR, RPL, QLDS>(knew, 0, 1, znew, nullptr, nullptr, alpha, scale, qq, C, lsum,
-                                                           et, Bz, part_w, lane);
+                                                           et, Bz, part_w, klane);
     }
 #pragma unroll
     for (int g = 0; g < G; ++g) {
