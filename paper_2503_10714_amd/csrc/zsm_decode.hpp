@@ -49,7 +49,11 @@ struct DecodeShape {
     static constexpr int R = UT * RPL;           // rows per wave tile
     static constexpr int PART = UH * RPL * (LPR + 1);   // doubles of partial-dot staging per wave
     static constexpr int NT = NW * 64;
-    static constexpr bool QLDS = G > 4;          // queries live in LDS instead of registers (G * EPL doubles per lane)
+    // pass 1 of full tiles on the 4x4x4 fp64 matrix instruction: four query heads, 16 keys of 16 pieces each per tile
+    static constexpr bool MFMA4 = G == 4 && sizeof(T) == 2 && D == 128;
+    // queries live in LDS instead of registers (G * EPL doubles per lane); the matrix path keeps its own
+    // operand registers and leaves the LDS copy to the masked tiles
+    static constexpr bool QLDS = G > 4 || MFMA4;
     // one LDS region serves the partial-dot staging of pass 1 and, after pass 2, the waves' partial outputs
     static constexpr size_t STAGE_A = sizeof(double) * NW * PART, STAGE_B = sizeof(float) * NW * G * D;
     static constexpr size_t STAGE = STAGE_A > STAGE_B ? STAGE_A : STAGE_B;
@@ -286,6 +290,44 @@ __device__ __forceinline__ void k_compute_gq(const Raw<KT, EPL>* kr, int row0, i
                 et[(size_t)g_own * Bz + zidx0 + row] = ev;
             }
         }
+    }
+}
+
+// ---- pass 1 for four grouped query heads on the matrix cores (16-bit K, d = 128, full tiles) ----
+// v_mfma_f64_4x4x4 multiplies, in each of four blocks, a 4x4 A by a 4x4 B.  Lane l supplies
+// A[i = l % 4][k = l / 16] and B[k = l / 16][j = l % 4] of block (l / 4) % 4 and receives
+// D[i = l / 16][j = l % 4] of that block (checked on the device with one-hot operands).  With
+// i = query head, block and j = key (key l % 16 of the tile's 16) and k = one of four 16-byte
+// pieces of the row, lane l loads pieces l/16, 4 + l/16, 8 + l/16, 12 + l/16 of key row l % 16
+// (one per wave-wide load) and holds head l % 4's query values of the same pieces; the 32 steps
+// (4 loads x 8 elements) contract all 128 channels, and lane l ends up with the exact-product
+// fp64 logit of (head l / 16, key l % 16): no exchange between lanes, one exp per lane.
+template <typename KT, int UU, int D, int EPL>
+__device__ __forceinline__ void tile_load_mfma4(Raw<KT, EPL>* dst, const KT* __restrict__ base, int row0, int nrows, int lane) {
+    const int r = row0 + (lane & 15);
+    const KT* p = base + ((size_t)(r < nrows ? r : nrows - 1) * D + (lane >> 4) * EPL);
+#pragma unroll
+    for (int u = 0; u < UU; ++u) dst[u].load(p + u * 4 * EPL);
+}
+
+template <typename KT, int UU, int EPL>
+__device__ __forceinline__ void k_compute_mfma4(const Raw<KT, EPL>* kr, const double (*qa)[EPL], int row0, int nrows,
+                                                int zidx0, double scale, double c_own, double& lsum_own,
+                                                double* et_own, int lane) {
+    double d0 = 0.0, d1 = 0.0;   // two accumulators: consecutive steps do not wait for each other
+#pragma unroll
+    for (int u = 0; u < UU; ++u) {
+#pragma unroll
+        for (int e = 0; e < EPL; e += 2) {
+            d0 = __builtin_amdgcn_mfma_f64_4x4x4f64(qa[u][e], (double)kr[u].get(e), d0, 0, 0, 0);
+            d1 = __builtin_amdgcn_mfma_f64_4x4x4f64(qa[u][e + 1], (double)kr[u].get(e + 1), d1, 0, 0, 0);
+        }
+    }
+    const int row = row0 + (lane & 15);
+    if (row < nrows) {
+        const double ev = exp(fmin((d0 + d1) * scale - c_own, 690.0));
+        lsum_own += ev;
+        et_own[zidx0 + row] = ev;
     }
 }
 
@@ -642,7 +684,8 @@ __global__ __launch_bounds__(NW * 64, (G == 1 ? 4 : (G <= 2 ? 3 : 2))) void deco
     // Pass 1 of grouped queries numbers the lanes for its exchange (GqLane); every part of that pass
     // (queries in registers, masked tiles, the reference logit) uses the same numbering.  Pass 2 and
     // the output use the plain one.
-    const int klane = G >= 2 ? GqLane<LPR>::as_row_major(lane) : lane;
+    constexpr bool MF = Sh::MFMA4;
+    const int klane = (G >= 2 && !MF) ? GqLane<LPR>::as_row_major(lane) : lane;
     const int grp = lane / LPR, seg = lane % LPR;
     const int kseg = klane % LPR;
 
@@ -681,7 +724,10 @@ __global__ __launch_bounds__(NW * 64, (G == 1 ? 4 : (G <= 2 ? 3 : 2))) void deco
     // the budgets (one workgroup per unit: tile `wave`); rows past the unit's budget exist up to
     // the slot stride and are discarded by the compute step.
     Raw<T, EPL> bufA[UT], bufB[UT];
-    if (!SPLIT) tile_load<T, UT, D, EPL, LPR, RPL>(bufA, Kt, wave * R, cv.cap_tok, klane);
+    if (!SPLIT) {
+        if constexpr (MF) tile_load_mfma4<T, UT, D, EPL>(bufA, Kt, wave * R, cv.cap_tok, lane);
+        else tile_load<T, UT, D, EPL, LPR, RPL>(bufA, Kt, wave * R, cv.cap_tok, klane);
+    }
     const T* qp = reinterpret_cast<const T*>(a.q) + (size_t)lu * G * D;
     const T* knew = reinterpret_cast<const T*>(a.k_new) + (size_t)lu * D;
     const T* vnew = reinterpret_cast<const T*>(a.v_new) + (size_t)lu * D;
@@ -706,6 +752,17 @@ __global__ __launch_bounds__(NW * 64, (G == 1 ? 4 : (G <= 2 ? 3 : 2))) void deco
             for (int e = 0; e < EPL; ++e) qq.r[g][e] = (double)qf[e];
         }
     }
+    // matrix path: head lane % 4's query values at the pieces this lane loads of a key row
+    double qa[MF ? UT : 1][EPL];
+    if constexpr (MF) {
+#pragma unroll
+        for (int u = 0; u < UT; ++u) {
+            float qf[EPL];
+            load_seg<EPL>(qp + (lane & 3) * D + (4 * u + (lane >> 4)) * EPL, qf);
+#pragma unroll
+            for (int e = 0; e < EPL; ++e) qa[u][e] = (double)qf[e];
+        }
+    }
     // reference logit C[g]: the incoming token against itself (every lane of every wave)
     double C[G], lsum[G];
     {
@@ -718,7 +775,7 @@ __global__ __launch_bounds__(NW * 64, (G == 1 ? 4 : (G <= 2 ? 3 : 2))) void deco
             double p = 0.0;
 #pragma unroll
             for (int e = 0; e < EPL; ++e) p = fma(qv[e], (double)kf[e], p);
-            if constexpr (G >= 2) {
+            if constexpr (G >= 2 && !MF) {
                 p = GqLane<LPR>::group_sum(p);
             } else {
 #pragma unroll
@@ -730,7 +787,7 @@ __global__ __launch_bounds__(NW * 64, (G == 1 ? 4 : (G <= 2 ? 3 : 2))) void deco
     }
     double* part_w = part_s + wave * PART;
     // grouped queries: the head whose sums this lane finishes in full tiles, its reference, its total
-    const int g_own = GqOwn<G, LPR>::head(GqLane<LPR>::seg(lane));
+    const int g_own = MF ? lane >> 4 : GqOwn<G, LPR>::head(GqLane<LPR>::seg(lane));
     double c_own = C[0], lsum_own = 0.0;
 #pragma unroll
     for (int g = 1; g < G; ++g) c_own = g == g_own ? C[g] : c_own;
@@ -740,14 +797,23 @@ __global__ __launch_bounds__(NW * 64, (G == 1 ? 4 : (G <= 2 ? 3 : 2))) void deco
     // of the wave's next tile (or of its first V tile) are in flight while it works on this one.
     if (full) {
         int t = tb + wave;
-        if (SPLIT && t < te) tile_load<T, UT, D, EPL, LPR, RPL>(bufA, Kt, t * R, ntok, klane);
+        if (SPLIT && t < te) {
+            if constexpr (MF) tile_load_mfma4<T, UT, D, EPL>(bufA, Kt, t * R, ntok, lane);
+            else tile_load<T, UT, D, EPL, LPR, RPL>(bufA, Kt, t * R, ntok, klane);
+        }
         while (t < te) {
             const int tn = t + NW;
             prio_from_progress(t - tb, 2 * (te - tb));
-            if (tn < te) tile_load<T, UT, D, EPL, LPR, RPL>(bufB, Kt, tn * R, ntok, klane);
-            else tile_load<T, UT, D, EPL, LPR, RPL>(bufB, Vt, (tb + wave) * R, ntok, lane);   // tb + wave < te here
+            if (tn < te) {
+                if constexpr (MF) tile_load_mfma4<T, UT, D, EPL>(bufB, Kt, tn * R, ntok, lane);
+                else tile_load<T, UT, D, EPL, LPR, RPL>(bufB, Kt, tn * R, ntok, klane);
+            } else {
+                tile_load<T, UT, D, EPL, LPR, RPL>(bufB, Vt, (tb + wave) * R, ntok, lane);   // tb + wave < te here
+            }
             if constexpr (G >= 2) __builtin_amdgcn_sched_barrier(0);   // the requests stay ahead of the tile's arithmetic
-            if constexpr (G >= 2)
+            if constexpr (MF)
+                k_compute_mfma4<T, UT, EPL>(bufA, qa, t * R, row_e, zt, scale, c_own, lsum_own, et + (size_t)g_own * Bz, lane);
+            else if constexpr (G >= 2)
                 k_compute_gq<T, D, G, EPL, LPR, RPL, QLDS>(bufA, t * R, row_e, zt, scale, qq, c_own, lsum_own, et, Bz, lane);
             else
                 k_compute<T, UT, false, D, G, EPL, LPR, RPL, QLDS>(bufA, t * R, row_e, zt, nullptr, nullptr, alpha, scale, qq,

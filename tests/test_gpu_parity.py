@@ -25,6 +25,12 @@ DECODE_CASES = {
     "three_residual_f16": lambda: small("three_residual_f16", n_residual=3, dtype="f16", head_dim=128, outliers=True),
     "alpha_half_bf16_gqa4": lambda: small("alpha_half_bf16_gqa4", alpha=0.5, dtype="bf16", q_per_kv=4, head_dim=128,
                                          n_kv_heads=2, outliers=True, budget=70),
+    # four query heads, 16-bit keys, d = 128: full tiles go through the matrix cores; more tiles than waves, a ragged last one
+    "gqa4_f16_many_tiles": lambda: small("gqa4_f16_many_tiles", dtype="f16", q_per_kv=4, head_dim=128, n_kv_heads=3,
+                                         n_residual=3, prompt_len=400, budget=150, decode_steps=48, outliers=True),
+    # the same shape while the cache still fills up (masked tiles, queries read from LDS)
+    "gqa4_bf16_fills_up": lambda: small("gqa4_bf16_fills_up", dtype="bf16", q_per_kv=4, head_dim=128, prompt_len=30,
+                                        budget=64, decode_steps=60, window=8),
     "gqa2_d64_f16": lambda: small("gqa2_d64_f16", dtype="f16", q_per_kv=2),
     "gqa8_f32_d128": lambda: small("gqa8_f32_d128", q_per_kv=8, head_dim=128, budget=33, prompt_len=120),
     "fills_up": lambda: small("fills_up", prompt_len=20, budget=48, decode_steps=60, window=8),       # T < B: free slots first
@@ -71,7 +77,7 @@ def test_decode_from_oracle_state(case):
 
 # (case, workgroups per unit): the split step must give the oracle's decisions and outputs whatever the cut
 SPLIT_CASES = [("cfg1", 4), ("cfg1", 13), ("three_residual_f16", 2), ("alpha_half_bf16_gqa4", 3), ("gqa8_f32_d128", 2),
-               ("fills_up", 2), ("empty_start", 3), ("ragged_multi_layer", 5), ("evict_only", 3), ("cfg0", 3)]
+               ("fills_up", 2), ("gqa4_f16_many_tiles", 2), ("empty_start", 3), ("ragged_multi_layer", 5), ("evict_only", 3), ("cfg0", 3)]
 
 
 @pytest.mark.parametrize("case,parts", SPLIT_CASES)
