@@ -80,13 +80,16 @@ __global__ __launch_bounds__(64) void pf_self_logit(PrefillArgs a, PrefillWs ws)
 //         per (row, workgroup) to the workspace.
 // MODE 1: s_t = sum over rows of roww_i * exp(z_it - C_i)  (Eq. 3 unrolled over the window); with
 //         one 32-row pass per unit the score is written at once, otherwise the passes add into sacc.
+// MODE 2: MODE 0, and every exp(z_it - C_i) of a key that exists is stored at ev[t][row]; pf_score_from_ev
+//         then forms s_t from there and K is swept once instead of twice.
 typedef double d4_t __attribute__((ext_vector_type(4)));
 
 template <typename T, int D, int MODE>
 __global__ __launch_bounds__(256, 4) void pf_score_mfma(PrefillArgs a, PrefillWs ws, const double* __restrict__ Qd,
                                                         const double* __restrict__ rowm,
                                                         const double* __restrict__ roww, double* __restrict__ pl,
-                                                        double* __restrict__ sacc, float* __restrict__ sc) {
+                                                        double* __restrict__ sacc, float* __restrict__ sc,
+                                                        double* __restrict__ evs) {
     constexpr int EPL = 16 / sizeof(T);            // elements per 16-byte piece
     constexpr int NSTEP = D / 4;                   // matrix steps (4 channels each) per tile
     constexpr int NLD = NSTEP / EPL;               // 16-byte pieces per lane and key
@@ -102,7 +105,8 @@ __global__ __launch_bounds__(256, 4) void pf_score_mfma(PrefillArgs a, PrefillWs
     const int W = a.W, G = cv.G, Wp = ws.Wp;
     const int nb = W < Tb ? W : Tb;
     const int qpos0 = Tb - nb;                 // position of query row 0
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // uniform: tile numbers stay in scalar registers
     const int j = lane & 15, q = lane >> 4;
     const T* Kbase = reinterpret_cast<const T*>(a.K) + (size_t)lu * a.T_max * D;
     const double scale = cv.scale;
@@ -130,7 +134,7 @@ __global__ __launch_bounds__(256, 4) void pf_score_mfma(PrefillArgs a, PrefillWs
             // keys past the last row's position are in the future of every row of this pass
             const int kend = k1 < qpos0 + rlast + 1 ? k1 : qpos0 + rlast + 1;
             if (k0 >= kend) {
-                if (MODE == 0 && tid < PF_MR) pl[(rowbase + tid) * ws.nsums + chunk] = 0.0;
+                if (MODE != 1 && tid < PF_MR) pl[(rowbase + tid) * ws.nsums + chunk] = 0.0;
                 continue;
             }
             __syncthreads();   // the previous pass has finished reading Qs / rm / rw
@@ -200,6 +204,13 @@ __global__ __launch_bounds__(256, 4) void pf_score_mfma(PrefillArgs a, PrefillWs
                 double sp[KB];
 #pragma unroll
                 for (int kb = 0; kb < KB; ++kb) sp[kb] = 0.0;
+                // MODE 2: ev is [unit][key][G * Wp rows]; row 16*rb + 4*r of this lane sits a constant away from ep[kb]
+                double* ep[KB];
+                if (MODE == 2) {
+#pragma unroll
+                    for (int kb = 0; kb < KB; ++kb)
+                        ep[kb] = evs + ((size_t)lu * a.T_max + (t0 + 16 * kb + j)) * ((size_t)G * Wp) + (g * Wp + r0 + q);
+                }
 #pragma unroll
                 for (int rb = 0; rb < RB; ++rb) {
 #pragma unroll
@@ -213,8 +224,9 @@ __global__ __launch_bounds__(256, 4) void pf_score_mfma(PrefillArgs a, PrefillWs
                             const int t = t0 + 16 * kb + j;
                             const bool ok = valid && t <= qp;
                             const double ev = exp(fmin(acc[rb][kb][r] * scale - rmv, 690.0));
-                            if (MODE == 0) lsum[rb][r] += ok ? ev : 0.0;
+                            if (MODE != 1) lsum[rb][r] += ok ? ev : 0.0;
                             else sp[kb] += ok ? rwv * ev : 0.0;
+                            if (MODE == 2 && t < Tb) ep[kb][16 * rb + 4 * r] = ev;   // masked entries are never read back
                         }
                     }
                 }
@@ -233,7 +245,7 @@ __global__ __launch_bounds__(256, 4) void pf_score_mfma(PrefillArgs a, PrefillWs
                     }
                 }
             }
-            if (MODE == 0) {
+            if (MODE != 1) {
 #pragma unroll
                 for (int rb = 0; rb < RB; ++rb) {
 #pragma unroll
@@ -253,6 +265,56 @@ __global__ __launch_bounds__(256, 4) void pf_score_mfma(PrefillArgs a, PrefillWs
             }
         }
     }
+    }
+}
+
+// ---- P2 from the stored exponentials: s_t = sum over the window rows at or after t of roww_i * ev[t][i] ----
+// Sixteen lanes per key: a key's G * Wp exponentials are contiguous, each lane takes two of every 32
+// (one 16-byte load, the wave reads 1 KB in one piece) and the sixteen partial sums meet by shuffles.
+__global__ __launch_bounds__(256) void pf_score_from_ev(PrefillArgs a, PrefillWs ws, const double* __restrict__ roww,
+                                                        const double* __restrict__ evs, float* __restrict__ sc) {
+    const CacheView& cv = a.cv;
+    const int lu = blockIdx.y;
+    const int Tb = seq_len_of(a, lu / cv.H);
+    const int nb = a.W < Tb ? a.W : Tb;
+    const int qpos0 = Tb - nb;
+    const int Wp = ws.Wp;
+    const int rows = cv.G * Wp;                  // a multiple of 32
+    const double* rw = roww + (size_t)lu * rows;
+    const int sub = threadIdx.x & 15, kl = threadIdx.x >> 4;
+    constexpr int KU = 4;                        // keys per 16-lane group and round: that many loads in flight
+    for (int tb = blockIdx.x * 16 * KU; tb < Tb; tb += gridDim.x * 16 * KU) {
+        double v[KU];
+        int i0[KU];
+        const double2* e[KU];
+#pragma unroll
+        for (int u = 0; u < KU; ++u) {
+            const int t = tb + u * 16 + kl;
+            const int tc = t < Tb ? t : Tb - 1;
+            e[u] = reinterpret_cast<const double2*>(evs + ((size_t)lu * a.T_max + tc) * rows);
+            i0[u] = tc > qpos0 ? tc - qpos0 : 0;   // first row whose position is at or after key t (Eq. 1: keys up to the row's own)
+            v[u] = 0.0;
+        }
+        for (int c = 0; c < rows; c += 32) {
+            const int r = c + 2 * sub, i = r % Wp;    // rows r and r + 1 belong to the same head (Wp is even)
+            const double2 w = *reinterpret_cast<const double2*>(rw + r);
+            double2 x[KU];
+#pragma unroll
+            for (int u = 0; u < KU; ++u) x[u] = e[u][r >> 1];
+#pragma unroll
+            for (int u = 0; u < KU; ++u) {            // values outside the causal window were never written: not touched
+                if (i >= i0[u] && i < nb) v[u] = fma(w.x, x[u].x, v[u]);
+                if (i + 1 >= i0[u] && i + 1 < nb) v[u] = fma(w.y, x[u].y, v[u]);
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < KU; ++u) {
+            double s = v[u];
+#pragma unroll
+            for (int o = 8; o > 0; o >>= 1) s += shfl_xor_d(s, o);
+            const int t = tb + u * 16 + kl;
+            if (sub == 0 && t < Tb) sc[(size_t)lu * a.T_max + t] = (float)s;
+        }
     }
 }
 
@@ -897,11 +959,19 @@ hipError_t launch_prefill_td(const PrefillArgs& a, hipStream_t st) {
     double* pl = reinterpret_cast<double*>(a.ws + ws.pl);
     double* sacc = reinterpret_cast<double*>(a.ws + ws.sacc);
     float* sc = reinterpret_cast<float*>(a.ws + ws.sc);
-    hipLaunchKernelGGL((pf_score_mfma<T, D, 0>), gs, dim3(256), 0, st, a, ws, Qd, rowm, roww, pl, sacc, sc);
-    hipLaunchKernelGGL(pf_row_combine, dim3(a.n_units), dim3(256), 0, st, a, ws);
-    if (ws.multi) hipLaunchKernelGGL(pf_fill_f64, dim3(1024), dim3(256), 0, st, sacc, (size_t)ws.rz * a.n_units * a.T_max, 0.0);
-    hipLaunchKernelGGL((pf_score_mfma<T, D, 1>), gs, dim3(256), 0, st, a, ws, Qd, rowm, roww, pl, sacc, sc);
-    if (ws.multi) hipLaunchKernelGGL(pf_sacc_to_sc, dim3((a.T_max + 255) / 256, a.n_units), dim3(256), 0, st, a, sacc, ws.rz, sc);
+    double* evs = reinterpret_cast<double*>(a.ws + ws.ev);
+    if (ws.store_e) {
+        hipLaunchKernelGGL((pf_score_mfma<T, D, 2>), gs, dim3(256), 0, st, a, ws, Qd, rowm, roww, pl, sacc, sc, evs);
+        hipLaunchKernelGGL(pf_row_combine, dim3(a.n_units), dim3(256), 0, st, a, ws);
+        const int tb16 = (a.T_max + 63) / 64;
+        hipLaunchKernelGGL(pf_score_from_ev, dim3(tb16 < 2048 ? tb16 : 2048, a.n_units), dim3(256), 0, st, a, ws, roww, evs, sc);
+    } else {
+        hipLaunchKernelGGL((pf_score_mfma<T, D, 0>), gs, dim3(256), 0, st, a, ws, Qd, rowm, roww, pl, sacc, sc, evs);
+        hipLaunchKernelGGL(pf_row_combine, dim3(a.n_units), dim3(256), 0, st, a, ws);
+        if (ws.multi) hipLaunchKernelGGL(pf_fill_f64, dim3(1024), dim3(256), 0, st, sacc, (size_t)ws.rz * a.n_units * a.T_max, 0.0);
+        hipLaunchKernelGGL((pf_score_mfma<T, D, 1>), gs, dim3(256), 0, st, a, ws, Qd, rowm, roww, pl, sacc, sc, evs);
+        if (ws.multi) hipLaunchKernelGGL(pf_sacc_to_sc, dim3((a.T_max + 255) / 256, a.n_units), dim3(256), 0, st, a, sacc, ws.rz, sc);
+    }
     if (a.T_max <= SEL_NT * SEL_NPT) hipLaunchKernelGGL(pf_select_reg, dim3(a.n_units), dim3(SEL_NT), 0, st, a, ws);
     else hipLaunchKernelGGL(pf_select, dim3(a.n_units), dim3(SEL_NT), 0, st, a, ws);
     constexpr int EPL = 16 / sizeof(T), LPR = D / EPL, RPB = 256 / LPR;

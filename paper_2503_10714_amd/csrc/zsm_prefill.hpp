@@ -25,12 +25,17 @@ constexpr int PF_SCORE_WGS = 1024;   // scoring launches aim at this many workgr
 constexpr int PF_RC = 1024;    // prompt positions per workgroup in the residual sum
 
 struct PrefillWs {
-    size_t Qd, pl, rowm, roww, sc, sacc, keep, kept_pos, sel, rsum, total;
+    size_t Qd, pl, rowm, roww, sc, sacc, ev, keep, kept_pos, sel, rsum, total;
     int Wp, nsums, chunk_keys, nchunks;   // nsums key ranges of chunk_keys keys per unit in the scoring kernels
     int multi;                            // more than one (query head, 32-row block) per unit: scores pass through sacc
     int rz;                               // groups the passes of a unit are dealt to (grid.z of the scoring launches)
     int fold;                             // a workgroup takes key ranges x and nsums-1-x
+    int store_e;                          // the first sweep keeps every exp(z - C) (ev), the scores are summed from there
 };
+
+// The exponentials of the first scoring sweep are kept, and the second sweep of K replaced by a
+// weighted column sum over them, when they fit this many bytes (fp64, rows x T_max per unit).
+constexpr size_t PF_EV_MAX = (size_t)1 << 30;
 
 inline PrefillWs prefill_ws_layout(const CacheView& cv, int T_max, int W) {
     PrefillWs w{};
@@ -62,7 +67,12 @@ inline PrefillWs prefill_ws_layout(const CacheView& cv, int T_max, int W) {
     w.rowm = o; o += up(sizeof(double) * units * cv.G * w.Wp);
     w.roww = o; o += up(sizeof(double) * units * cv.G * w.Wp);
     w.sc = o; o += up(sizeof(float) * units * T_max);
-    w.sacc = o; o += up(w.multi ? sizeof(double) * w.rz * units * T_max : 0);   // [rz][units][T_max]
+    {
+        const size_t evb = sizeof(double) * units * cv.G * w.Wp * (size_t)T_max;     // [units][G][Wp][T_max]
+        w.store_e = !w.fold && evb <= PF_EV_MAX;
+        w.ev = o; o += up(w.store_e ? evb : 0);
+    }
+    w.sacc = o; o += up(w.multi && !w.store_e ? sizeof(double) * w.rz * units * T_max : 0);   // [rz][units][T_max]
     w.keep = o; o += up(units * (size_t)T_max);
     w.kept_pos = o; o += up(sizeof(int32_t) * units * (cv.cap_tok > 0 ? cv.cap_tok : 1));
     w.sel = o; o += up(sizeof(int32_t) * units * 4);
