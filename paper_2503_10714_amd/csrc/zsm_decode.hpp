@@ -50,7 +50,7 @@ struct DecodeShape {
     static constexpr int PART = UH * RPL * (LPR + 1);   // doubles of partial-dot staging per wave
     static constexpr int NT = NW * 64;
     // pass 1 of full tiles on the 4x4x4 fp64 matrix instruction: four query heads, 16 keys of 16 pieces each per tile
-    static constexpr bool MFMA4 = G == 4 && sizeof(T) == 2 && D == 128;
+    static constexpr bool MFMA4 = (G == 4 || G == 8) && sizeof(T) == 2 && D == 128;   // G / 4 groups of four heads
     // queries live in LDS instead of registers (G * EPL doubles per lane); the matrix path keeps its own
     // operand registers and leaves the LDS copy to the masked tiles
     static constexpr bool QLDS = G > 4 || MFMA4;
@@ -310,24 +310,34 @@ __device__ __forceinline__ void tile_load_mfma4(Raw<KT, EPL>* dst, const KT* __r
     for (int u = 0; u < UU; ++u) dst[u].load(p + u * 4 * EPL);
 }
 
-template <typename KT, int UU, int EPL>
-__device__ __forceinline__ void k_compute_mfma4(const Raw<KT, EPL>* kr, const double (*qa)[EPL], int row0, int nrows,
-                                                int zidx0, double scale, double c_own, double& lsum_own,
-                                                double* et_own, int lane) {
-    double d0 = 0.0, d1 = 0.0;   // two accumulators: consecutive steps do not wait for each other
+// NG groups of four heads (G = 4 * NG): group h uses qa[h] and gives lane l head 4h + l / 16.
+template <typename KT, int UU, int EPL, int NG>
+__device__ __forceinline__ void k_compute_mfma4(const Raw<KT, EPL>* kr, const double (*qa)[UU][EPL], int row0, int nrows,
+                                                int zidx0, double scale, const double* c_own, double* lsum_own,
+                                                double* et_own, int Bz, int lane) {
+    double d0[NG], d1[NG];   // two accumulators per group: consecutive steps do not wait for each other
+#pragma unroll
+    for (int h = 0; h < NG; ++h) d0[h] = d1[h] = 0.0;
 #pragma unroll
     for (int u = 0; u < UU; ++u) {
 #pragma unroll
         for (int e = 0; e < EPL; e += 2) {
-            d0 = __builtin_amdgcn_mfma_f64_4x4x4f64(qa[u][e], (double)kr[u].get(e), d0, 0, 0, 0);
-            d1 = __builtin_amdgcn_mfma_f64_4x4x4f64(qa[u][e + 1], (double)kr[u].get(e + 1), d1, 0, 0, 0);
+            const double b0 = (double)kr[u].get(e), b1 = (double)kr[u].get(e + 1);
+#pragma unroll
+            for (int h = 0; h < NG; ++h) {
+                d0[h] = __builtin_amdgcn_mfma_f64_4x4x4f64(qa[h][u][e], b0, d0[h], 0, 0, 0);
+                d1[h] = __builtin_amdgcn_mfma_f64_4x4x4f64(qa[h][u][e + 1], b1, d1[h], 0, 0, 0);
+            }
         }
     }
     const int row = row0 + (lane & 15);
     if (row < nrows) {
-        const double ev = exp(fmin((d0 + d1) * scale - c_own, 690.0));
-        lsum_own += ev;
-        et_own[zidx0 + row] = ev;
+#pragma unroll
+        for (int h = 0; h < NG; ++h) {
+            const double ev = exp(fmin((d0[h] + d1[h]) * scale - c_own[h], 690.0));
+            lsum_own[h] += ev;
+            et_own[(size_t)4 * h * Bz + zidx0 + row] = ev;   // et_own = et + (lane / 16) * Bz
+        }
     }
 }
 
@@ -753,15 +763,18 @@ __global__ __launch_bounds__(NW * 64, (G == 1 ? 4 : (G <= 2 ? 3 : 2))) void deco
         }
     }
     // matrix path: head lane % 4's query values at the pieces this lane loads of a key row
-    double qa[MF ? UT : 1][EPL];
+    constexpr int NG = MF ? G / 4 : 1;
+    double qa[NG][MF ? UT : 1][EPL];
     if constexpr (MF) {
 #pragma unroll
-        for (int u = 0; u < UT; ++u) {
-            float qf[EPL];
-            load_seg<EPL>(qp + (lane & 3) * D + (4 * u + (lane >> 4)) * EPL, qf);
+        for (int h = 0; h < NG; ++h)
 #pragma unroll
-            for (int e = 0; e < EPL; ++e) qa[u][e] = (double)qf[e];
-        }
+            for (int u = 0; u < UT; ++u) {
+                float qf[EPL];
+                load_seg<EPL>(qp + (4 * h + (lane & 3)) * D + (4 * u + (lane >> 4)) * EPL, qf);
+#pragma unroll
+                for (int e = 0; e < EPL; ++e) qa[h][u][e] = (double)qf[e];
+            }
     }
     // reference logit C[g]: the incoming token against itself (every lane of every wave)
     double C[G], lsum[G];
@@ -787,10 +800,21 @@ __global__ __launch_bounds__(NW * 64, (G == 1 ? 4 : (G <= 2 ? 3 : 2))) void deco
     }
     double* part_w = part_s + wave * PART;
     // grouped queries: the head whose sums this lane finishes in full tiles, its reference, its total
+    // (matrix path: heads 4h + lane / 16, one per group of four heads)
     const int g_own = MF ? lane >> 4 : GqOwn<G, LPR>::head(GqLane<LPR>::seg(lane));
     double c_own = C[0], lsum_own = 0.0;
 #pragma unroll
     for (int g = 1; g < G; ++g) c_own = g == g_own ? C[g] : c_own;
+    double c_mf[NG], lsum_mf[NG];
+#pragma unroll
+    for (int h = 0; h < NG; ++h) {
+        lsum_mf[h] = 0.0;
+        c_mf[h] = C[MF ? 4 * h : 0];
+        if constexpr (MF) {
+#pragma unroll
+            for (int i = 1; i < 4; ++i) c_mf[h] = i == g_own ? C[4 * h + i] : c_mf[h];
+        }
+    }
 
     // ---- pass 1 (D1): logits of this workgroup's slots, exp(logit - C) into LDS ---------
     // Fast path (every token slot occupied): tiles are double-buffered in registers, the loads
@@ -812,7 +836,7 @@ __global__ __launch_bounds__(NW * 64, (G == 1 ? 4 : (G <= 2 ? 3 : 2))) void deco
             }
             if constexpr (G >= 2) __builtin_amdgcn_sched_barrier(0);   // the requests stay ahead of the tile's arithmetic
             if constexpr (MF)
-                k_compute_mfma4<T, UT, EPL>(bufA, qa, t * R, row_e, zt, scale, c_own, lsum_own, et + (size_t)g_own * Bz, lane);
+                k_compute_mfma4<T, UT, EPL, NG>(bufA, qa, t * R, row_e, zt, scale, c_mf, lsum_mf, et + (size_t)g_own * Bz, Bz, lane);
             else if constexpr (G >= 2)
                 k_compute_gq<T, D, G, EPL, LPR, RPL, QLDS>(bufA, t * R, row_e, zt, scale, qq, c_own, lsum_own, et, Bz, lane);
             else
@@ -838,7 +862,9 @@ __global__ __launch_bounds__(NW * 64, (G == 1 ? 4 : (G <= 2 ? 3 : 2))) void deco
     }
 #pragma unroll
     for (int g = 0; g < G; ++g) {
-        const double t = wave_sum(lsum[g] + (G >= 2 && g == g_own ? lsum_own : 0.0));
+        double mine = (G >= 2 && !MF && g == g_own) ? lsum_own : 0.0;
+        if constexpr (MF) mine = (g & 3) == g_own ? lsum_mf[g >> 2] : 0.0;
+        const double t = wave_sum(lsum[g] + mine);
         if (lane == 0) red64[wave * G + g] = t;
     }
     __syncthreads();

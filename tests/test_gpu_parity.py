@@ -31,6 +31,9 @@ DECODE_CASES = {
     # the same shape while the cache still fills up (masked tiles, queries read from LDS)
     "gqa4_bf16_fills_up": lambda: small("gqa4_bf16_fills_up", dtype="bf16", q_per_kv=4, head_dim=128, prompt_len=30,
                                         budget=64, decode_steps=60, window=8),
+    # eight query heads as two groups of four on the matrix cores
+    "gqa8_bf16_d128": lambda: small("gqa8_bf16_d128", dtype="bf16", q_per_kv=8, head_dim=128, n_kv_heads=2,
+                                    prompt_len=300, budget=101, decode_steps=40, outliers=True),
     "gqa2_d64_f16": lambda: small("gqa2_d64_f16", dtype="f16", q_per_kv=2),
     "gqa8_f32_d128": lambda: small("gqa8_f32_d128", q_per_kv=8, head_dim=128, budget=33, prompt_len=120),
     "fills_up": lambda: small("fills_up", prompt_len=20, budget=48, decode_steps=60, window=8),       # T < B: free slots first
@@ -77,7 +80,7 @@ def test_decode_from_oracle_state(case):
 
 # (case, workgroups per unit): the split step must give the oracle's decisions and outputs whatever the cut
 SPLIT_CASES = [("cfg1", 4), ("cfg1", 13), ("three_residual_f16", 2), ("alpha_half_bf16_gqa4", 3), ("gqa8_f32_d128", 2),
-               ("fills_up", 2), ("gqa4_f16_many_tiles", 2), ("empty_start", 3), ("ragged_multi_layer", 5), ("evict_only", 3), ("cfg0", 3)]
+               ("fills_up", 2), ("gqa4_f16_many_tiles", 2), ("gqa8_bf16_d128", 3), ("empty_start", 3), ("ragged_multi_layer", 5), ("evict_only", 3), ("cfg0", 3)]
 
 
 @pytest.mark.parametrize("case,parts", SPLIT_CASES)
