@@ -99,7 +99,7 @@ __global__ __launch_bounds__(256, 4) void pf_score_mfma(PrefillArgs a, PrefillWs
     constexpr int NWV = 4;
     static_assert(PF_KQ % (NWV * 32) == 0, "");
     const CacheView& cv = a.cv;
-    const int lu = blockIdx.y;
+    const int lu = (MODE == 2 ? ws.lu0 : 0) + blockIdx.y;   // MODE 2 launches cover units lu0, lu0 + 1, ...
     const int b = lu / cv.H;
     const int Tb = seq_len_of(a, b);
     const int W = a.W, G = cv.G, Wp = ws.Wp;
@@ -209,7 +209,7 @@ __global__ __launch_bounds__(256, 4) void pf_score_mfma(PrefillArgs a, PrefillWs
                 if (MODE == 2) {
 #pragma unroll
                     for (int kb = 0; kb < KB; ++kb)
-                        ep[kb] = evs + ((size_t)lu * a.T_max + (t0 + 16 * kb + j)) * ((size_t)G * Wp) + (g * Wp + r0 + q);
+                        ep[kb] = evs + ((size_t)blockIdx.y * a.T_max + (t0 + 16 * kb + j)) * ((size_t)G * Wp) + (g * Wp + r0 + q);
                 }
 #pragma unroll
                 for (int rb = 0; rb < RB; ++rb) {
@@ -274,7 +274,7 @@ __global__ __launch_bounds__(256, 4) void pf_score_mfma(PrefillArgs a, PrefillWs
 __global__ __launch_bounds__(256) void pf_score_from_ev(PrefillArgs a, PrefillWs ws, const double* __restrict__ roww,
                                                         const double* __restrict__ evs, float* __restrict__ sc) {
     const CacheView& cv = a.cv;
-    const int lu = blockIdx.y;
+    const int lu = ws.lu0 + blockIdx.y;
     const int Tb = seq_len_of(a, lu / cv.H);
     const int nb = a.W < Tb ? a.W : Tb;
     const int qpos0 = Tb - nb;
@@ -291,7 +291,7 @@ __global__ __launch_bounds__(256) void pf_score_from_ev(PrefillArgs a, PrefillWs
         for (int u = 0; u < KU; ++u) {
             const int t = tb + u * 16 + kl;
             const int tc = t < Tb ? t : Tb - 1;
-            e[u] = reinterpret_cast<const double2*>(evs + ((size_t)lu * a.T_max + tc) * rows);
+            e[u] = reinterpret_cast<const double2*>(evs + ((size_t)blockIdx.y * a.T_max + tc) * rows);
             i0[u] = tc > qpos0 ? tc - qpos0 : 0;   // first row whose position is at or after key t (Eq. 1: keys up to the row's own)
             v[u] = 0.0;
         }
@@ -337,7 +337,7 @@ __global__ void pf_fill_f64(double* p, size_t n, double v) {
 // ---- P1b: combine the workgroups' partial denominators per query row ---------------------
 __global__ void pf_row_combine(PrefillArgs a, PrefillWs ws) {
     const CacheView& cv = a.cv;
-    const int lu = blockIdx.x;
+    const int lu = ws.lu0 + blockIdx.x;
     const int b = lu / cv.H;
     const int Tb = seq_len_of(a, b);
     const int nb = a.W < Tb ? a.W : Tb;
@@ -961,10 +961,15 @@ hipError_t launch_prefill_td(const PrefillArgs& a, hipStream_t st) {
     float* sc = reinterpret_cast<float*>(a.ws + ws.sc);
     double* evs = reinterpret_cast<double*>(a.ws + ws.ev);
     if (ws.store_e) {
-        hipLaunchKernelGGL((pf_score_mfma<T, D, 2>), gs, dim3(256), 0, st, a, ws, Qd, rowm, roww, pl, sacc, sc, evs);
-        hipLaunchKernelGGL(pf_row_combine, dim3(a.n_units), dim3(256), 0, st, a, ws);
         const int tb16 = (a.T_max + 63) / 64;
-        hipLaunchKernelGGL(pf_score_from_ev, dim3(tb16 < 2048 ? tb16 : 2048, a.n_units), dim3(256), 0, st, a, ws, roww, evs, sc);
+        for (int u0 = 0; u0 < a.n_units; u0 += ws.ev_units) {   // batches of units whose exponentials fit the workspace
+            const int nu = a.n_units - u0 < ws.ev_units ? a.n_units - u0 : ws.ev_units;
+            PrefillWs wb = ws;
+            wb.lu0 = u0;
+            hipLaunchKernelGGL((pf_score_mfma<T, D, 2>), dim3(gs.x, nu, gs.z), dim3(256), 0, st, a, wb, Qd, rowm, roww, pl, sacc, sc, evs);
+            hipLaunchKernelGGL(pf_row_combine, dim3(nu), dim3(256), 0, st, a, wb);
+            hipLaunchKernelGGL(pf_score_from_ev, dim3(tb16 < 2048 ? tb16 : 2048, nu), dim3(256), 0, st, a, wb, roww, evs, sc);
+        }
     } else {
         hipLaunchKernelGGL((pf_score_mfma<T, D, 0>), gs, dim3(256), 0, st, a, ws, Qd, rowm, roww, pl, sacc, sc, evs);
         hipLaunchKernelGGL(pf_row_combine, dim3(a.n_units), dim3(256), 0, st, a, ws);

@@ -31,10 +31,13 @@ struct PrefillWs {
     int rz;                               // groups the passes of a unit are dealt to (grid.z of the scoring launches)
     int fold;                             // a workgroup takes key ranges x and nsums-1-x
     int store_e;                          // the first sweep keeps every exp(z - C) (ev), the scores are summed from there
+    int ev_units;                         // store_e: units per scoring launch (their exponentials fit PF_EV_MAX)
+    int lu0;                              // store_e: first unit of the current scoring launch (set by the launcher)
 };
 
 // The exponentials of the first scoring sweep are kept, and the second sweep of K replaced by a
-// weighted column sum over them, when they fit this many bytes (fp64, rows x T_max per unit).
+// weighted column sum over them; a call is scored in batches of units whose exponentials (fp64,
+// rows x T_max per unit) fit this many bytes.
 constexpr size_t PF_EV_MAX = (size_t)1 << 30;
 
 inline PrefillWs prefill_ws_layout(const CacheView& cv, int T_max, int W) {
@@ -53,7 +56,11 @@ inline PrefillWs prefill_ws_layout(const CacheView& cv, int T_max, int W) {
         // ranges carry far more work than the late ones: a workgroup then takes key range x together
         // with range nsums-1-x ("fold"), which evens the work out whatever XCD the workgroup lands on.
         w.fold = w.rz > 1 && 2 * (long long)W >= T_max;   // a short window sits at the end of the prompt: every key range sees all of it
-        int n = PF_SCORE_WGS / (int)((units > 0 ? units : 1) * w.rz) * (w.fold ? 2 : 1);
+        const size_t ev_unit = sizeof(double) * cv.G * w.Wp * (size_t)T_max;          // exponentials of one unit
+        w.store_e = !w.fold && ev_unit <= PF_EV_MAX && units > 0;
+        w.ev_units = w.store_e ? (int)(PF_EV_MAX / ev_unit < units ? PF_EV_MAX / ev_unit : units) : 0;
+        const size_t su = w.store_e ? (size_t)w.ev_units : units;                     // units per scoring launch
+        int n = PF_SCORE_WGS / (int)((su > 0 ? su : 1) * w.rz) * (w.fold ? 2 : 1);
         const int most = (T_max + PF_KQ - 1) / PF_KQ;
         n = n < 1 ? 1 : (n > most ? most : n);
         w.chunk_keys = ((T_max + n - 1) / n + PF_KQ - 1) / PF_KQ * PF_KQ;
@@ -67,11 +74,7 @@ inline PrefillWs prefill_ws_layout(const CacheView& cv, int T_max, int W) {
     w.rowm = o; o += up(sizeof(double) * units * cv.G * w.Wp);
     w.roww = o; o += up(sizeof(double) * units * cv.G * w.Wp);
     w.sc = o; o += up(sizeof(float) * units * T_max);
-    {
-        const size_t evb = sizeof(double) * units * cv.G * w.Wp * (size_t)T_max;     // [units][G][Wp][T_max]
-        w.store_e = !w.fold && evb <= PF_EV_MAX;
-        w.ev = o; o += up(w.store_e ? evb : 0);
-    }
+    w.ev = o; o += up(w.store_e ? sizeof(double) * (size_t)w.ev_units * T_max * cv.G * w.Wp : 0);   // [ev_units][T_max][G * Wp]
     w.sacc = o; o += up(w.multi && !w.store_e ? sizeof(double) * w.rz * units * T_max : 0);   // [rz][units][T_max]
     w.keep = o; o += up(units * (size_t)T_max);
     w.kept_pos = o; o += up(sizeof(int32_t) * units * (cv.cap_tok > 0 ? cv.cap_tok : 1));
