@@ -76,7 +76,9 @@ int zsm_cache_alloc(const zsm_config_t* cfg, const int32_t* B_p, const int32_t* 
 int zsm_cache_free(zsm_cache_t* cache);
 
 /* Bytes of device workspace zsm_prefill_compress needs for prompts of up to T_max
- * tokens scored from W query rows (0 on invalid arguments). */
+ * tokens scored from W query rows (0 on invalid arguments).  Besides scores, masks and
+ * partial sums it holds up to 1 GiB of softmax numerators (8 bytes per window row and
+ * key) when one unit's fit: K is then swept once for the scores instead of twice. */
 size_t zsm_prefill_workspace_bytes(const zsm_cache_t* cache, int32_t T_max, int32_t W);
 
 /*

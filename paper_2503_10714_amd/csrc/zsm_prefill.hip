@@ -85,7 +85,7 @@ __global__ __launch_bounds__(64) void pf_self_logit(PrefillArgs a, PrefillWs ws)
 typedef double d4_t __attribute__((ext_vector_type(4)));
 
 template <typename T, int D, int MODE>
-__global__ __launch_bounds__(256, 4) void pf_score_mfma(PrefillArgs a, PrefillWs ws, const double* __restrict__ Qd,
+__global__ __launch_bounds__(256, MODE == 2 ? 3 : 4) void pf_score_mfma(PrefillArgs a, PrefillWs ws, const double* __restrict__ Qd,
                                                         const double* __restrict__ rowm,
                                                         const double* __restrict__ roww, double* __restrict__ pl,
                                                         double* __restrict__ sacc, float* __restrict__ sc,

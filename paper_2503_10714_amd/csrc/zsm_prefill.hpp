@@ -60,7 +60,9 @@ inline PrefillWs prefill_ws_layout(const CacheView& cv, int T_max, int W) {
         w.store_e = !w.fold && ev_unit <= PF_EV_MAX && units > 0;
         w.ev_units = w.store_e ? (int)(PF_EV_MAX / ev_unit < units ? PF_EV_MAX / ev_unit : units) : 0;
         const size_t su = w.store_e ? (size_t)w.ev_units : units;                     // units per scoring launch
-        int n = PF_SCORE_WGS / (int)((su > 0 ? su : 1) * w.rz) * (w.fold ? 2 : 1);
+        // one round of workgroups: 4 per compute unit, 3 for the sweep that also stores its exponentials (more registers)
+        const int wgs = w.store_e ? PF_SCORE_WGS / 4 * 3 : PF_SCORE_WGS;
+        int n = wgs / (int)((su > 0 ? su : 1) * w.rz) * (w.fold ? 2 : 1);
         const int most = (T_max + PF_KQ - 1) / PF_KQ;
         n = n < 1 ? 1 : (n > most ? most : n);
         w.chunk_keys = ((T_max + n - 1) / n + PF_KQ - 1) / PF_KQ * PF_KQ;
