@@ -258,6 +258,47 @@ def test_error_paths_on_device():
     big.close(); cache.close()
 
 
+def random_workload(seed: int) -> synth.Workload:
+    """A small workload whose shape is drawn from the seed: every dtype, head dim, group size, residual count,
+    window (short, longer than 32, full history), ragged or not, budgets that end in a ragged tile."""
+    import random
+    r = random.Random(1000 + seed)
+    dtype = r.choice(["f32", "f16", "bf16"])
+    d = r.choice([64, 128])
+    G = r.choice([1, 1, 2, 4, 8])
+    n_res = r.choice([0, 1, 1, 2, 5])
+    T = r.choice([37, 150, 333, 700])
+    budget = r.randint(n_res + 4, 140)
+    window = r.choice([0, 8, 32, 40])
+    ragged = (max(0, T // 3), T) if r.random() < 0.4 else None
+    return synth.Workload(name=f"random{seed}", n_layers=r.choice([1, 2]), n_seqs=r.choice([1, 3]) if ragged else r.choice([1, 2]),
+                          n_kv_heads=r.choice([1, 2, 3]), q_per_kv=G, head_dim=d, dtype=dtype, prompt_len=T, budget=budget,
+                          decode_steps=24, window=window, outliers=r.random() < 0.5, ragged=ragged,
+                          budget_ratio=(budget / T if ragged else None), n_residual=n_res,
+                          prox=r.choice([None, None, max(1, (budget - n_res) // 3)]), alpha=r.choice([1.0, 1.0, 0.5]), seed=synth.MASTER_SEED + seed)
+
+
+@pytest.mark.parametrize("seed", list(range(48)))
+def test_random_shapes_prefill_then_decode(seed):
+    """Seeded sweep over shapes: the whole path on the device against the oracle, first in the launch shape the
+    library picks (so few units are split over workgroups), then with one workgroup per unit."""
+    wl = random_workload(seed)
+    bp, bc, br = wl.budgets()
+    print(f"[case] random {seed}: {wl.dtype} d={wl.head_dim} G={wl.q_per_kv} B_r={br} T={wl.seq_lens()} B_p={bp} B_c={bc} "
+          f"W={wl.window} L={wl.n_layers} H={wl.n_kv_heads} alpha={wl.alpha}", flush=True)
+    if min(p for p in bp) < 1 or min(c for c in bc) < 0:
+        pytest.skip("drawn budget leaves no proximity slot")
+    cache, units = prefill_gpu_and_oracle(wl, gen_device="cpu")
+    pu.compare_all_state(wl, cache, units, pu.tol_for(wl.dtype), "after prefill")
+    st0 = pu.run_decode_parity(wl, cache, units, 12, state_every=0)
+    used = cache.decode_parts()
+    cache.set_decode_parts(1)
+    st = pu.run_decode_parity(wl, cache, units, 12, state_every=0, first_step=12)
+    print(f"[done] random {seed}: parts {used} then 1, unit-steps={st0.unit_steps + st.unit_steps} evictions={st0.evictions + st.evictions} "
+          f"near_ties={st0.near_ties + st.near_ties} max|out err|={max(st0.max_out_err, st.max_out_err):.2e}", flush=True)
+    cache.close()
+
+
 def test_workload2_full_size_sampled_units():
     """The benchmark's launch configuration (1024 units, all 32 layers per launch, B = 2700 after a
     54 000-token prompt): prefill and decode run at full size on the device, a sample of units
