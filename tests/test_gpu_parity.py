@@ -280,8 +280,8 @@ def random_workload(seed: int) -> synth.Workload:
 
 @pytest.mark.parametrize("seed", list(range(48)))
 def test_random_shapes_prefill_then_decode(seed):
-    """Seeded sweep over shapes: the whole path on the device against the oracle, first in the launch shape the
-    library picks (so few units are split over workgroups), then with one workgroup per unit."""
+    """Seeded sweep over shapes: the whole path on the device against the oracle, the decode steps first cut over
+    2 to 4 workgroups per unit (where the budget allows), then with one workgroup per unit."""
     wl = random_workload(seed)
     bp, bc, br = wl.budgets()
     print(f"[case] random {seed}: {wl.dtype} d={wl.head_dim} G={wl.q_per_kv} B_r={br} T={wl.seq_lens()} B_p={bp} B_c={bc} "
@@ -290,8 +290,9 @@ def test_random_shapes_prefill_then_decode(seed):
         pytest.skip("drawn budget leaves no proximity slot")
     cache, units = prefill_gpu_and_oracle(wl, gen_device="cpu")
     pu.compare_all_state(wl, cache, units, pu.tol_for(wl.dtype), "after prefill")
-    st0 = pu.run_decode_parity(wl, cache, units, 12, state_every=0)
+    cache.set_decode_parts(2 + seed % 3)      # cut over workgroups where the budget has the tiles for it
     used = cache.decode_parts()
+    st0 = pu.run_decode_parity(wl, cache, units, 12, state_every=0)
     cache.set_decode_parts(1)
     st = pu.run_decode_parity(wl, cache, units, 12, state_every=0, first_step=12)
     print(f"[done] random {seed}: parts {used} then 1, unit-steps={st0.unit_steps + st.unit_steps} evictions={st0.evictions + st.evictions} "
