@@ -817,6 +817,17 @@ __global__ __launch_bounds__(NW * 64, (G == 1 ? 4 : (G <= 2 ? 3 : 2))) void deco
     }
 
     // ---- pass 1 (D1): logits of this workgroup's slots, exp(logit - C) into LDS ---------
+    // Residual slots (fp32 rows, log-count term) and the incoming token itself come first: their
+    // few rows are requested while the wave's first K tile is still on its way, so their round
+    // trip hides behind that one instead of standing alone at the end of the pass.
+    if (part == 0) {
+        for (int t = wave; t * RPL < Br; t += NW)
+            k_tile_masked<float, 1, D, G, EPL, LPR, RPL, QLDS>(Kr, t * RPL, Br, 0, nullptr, w, alpha, scale, qq, C, lsum,
+                                                               et, Bz, part_w, klane);
+        if (wave == NW - 1)
+            k_tile_masked<T, 1, D, G, EPL, LPR, RPL, QLDS>(knew, 0, 1, znew, nullptr, nullptr, alpha, scale, qq, C, lsum,
+                                                           et, Bz, part_w, klane);
+    }
     // Fast path (every token slot occupied): tiles are double-buffered in registers, the loads
     // of the wave's next tile (or of its first V tile) are in flight while it works on this one.
     if (full) {
@@ -851,14 +862,23 @@ __global__ __launch_bounds__(NW * 64, (G == 1 ? 4 : (G <= 2 ? 3 : 2))) void deco
             k_tile_masked<T, 1, D, G, EPL, LPR, RPL, QLDS>(Kt, r0, row_e, zt, pos + Br, nullptr, alpha, scale, qq, C, lsum,
                                                            et, Bz, part_w, klane);
     }
-    // residual slots (fp32 rows, log-count term) and the incoming token itself
+    // The wave's first tile of residual V rows and (last wave) the incoming token's V row are
+    // requested before the barrier, so their round trip passes while the waves meet; rows whose
+    // probability is exactly 0 (empty slots among them) are not loaded.  This wave wrote their
+    // exponentials itself (same tile assignment in both passes).
+    Raw<float, EPL> vres;
+    Raw<T, EPL> vnw;
+    vres.zero();
+    vnw.zero();
     if (part == 0) {
-        for (int t = wave; t * RPL < Br; t += NW)
-            k_tile_masked<float, 1, D, G, EPL, LPR, RPL, QLDS>(Kr, t * RPL, Br, 0, nullptr, w, alpha, scale, qq, C, lsum,
-                                                               et, Bz, part_w, klane);
-        if (wave == NW - 1)
-            k_tile_masked<T, 1, D, G, EPL, LPR, RPL, QLDS>(knew, 0, 1, znew, nullptr, nullptr, alpha, scale, qq, C, lsum,
-                                                           et, Bz, part_w, klane);
+        const int r = wave * RPL + grp;
+        bool any = false;
+        if (r < Br) {
+#pragma unroll
+            for (int g = 0; g < G; ++g) any = any || (et[(size_t)g * Bz + r] != 0.0);
+        }
+        if (any) vres.load(Vr + (size_t)r * D + seg * EPL);
+        if (wave == NW - 1 && grp == 0) vnw.load(vnew + seg * EPL);   // its probability is never 0: exp(0) / L
     }
 #pragma unroll
     for (int g = 0; g < G; ++g) {
@@ -883,6 +903,10 @@ __global__ __launch_bounds__(NW * 64, (G == 1 ? 4 : (G <= 2 ? 3 : 2))) void deco
     for (int g = 0; g < G; ++g)
 #pragma unroll
         for (int e = 0; e < EPL; ++e) acc[g][e] = 0.f;
+    if (part == 0) {
+        if (wave * RPL < Br) v_compute<float, 1, D, G, EPL, LPR, RPL>(&vres, wave * RPL, Br, 0, rL, acc, et, Bz, lane);
+        if (wave == NW - 1) v_compute<T, 1, D, G, EPL, LPR, RPL>(&vnw, 0, 1, znew, rL, acc, et, Bz, lane);
+    }
     if (full) {
         int t = tb + wave;   // bufA already holds this wave's first V tile
         while (t < te) {
@@ -899,11 +923,9 @@ __global__ __launch_bounds__(NW * 64, (G == 1 ? 4 : (G <= 2 ? 3 : 2))) void deco
             v_tile_masked<T, 1, D, G, EPL, LPR, RPL>(Vt, r0, row_e, zt, rL, acc, et, Bz, lane);
     }
     __builtin_amdgcn_s_setprio(0);
-    if (part == 0) {
-        for (int t = wave; t * RPL < Br; t += NW)
+    if (part == 0) {   // residual tiles beyond the waves' first ones (more than NW * RPL residual slots)
+        for (int t = wave + NW; t * RPL < Br; t += NW)
             v_tile_masked<float, 1, D, G, EPL, LPR, RPL>(Vr, t * RPL, Br, 0, rL, acc, et, Bz, lane);
-        if (wave == NW - 1)
-            v_tile_masked<T, 1, D, G, EPL, LPR, RPL>(vnew, 0, 1, znew, rL, acc, et, Bz, lane);
     }
 
     // What the end of the step reads regardless of its decisions: requested now, used after the
