@@ -678,7 +678,7 @@ __device__ __forceinline__ void decode_finish(const DecodeArgs& a, const CacheVi
 //   boundary is what makes one workgroup's scratch visible to another: fences inside one
 //   kernel cost more here than the whole sweep of a small launch).
 template <typename T, int D, int G, int NW, bool SPLIT>
-__global__ __launch_bounds__(NW * 64, (G == 1 ? 4 : (G <= 2 ? 3 : 2))) void decode_kernel(DecodeArgs a) {
+__global__ __launch_bounds__(NW * 64, (G == 1 ? 4 : (G < 2 ? 3 : 2))) void decode_kernel(DecodeArgs a) {
     using Sh = DecodeShape<T, D, G, NW>;
     constexpr int EPL = Sh::EPL, LPR = Sh::LPR, RPL = Sh::RPL, R = Sh::R, PART = Sh::PART, NT = Sh::NT, UT = Sh::UT;
     constexpr bool QLDS = Sh::QLDS;
@@ -866,11 +866,12 @@ __global__ __launch_bounds__(NW * 64, (G == 1 ? 4 : (G <= 2 ? 3 : 2))) void deco
     // requested before the barrier, so their round trip passes while the waves meet; rows whose
     // probability is exactly 0 (empty slots among them) are not loaded.  This wave wrote their
     // exponentials itself (same tile assignment in both passes).
+    constexpr bool VPRE = G <= 4;   // eight query heads leave no registers for it: their rows are loaded where they are used
     Raw<float, EPL> vres;
     Raw<T, EPL> vnw;
     vres.zero();
     vnw.zero();
-    if (part == 0) {
+    if (VPRE && part == 0) {
         const int r = wave * RPL + grp;
         bool any = false;
         if (r < Br) {
@@ -903,7 +904,7 @@ __global__ __launch_bounds__(NW * 64, (G == 1 ? 4 : (G <= 2 ? 3 : 2))) void deco
     for (int g = 0; g < G; ++g)
 #pragma unroll
         for (int e = 0; e < EPL; ++e) acc[g][e] = 0.f;
-    if (part == 0) {
+    if (VPRE && part == 0) {
         if (wave * RPL < Br) v_compute<float, 1, D, G, EPL, LPR, RPL>(&vres, wave * RPL, Br, 0, rL, acc, et, Bz, lane);
         if (wave == NW - 1) v_compute<T, 1, D, G, EPL, LPR, RPL>(&vnw, 0, 1, znew, rL, acc, et, Bz, lane);
     }
@@ -924,8 +925,10 @@ __global__ __launch_bounds__(NW * 64, (G == 1 ? 4 : (G <= 2 ? 3 : 2))) void deco
     }
     __builtin_amdgcn_s_setprio(0);
     if (part == 0) {   // residual tiles beyond the waves' first ones (more than NW * RPL residual slots)
-        for (int t = wave + NW; t * RPL < Br; t += NW)
+        for (int t = wave + (VPRE ? NW : 0); t * RPL < Br; t += NW)
             v_tile_masked<float, 1, D, G, EPL, LPR, RPL>(Vr, t * RPL, Br, 0, rL, acc, et, Bz, lane);
+        if (!VPRE && wave == NW - 1)
+            v_tile_masked<T, 1, D, G, EPL, LPR, RPL>(vnew, 0, 1, znew, rL, acc, et, Bz, lane);
     }
 
     // What the end of the step reads regardless of its decisions: requested now, used after the
