@@ -300,6 +300,28 @@ def test_random_shapes_prefill_then_decode(seed):
     cache.close()
 
 
+def test_prefill_workspace_size():
+    """The workspace holds the kept softmax numerators of as many units as fit 1 GiB (8 bytes per window row and
+    key), never more, and none when the window covers half the prompt or more (those calls sweep K twice)."""
+    from paper_2503_10714_amd import binding as zb
+    GiB = 1 << 30
+    # workload 2's layer: 32 units x 32 rows x 54 000 keys x 8 B = 442 MB of numerators, all kept
+    c = zb.Cache(1, 1, 32, 1, 128, 1350, 1349, 1, "f16", device=DEV)
+    short = zb.zsm_prefill_workspace_bytes(c.handle, 54000, 32)
+    ev = 32 * 32 * 54000 * 8
+    assert ev < short < ev + 200 * (1 << 20)
+    # full history at the same length: no numerators kept, far smaller
+    full = zb.zsm_prefill_workspace_bytes(c.handle, 4096, 4096)
+    assert full < 200 * (1 << 20)
+    c.close()
+    # workload 3's layer: 2048 units x 32 rows x 16 384 keys x 8 B = 8.6 GB of numerators: only 1 GiB of them at a time
+    c = zb.Cache(1, 64, 32, 1, 128, [819] * 64, [819] * 64, 1, "f16", device=DEV)
+    big = zb.zsm_prefill_workspace_bytes(c.handle, 16384, 32)
+    assert GiB - (1 << 23) < big < GiB + 700 * (1 << 20)
+    assert zb.zsm_prefill_workspace_bytes(c.handle, 8192, 32) < big
+    c.close()
+
+
 def test_workload2_full_size_sampled_units():
     """The benchmark's launch configuration (1024 units, all 32 layers per launch, B = 2700 after a
     54 000-token prompt): prefill and decode run at full size on the device, a sample of units
