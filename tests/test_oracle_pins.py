@@ -452,3 +452,169 @@ def test_figure_walk_structure():
             assert sorted(c.pos[list(c.Kp)].tolist()) == list(range(n - cfg["B_p"], n))   # latest 3
             assert c.w[:cfg["B_r"]].sum() == n - cfg["B_p"] - cfg["B_c"]
             assert (c.w[cfg["B_r"]:] == 1).all() and len(set(tok.tolist())) == tok.size
+
+
+# ---------------------------------------------------------------------------------------
+# grouped queries in the decode update (appendix, GQA adaptation, with Eq. 3)
+# ---------------------------------------------------------------------------------------
+
+def test_decode_score_update_pools_the_group_by_its_unweighted_mean():
+    """G = 2, two very different query heads, nothing evicted: every stored score becomes
+    lam * s + (p_head0 + p_head1) / 2 with p_g the scipy softmax row of head g, and the
+    incoming token starts at the mean of its own two probabilities."""
+    d, lam = 4, 0.9
+    K, V = rnd(100, 5, d), rnd(101, 5, d)
+    q = np.array([[3.0, 0.0, -1.0, 0.5], [-2.0, 1.0, 0.0, 4.0]])        # head 0, head 1
+    kn, vn = rnd(102, d), rnd(103, d)
+    s0 = np.array([0.25, 0.5, 1.0, 2.0, 0.125, 0.0, 0.0, 0.0])
+    c = UnitCache(d, 2, B_p=3, B_c=5, B_r=0, lam=lam)
+    Kst, Vst = np.zeros((8, d)), np.zeros((8, d))
+    Kst[:5], Vst[:5] = K, V
+    c.import_state(Kst, Vst, pos=np.array([0, 1, 2, 3, 4, -1, -1, -1]),
+                   w=np.array([1, 1, 1, 1, 1, 0, 0, 0]), s=s0, n_seen=5)
+    out, info = c.decode_step(q, kn, vn)
+    assert info.evicted_pos == -1 and info.write_slot == 5
+    Kall, Vall = np.vstack([K, kn]), np.vstack([V, vn])
+    p0 = sp_softmax(Kall @ q[0] / math.sqrt(d))
+    p1 = sp_softmax(Kall @ q[1] / math.sqrt(d))
+    assert np.abs(p0 - p1).max() > 0.2                                   # the heads really differ
+    expect = lam * s0[:5] + 0.5 * (p0[:5] + p1[:5])
+    np.testing.assert_allclose(c.s[:5], expect, rtol=1e-6)
+    assert abs(c.s[5] - 0.5 * (p0[5] + p1[5])) < 1e-7
+    # head 0 alone, head 1 alone, or an uneven weighting would all be off by far more than that
+    assert np.abs(lam * s0[:5] + p0[:5] - c.s[:5]).max() > 1e-2
+    np.testing.assert_allclose(out[0], p0 @ Vall, atol=1e-13)            # one softmax per head
+    np.testing.assert_allclose(out[1], p1 @ Vall, atol=1e-13)
+
+
+def test_decode_eviction_choice_uses_the_pooled_score():
+    """G = 2: head 0 alone would make position 0 the weakest token, the mean over both heads
+    makes it position 1 (Alg. 1 context overflow on the pooled Eq. 3 scores)."""
+    d = 2
+    K = np.array([[0.0, 8.0], [1.0, 1.0], [4.0, 4.0], [4.0, 4.0]])
+    V = np.eye(4)[:, :d] * 0 + np.arange(4)[:, None]
+    q = np.array([[4.0, 0.0], [0.0, 4.0]])        # head 0 ignores position 0, head 1 loves it
+    c = UnitCache(d, 2, B_p=2, B_c=2, B_r=0, lam=1.0, scale=1.0)
+    c.import_state(K, V, pos=np.arange(4), w=np.ones(4, dtype=int), s=np.zeros(4), n_seen=4)
+    _, info = c.decode_step(q, np.array([4.0, 4.0]), np.zeros(d))
+    Kall = np.vstack([K, [4.0, 4.0]])
+    p = 0.5 * (sp_softmax(Kall @ q[0]) + sp_softmax(Kall @ q[1]))
+    assert sp_softmax(Kall @ q[0])[0] < sp_softmax(Kall @ q[0])[1]      # head 0's view
+    assert p[1] < p[0]                                                    # the pooled view
+    assert sorted(info.cand_pos.tolist()) == [0, 1, 2]
+    assert info.evicted_pos == 1
+
+
+# ---------------------------------------------------------------------------------------
+# one-shot prefill with two residual slots: absorption order (Alg. 1 residual branch,
+# Eq. 5, Eq. 6; the tokens not kept are taken in position order)
+# ---------------------------------------------------------------------------------------
+
+def _two_slot_prompt():
+    """Eight tokens, d = 2, B_p = 1, B_c = 1, B_r = 2.  The single query (last position) points
+    along (1, 1), so position 2 with key (5, 5) has by far the largest score and is the context
+    token; position 7 is the proximity token.  Dropped, in position order: 0, 1, 3, 4, 5, 6."""
+    K = np.array([[1.0, 0.0],      # 0  opens residual slot 0
+                  [2.0, 0.5],      # 1  opens residual slot 1
+                  [5.0, 5.0],      # 2  kept (context)
+                  [0.0, 2.0],      # 3  dots 0 vs 1            -> slot 1: K = (1, 1.25), w = 2
+                  [3.0, 0.0],      # 4  dots 3 vs 3, a tie     -> slot 0: K = (2, 0), w = 2
+                  [0.0, 1.0],      # 5  dots 0 vs 1.25         -> slot 1: K = (2/3, 7/6), w = 3
+                  [1.0, 1.0],      # 6  dots 2 vs 11/6         -> slot 0 (it would go to slot 1, 1 vs 11/6,
+                                   #    had token 4 not moved slot 0 first): K = (5/3, 1/3), w = 3
+                  [0.5, 0.5]])     # 7  kept (proximity)
+    V = np.array([[1.0, 10.0], [2.0, 20.0], [3.0, 30.0], [4.0, 40.0],
+                  [5.0, 50.0], [6.0, 60.0], [7.0, 70.0], [8.0, 80.0]])
+    Q = np.array([[[1.0, 1.0]]])
+    return Q, K, V
+
+
+def test_one_shot_prefill_two_residual_slots_hand_computed():
+    Q, K, V = _two_slot_prompt()
+    c = UnitCache(2, 1, B_p=1, B_c=1, B_r=2, scale=1.0)
+    s = c.prefill_compress(Q, K, V)
+    assert c.pos[2:].tolist() == [2, 7]
+    # values worked out by hand from Eq. 5 (largest raw dot product, ties to the lower slot)
+    # and Eq. 6 (incremental mean): slot 0 absorbed tokens 0, 4, 6 and slot 1 tokens 1, 3, 5
+    np.testing.assert_allclose(c.K[0], [5.0 / 3, 1.0 / 3], rtol=3e-7)
+    np.testing.assert_allclose(c.K[1], [2.0 / 3, 3.5 / 3], rtol=3e-7)
+    np.testing.assert_allclose(c.V[0], [13.0 / 3, 130.0 / 3], rtol=3e-7)
+    np.testing.assert_allclose(c.V[1], [4.0, 40.0], rtol=3e-7)
+    assert c.w.tolist() == [3, 3, 1, 1] and c.w.sum() == 8
+    # a residual slot keeps the position and the score of the token that opened it
+    assert c.pos[:2].tolist() == [0, 1]
+    assert c.s[0] == s[0] and c.s[1] == s[1] and s[1] > s[0] > 0
+    assert c.n_seen == 8 and c.Kr == [0, 1]
+
+
+def test_one_shot_prefill_absorbs_in_position_order_not_another():
+    """The same prompt walked by an explicit Eq. 5 / Eq. 6 loop written here: position order
+    reproduces the oracle, the reverse order gives a different residual set."""
+    Q, K, V = _two_slot_prompt()
+    c = UnitCache(2, 1, 1, 1, 2, scale=1.0)
+    c.prefill_compress(Q, K, V)
+
+    def walk(order):
+        Kr, Vr, w = [], [], []
+        for t in order:
+            if len(Kr) < 2:
+                Kr.append(K[t].copy()); Vr.append(V[t].copy()); w.append(1)
+                continue
+            dots = [float(kr @ K[t]) for kr in Kr]
+            r = 0 if dots[0] >= dots[1] else 1
+            Kr[r] = (w[r] * Kr[r] + K[t]) / (w[r] + 1)
+            Vr[r] = (w[r] * Vr[r] + V[t]) / (w[r] + 1)
+            w[r] += 1
+        return np.array(Kr), np.array(Vr), w
+
+    dropped = [0, 1, 3, 4, 5, 6]
+    Kf, Vf, wf = walk(dropped)
+    np.testing.assert_allclose(c.K[:2], Kf, rtol=3e-7)
+    np.testing.assert_allclose(c.V[:2], Vf, rtol=3e-7)
+    assert c.w[:2].tolist() == wf
+    Kb, Vb, wb = walk(dropped[::-1])
+    assert np.abs(Kb - Kf).max() > 0.1 and np.abs(Vb - Vf).max() > 0.1
+
+
+def test_eviction_that_opens_a_residual_slot_hands_over_position_and_score():
+    """Decode: the first eviction fills the unused residual slot with the evicted token's
+    key, value, count 1, position, and its score as updated in this very step (Eq. 3)."""
+    d, lam = 2, 0.5
+    K = np.array([[9.0, 9.0], [1.0, 2.0], [3.0, 4.0], [5.0, 6.0]])
+    V = np.array([[9.0, 9.0], [0.5, 0.25], [7.0, 8.0], [1.0, 1.0]])
+    c = UnitCache(d, 1, B_p=1, B_c=2, B_r=1, lam=lam)
+    c.import_state(K, V, pos=np.array([-1, 4, 5, 6]), w=np.array([0, 1, 1, 1]),
+                   s=np.array([0.0, 0.25, 2.0, 3.0]), n_seen=7)
+    _, info = c.decode_step(np.zeros((1, d)), np.array([0.0, 1.0]), np.array([1.0, 0.0]))
+    # q = 0: four entries (three tokens + the incoming one) get probability 1/4 each
+    assert info.evicted_pos == 4 and info.merged_slot == 0 and info.write_slot == 1
+    assert c.pos[0] == 4 and c.w[0] == 1
+    assert c.s[0] == np.float32(lam * 0.25 + 0.25)
+    np.testing.assert_array_equal(c.K[0], K[1]); np.testing.assert_array_equal(c.V[0], V[1])
+    # a later merge leaves that position and score alone (the score only decays and accrues)
+    _, info = c.decode_step(np.zeros((1, d)), np.array([1.0, 1.0]), np.array([2.0, 2.0]))
+    assert info.merged_slot == 0 and c.w[0] == 2 and c.pos[0] == 4
+    # entries: residual (w = 2 -> weight 2), three tokens, incoming: probabilities 2/5? no - the
+    # count seen by the softmax is the one before this step's merge (w = 1): 1/5 each
+    assert c.s[0] == np.float32(lam * float(np.float32(lam * 0.25 + 0.25)) + 0.2)
+
+
+# ---------------------------------------------------------------------------------------
+# the full-attention checker itself (Eq. 1)
+# ---------------------------------------------------------------------------------------
+
+def test_full_attention_row_is_textbook_softmax_attention():
+    T, d = 17, 8
+    Q, K, V = skewed(110, T, d)
+    K[3] *= 40.0                                      # large logits: the shift by the maximum matters
+    for scale in (1 / math.sqrt(d), 0.21):
+        o, a = full_attention_row(Q[0, 5], K, V, scale)
+        p = sp_softmax(K @ Q[0, 5] * scale)
+        np.testing.assert_allclose(a, p, rtol=1e-13, atol=1e-300)
+        np.testing.assert_allclose(o, p @ V, atol=1e-12)
+        assert abs(a.sum() - 1) < 1e-14
+    # an asymmetric case worked by hand: logits (0, ln 3) -> probabilities (1/4, 3/4)
+    o, a = full_attention_row(np.array([1.0, 0.0]), np.array([[0.0, 5.0], [math.log(3.0), -2.0]]),
+                              np.array([[4.0, 0.0], [0.0, 8.0]]), 1.0)
+    np.testing.assert_allclose(a, [0.25, 0.75], rtol=1e-14)
+    np.testing.assert_allclose(o, [1.0, 6.0], rtol=1e-14)
