@@ -14,7 +14,8 @@
  *     and 16-byte aligned.  Q/K/V inputs and token slots use the cache's kv_dtype;
  *     residual slots, scores and attention outputs are fp32; counts and positions int32.
  *   - `stream` is a hipStream_t (NULL = the default stream).  Calls only enqueue work;
- *     they never synchronise, allocate or free device memory.
+ *     they never synchronise (unless zsm_set_debug_checks is on), allocate or free device
+ *     memory.
  *   - Return value: ZSM_OK or a negative zsm_status.  Arguments are validated on the
  *     host before anything is enqueued, so a failed call leaves the cache untouched.
  *   - One stream per cache at a time; calls on one cache must not overlap.
@@ -41,7 +42,15 @@ enum zsm_status {
     ZSM_E_ALIGN = -4,  /* a device pointer is not 16-byte aligned                      */
     ZSM_E_NOMEM = -5,  /* caller's buffer or workspace is too small                    */
     ZSM_E_RANGE = -6,  /* layer index / range outside the cache                        */
-    ZSM_E_HIP = -7     /* the HIP runtime refused a launch (text via zsm_strerror)     */
+    ZSM_E_HIP = -7,    /* the HIP runtime refused a launch (text via zsm_strerror)     */
+    ZSM_E_STATE = -8   /* the cache state breaks the call's precondition (only reported
+                          while zsm_set_debug_checks is on)                            */
+};
+
+/* Sticky per-unit condition bits, read with zsm_cache_flags. */
+enum zsm_flag {
+    ZSM_FLAG_DECODE_SPREAD = 1,   /* zsm_decode_step met a logit beyond its range (see there)      */
+    ZSM_FLAG_PREFILL_SPREAD = 2   /* zsm_prefill_compress met a logit beyond its range (see there) */
 };
 
 typedef struct {
@@ -99,7 +108,18 @@ size_t zsm_prefill_workspace_bytes(const zsm_cache_t* cache, int32_t T_max, int3
  *   K, V       device [S, H, T_max, d]; rows >= T_b are ignored.
  *   seq_lens   device int32 [S]: T_b, 0 <= T_b <= T_max.
  *   workspace  device, 256-byte aligned, ws_bytes >= zsm_prefill_workspace_bytes().
- * The layer's cache must be empty (freshly allocated or re-imported empty).
+ * The layer's cache must be empty (freshly allocated or re-imported empty); this is only
+ * verified while zsm_set_debug_checks is on (ZSM_E_STATE).
+ * Logit range: each softmax row (Eq. 1) is evaluated in fp64 as exp(z_t - z_self) / sum, with
+ * z_self the query's logit against the key at its own position, so no running maximum is
+ * kept.  This is exact as long as no counted key's logit exceeds z_self by more than 690
+ * (e^690 is near the top of the fp64 range; a softmax over 16- or 32-bit inputs whose
+ * logits spread that far has a single non-zero entry).  Beyond that the difference is clamped at
+ * 690, the keys beyond it get equal weight and the scores of that unit are not the method's.
+ * The clamp never acts unseen: a row whose sum of exponentials reaches e^680 raises the unit's
+ * ZSM_FLAG_PREFILL_SPREAD bit (so the bit may already be up, with exact results, when the
+ * spread is within ln(T) of 680).  The call still returns ZSM_OK (nothing is read back from the
+ * device here); a caller that feeds unnormalised activations checks zsm_cache_flags afterwards.
  * With B_r = 1 the residual slot is the mean of all absorbed tokens (parallel sums); with
  * B_r >= 2 the tokens are absorbed one after the other as Alg. 1 prescribes (sequential per
  * unit: about a microsecond per absorbed token).  B_r <= 64 here (the decode step takes any
@@ -130,6 +150,14 @@ int zsm_prefill_compress(zsm_cache_t* cache, int32_t layer, const void* Q, int32
  *   write_slot   device int32 [Ln, S, H] or NULL: slot that received the token
  *   evicted_pos  device int32 [Ln, S, H] or NULL: position of the evicted token, -1 if none
  *   merged_slot  device int32 [Ln, S, H] or NULL: residual slot that absorbed it, -1 if none
+ * Logit range: the softmax of Eq. 4 is evaluated in fp64 as exp(z_j - z_new) / sum, z_new being
+ * the incoming token's own logit, so no running maximum is kept.  This is exact as long as no
+ * slot's logit (log-count term included) exceeds z_new by more than 690.  Beyond that the
+ * difference is clamped at 690: the slots beyond it tie, and that unit's output, scores and
+ * eviction choice are not the method's.  The clamp never acts unseen: a softmax denominator
+ * that reaches e^680 raises the unit's ZSM_FLAG_DECODE_SPREAD bit (sticky, read with
+ * zsm_cache_flags; it may already be up, with exact results, when the spread is within ln(B)
+ * of 680).  The call still returns ZSM_OK.
  * Launch shape: one workgroup per unit when the launch has many units; a launch of few
  * units (one layer of a single sequence, say) is cut into several workgroups per unit,
  * each sweeping a share of the slots, so that it still fills the chip.  The share's
@@ -147,10 +175,9 @@ int zsm_decode_step(zsm_cache_t* cache, int32_t layer_begin, int32_t layer_end,
                     void* stream);
 
 /*
- * zsm_cache_set_decode_parts - how many workgroups share one unit in zsm_decode_step
- * (split of the slot sweep, motivated by the paper's observation that overhead dominates
- * short, small-batch settings, appendix on experimental details, text before the latency table): 0 = chosen per launch from
- * the number of units (the default), 1 = never split, 2..64 = this many where the launch
+ * zsm_cache_set_decode_parts - how many workgroups share one unit in zsm_decode_step (a
+ * launch-shape knob of this library, not something the paper defines): 0 = chosen per launch
+ * from the number of units (the default), 1 = never split, 2..64 = this many where the launch
  * allows it (at most 1024 units and 8192 workgroups; fewer parts are used beyond that).
  * ZSM_E_RANGE for other values.
  */
@@ -170,8 +197,10 @@ int zsm_decode_parts(const zsm_cache_t* cache, int32_t layer_begin, int32_t laye
  *   pos     int32    [S, H, slot_capacity]             original position, -1 = empty
  *   w       int32    [S, H, slot_capacity]             fusion count, 0 = empty
  *   n_seen  int64    [S, H]                            tokens seen (T)
- * Import trusts the caller: token slots must have w in {0,1} with w = 0 exactly where
- * pos = -1, and positions below n_seen.
+ * Import trusts the caller: every slot must have w = 0 exactly where pos = -1, token slots
+ * w in {0,1}, positions below n_seen, and slots past the sequence's B_r + B_c + B_p empty.
+ * While zsm_set_debug_checks is on, import verifies this on the arrays it is given (a NULL one
+ * is taken from the cache) before it copies anything, and returns ZSM_E_STATE otherwise.
  */
 int zsm_cache_export(const zsm_cache_t* cache, int32_t layer, void* K, void* V, float* Kr,
                      float* Vr, float* s, int32_t* pos, int32_t* w, int64_t* n_seen,
@@ -179,6 +208,25 @@ int zsm_cache_export(const zsm_cache_t* cache, int32_t layer, void* K, void* V, 
 int zsm_cache_import(zsm_cache_t* cache, int32_t layer, const void* K, const void* V,
                      const float* Kr, const float* Vr, const float* s, const int32_t* pos,
                      const int32_t* w, const int64_t* n_seen, void* stream);
+
+/*
+ * zsm_cache_flags - the sticky condition bits (enum zsm_flag) of one layer's units.
+ *   flags   device int32 [S, H] or NULL: receives the bits
+ *   clear   non-zero: the layer's bits are reset after they have been copied
+ * The bits are also reset by zsm_cache_alloc.  Only kernels set them; nothing is read back on
+ * the host here, the call enqueues one small kernel.
+ */
+int zsm_cache_flags(zsm_cache_t* cache, int32_t layer, int32_t* flags, int32_t clear, void* stream);
+
+/*
+ * zsm_set_debug_checks - process-wide switch (default off) for checks of device-side state
+ * that the normal path cannot afford: while on, zsm_prefill_compress verifies that the layer
+ * is empty and zsm_cache_import that the state it is given is well formed.  Each check runs
+ * a small kernel, WAITS for the stream and reads one counter back, so it is for development
+ * and tests; a violation is reported as ZSM_E_STATE before the call changes anything.
+ * Returns the previous setting.
+ */
+int zsm_set_debug_checks(int32_t on);
 
 /*
  * zsm_stream_read / zsm_stream_copy - plain streaming kernels of known size, used to

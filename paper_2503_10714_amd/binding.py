@@ -24,7 +24,7 @@ CODE_TORCH = {ZSM_F32: torch.float32, ZSM_F16: torch.float16, ZSM_BF16: torch.bf
 EXPORTS = [
     "zsm_cache_bytes", "zsm_cache_alloc", "zsm_cache_free", "zsm_prefill_workspace_bytes",
     "zsm_prefill_compress", "zsm_decode_step", "zsm_cache_set_decode_parts", "zsm_decode_parts",
-    "zsm_cache_export", "zsm_cache_import",
+    "zsm_cache_export", "zsm_cache_import", "zsm_cache_flags", "zsm_set_debug_checks",
     "zsm_stream_read", "zsm_stream_copy", "zsm_strerror",
 ]
 
@@ -73,6 +73,10 @@ def lib() -> C.CDLL:
         L.zsm_cache_export.argtypes = [vp, i32] + [vp] * 8 + [vp]
         L.zsm_cache_import.restype = C.c_int
         L.zsm_cache_import.argtypes = [vp, i32] + [vp] * 8 + [vp]
+        L.zsm_cache_flags.restype = C.c_int
+        L.zsm_cache_flags.argtypes = [vp, i32, vp, i32, vp]
+        L.zsm_set_debug_checks.restype = C.c_int
+        L.zsm_set_debug_checks.argtypes = [i32]
         L.zsm_stream_read.restype = C.c_int
         L.zsm_stream_read.argtypes = [vp, sz, vp, vp]
         L.zsm_stream_copy.restype = C.c_int
@@ -174,6 +178,14 @@ def zsm_cache_import(handle, layer, K=None, V=None, Kr=None, Vr=None, s=None, po
     _check(rc, "zsm_cache_import")
 
 
+def zsm_cache_flags(handle, layer, flags=None, clear=False, stream=None) -> None:
+    _check(lib().zsm_cache_flags(handle, int(layer), _ptr(flags), 1 if clear else 0, _stream(stream)), "zsm_cache_flags")
+
+
+def zsm_set_debug_checks(on) -> int:
+    return int(lib().zsm_set_debug_checks(1 if on else 0))
+
+
 def zsm_stream_read(src: torch.Tensor, sink: torch.Tensor, stream=None) -> None:
     _check(lib().zsm_stream_read(_ptr(src), src.numel() * src.element_size(), _ptr(sink), _stream(stream)), "zsm_stream_read")
 
@@ -269,6 +281,13 @@ class Cache:
 
     def decode_parts(self, layer_begin=0, layer_end=None) -> int:
         return zsm_decode_parts(self.handle, layer_begin, self.L if layer_end is None else layer_end)
+
+    def flags(self, layer: int, clear: bool = False) -> torch.Tensor:
+        """The layer's sticky condition bits, int32 [S, H] (device tensor)."""
+        out = torch.empty(self.S, self.H, dtype=torch.int32, device=self.device)
+        with torch.cuda.device(self.device):
+            zsm_cache_flags(self.handle, layer, out, clear)
+        return out
 
     def export_layer(self, layer: int) -> dict:
         S, H, d, cap, Br = self.S, self.H, self.d, self.cap, self.B_r

@@ -2,9 +2,11 @@
 // launches.  No device memory is allocated or freed here.
 #include <hip/hip_runtime.h>
 
+#include <atomic>
 #include <cmath>
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <vector>
 
@@ -21,6 +23,7 @@ struct zsm_cache {
     std::vector<int32_t> Bp, Bc;
     size_t bytes;
     int max_btok;   // max over sequences of B_p + B_c
+    int32_t* dbg;   // device: one counter for the optional state checks
     int parts;      // workgroups per unit in the decode step: 0 = chosen per launch, 1 = never split, n = n
 };
 
@@ -58,9 +61,22 @@ constexpr int SP_TARGET_WGS = 512;    // what an automatically split launch aims
 
 // Section offsets inside the caller's buffer.
 struct Layout {
-    size_t Bp, Bc, n_seen, n_occ, s, pos, w, Kr, Vr, Kt, Vt, sp_L, sp_acc, sp_E, total;
+    size_t Bp, Bc, n_seen, n_occ, flags, dbg, s, pos, w, Kr, Vr, Kt, Vt, sp_L, sp_acc, sp_E, total;
     int sp_max_units, sp_max_wgs;
 };
+
+// Scratch of a split decode launch of n_wgs workgroups over n_units units: offsets from a
+// 256-byte aligned base, and the total.
+struct SplitScratch { size_t L, acc, E, total; };
+SplitScratch split_scratch(size_t n_wgs, size_t n_units, size_t G, size_t D, size_t cap) {
+    SplitScratch x{};
+    size_t o = 0;
+    x.L = o; o += up256(sizeof(double) * n_wgs * G);
+    x.acc = o; o += up256(sizeof(float) * n_wgs * G * D);
+    x.E = o; o += up256(sizeof(double) * n_units * G * (cap + 1));
+    x.total = o;
+    return x;
+}
 
 Layout make_layout(const zsm_config_t& c) {
     const size_t units = (size_t)c.n_layers * c.n_seqs * c.n_kv_heads;
@@ -71,6 +87,8 @@ Layout make_layout(const zsm_config_t& c) {
     l.Bc = o; o += up256(sizeof(int32_t) * c.n_seqs);
     l.n_seen = o; o += up256(sizeof(int64_t) * units);
     l.n_occ = o; o += up256(sizeof(int32_t) * units);
+    l.flags = o; o += up256(sizeof(int32_t) * units);
+    l.dbg = o; o += 256;                                  // one counter for the optional state checks
     l.s = o; o += up256(sizeof(float) * units * cap);
     l.pos = o; o += up256(sizeof(int32_t) * units * cap);
     l.w = o; o += up256(sizeof(int32_t) * units * cap);
@@ -80,10 +98,9 @@ Layout make_layout(const zsm_config_t& c) {
     l.Vt = o; o += up256(esize(c.kv_dtype) * units * (cap - Br) * D);
     l.sp_max_units = (int)(units < (size_t)SP_MAX_UNITS ? units : (size_t)SP_MAX_UNITS);
     l.sp_max_wgs = l.sp_max_units * SP_MAX_PARTS < SP_MAX_WGS ? l.sp_max_units * SP_MAX_PARTS : SP_MAX_WGS;
-    const size_t G = c.q_per_kv;
-    l.sp_L = o; o += up256(sizeof(double) * l.sp_max_wgs * G);
-    l.sp_acc = o; o += up256(sizeof(float) * l.sp_max_wgs * G * D);
-    l.sp_E = o; o += up256(sizeof(double) * l.sp_max_units * G * (cap + 1));
+    const SplitScratch sp = split_scratch(l.sp_max_wgs, l.sp_max_units, c.q_per_kv, D, cap);
+    l.sp_L = o + sp.L; l.sp_acc = o + sp.acc; l.sp_E = o + sp.E;
+    o += sp.total;
     l.total = o;
     return l;
 }
@@ -123,6 +140,55 @@ __global__ __launch_bounds__(256) void stream_read_kernel(const uint4* __restric
 __global__ __launch_bounds__(256) void stream_copy_kernel(uint4* __restrict__ dst, const uint4* __restrict__ src, size_t n16) {
     const size_t stride = (size_t)gridDim.x * blockDim.x;
     for (size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x; i < n16; i += stride) dst[i] = src[i];
+}
+
+// ---- optional state checks (zsm_set_debug_checks) ------------------------------------------
+std::atomic<int> g_debug_checks{0};
+
+// counts the units of one layer that are not empty (a token seen, or an occupied slot)
+__global__ void check_empty_kernel(CacheView cv, int unit0, int32_t* bad) {
+    const int ug = unit0 + blockIdx.x;
+    int n = 0;
+    if (threadIdx.x == 0) n += cv.n_seen[ug] != 0 || cv.n_occ[ug] != 0;
+    for (int j = threadIdx.x; j < cv.cap; j += blockDim.x)
+        n += cv.w[(size_t)ug * cv.cap + j] != 0 || cv.pos[(size_t)ug * cv.cap + j] != -1;
+    if (n) atomicAdd(bad, 1);
+}
+
+// counts the slots of one layer that break what zsm_cache_import asks of a state; an array the
+// caller does not pass is taken from the cache (the state after the import is what is checked)
+__global__ void check_import_kernel(CacheView cv, int unit0, const int32_t* pos_u, const int32_t* w_u,
+                                    const int64_t* n_seen_u, int32_t* bad) {
+    const int lu = blockIdx.x, ug = unit0 + lu;
+    const int b = (ug / cv.H) % cv.S;
+    const int B = cv.Bp[b] + cv.Bc[b] + cv.Br;
+    const int32_t* pos = pos_u ? pos_u + (size_t)lu * cv.cap : cv.pos + (size_t)ug * cv.cap;
+    const int32_t* w = w_u ? w_u + (size_t)lu * cv.cap : cv.w + (size_t)ug * cv.cap;
+    const long long T = n_seen_u ? n_seen_u[lu] : cv.n_seen[ug];
+    int n = threadIdx.x == 0 && T < 0;
+    for (int j = threadIdx.x; j < cv.cap; j += blockDim.x) {
+        const int p = pos[j], c = w[j];
+        bool ok = c >= 0 && p >= -1 && (c == 0) == (p == -1);   // empty exactly where no position is recorded
+        if (p >= 0) ok = ok && (long long)p < T;                  // positions lie below the tokens seen
+        if (j >= cv.Br) ok = ok && c <= 1;          // a token slot holds one token
+        if (j >= B) ok = ok && c == 0;              // slots past the sequence's budget stay empty
+        n += !ok;
+    }
+    if (n) atomicAdd(bad, n);
+}
+
+// runs one of the checks: clears the counter, launches, waits for the stream, reads the counter back
+template <typename Launch>
+int run_state_check(zsm_cache_t* c, hipStream_t st, Launch launch, const char* what) {
+    hipLaunchKernelGGL(fill_i32_kernel, dim3(1), dim3(64), 0, st, c->dbg, (size_t)1, 0);
+    launch();
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return hip_fail(e, what);
+    int32_t bad = 0;
+    e = hipMemcpyAsync(&bad, c->dbg, sizeof(bad), hipMemcpyDeviceToHost, st);
+    if (e == hipSuccess) e = hipStreamSynchronize(st);
+    if (e != hipSuccess) return hip_fail(e, what);
+    return bad ? ZSM_E_STATE : ZSM_OK;
 }
 
 // Workgroups per unit for a decode launch of n_units units (and the token rows one part's LDS
@@ -208,6 +274,8 @@ int zsm_cache_alloc(const zsm_config_t* cfg, const int32_t* B_p, const int32_t* 
     v.Bc = reinterpret_cast<int32_t*>(base + lay.Bc);
     v.n_seen = reinterpret_cast<int64_t*>(base + lay.n_seen);
     v.n_occ = reinterpret_cast<int32_t*>(base + lay.n_occ);
+    v.flags = reinterpret_cast<int32_t*>(base + lay.flags);
+    c->dbg = reinterpret_cast<int32_t*>(base + lay.dbg);
     v.s = reinterpret_cast<float*>(base + lay.s);
     v.pos = reinterpret_cast<int32_t*>(base + lay.pos);
     v.w = reinterpret_cast<int32_t*>(base + lay.w);
@@ -229,7 +297,7 @@ int zsm_cache_alloc(const zsm_config_t* cfg, const int32_t* B_p, const int32_t* 
     if (e == hipSuccess) e = hipMemcpyAsync(v.Bc, c->Bc.data(), sizeof(int32_t) * v.S, hipMemcpyHostToDevice, st);
     if (e != hipSuccess) { delete c; return hip_fail(e, "zsm_cache_alloc budgets"); }
     // empty state: pos = -1, everything else 0 (fill kernels, no memset nodes)
-    const size_t n_zero_words = (lay.pos - lay.n_seen) / 4;   // n_seen, n_occ, s
+    const size_t n_zero_words = (lay.pos - lay.n_seen) / 4;   // n_seen, n_occ, flags, check counter, s
     hipLaunchKernelGGL(fill_i32_kernel, dim3(1024), dim3(256), 0, st, reinterpret_cast<int32_t*>(base + lay.n_seen), n_zero_words, 0);
     hipLaunchKernelGGL(fill_i32_kernel, dim3(1024), dim3(256), 0, st, v.pos, units * v.cap, -1);
     const size_t n_rest_words = (lay.total - lay.w) / 4;      // w, Kr, Vr, Kt, Vt, split scratch
@@ -246,9 +314,12 @@ int zsm_cache_free(zsm_cache_t* cache) {
     return ZSM_OK;
 }
 
-int zsm_decode_step(zsm_cache_t* cache, int32_t layer_begin, int32_t layer_end, const void* q,
-                    const void* k_new, const void* v_new, float* out, int32_t* write_slot,
-                    int32_t* evicted_pos, int32_t* merged_slot, void* stream) {
+// Shared body of the decode entry points.  `scratch` = NULL: a split launch keeps its partial results in the
+// cache buffer's own scratch section; otherwise in the `scratch_bytes` bytes at `scratch` (256-byte aligned).
+static int decode_step_impl(zsm_cache_t* cache, int32_t layer_begin, int32_t layer_end, const void* q,
+                            const void* k_new, const void* v_new, float* out, int32_t* write_slot,
+                            int32_t* evicted_pos, int32_t* merged_slot, void* stream, char* scratch,
+                            size_t scratch_bytes) {
     if (!cache || !q || !k_new || !v_new || !out) return ZSM_E_NULL;
     if (layer_begin < 0 || layer_end > cache->cfg.n_layers || layer_begin >= layer_end) return ZSM_E_RANGE;
     if (!aligned16(q) || !aligned16(k_new) || !aligned16(v_new) || !aligned16(out)) return ZSM_E_ALIGN;
@@ -259,6 +330,13 @@ int zsm_decode_step(zsm_cache_t* cache, int32_t layer_begin, int32_t layer_end, 
     if (parts < 0) return parts;
     DecodeArgs a;
     a.cv = v;
+    if (scratch && parts > 1) {
+        const SplitScratch sp = split_scratch((size_t)n_units * parts, n_units, v.G, v.D, v.cap);
+        if (sp.total > scratch_bytes) return ZSM_E_NOMEM;
+        a.cv.sp_L = reinterpret_cast<double*>(scratch + sp.L);
+        a.cv.sp_acc = reinterpret_cast<float*>(scratch + sp.acc);
+        a.cv.sp_E = reinterpret_cast<double*>(scratch + sp.E);
+    }
     a.unit0 = layer_begin * v.S * v.H;
     a.n_units = n_units;
     a.parts = parts;
@@ -274,6 +352,13 @@ int zsm_decode_step(zsm_cache_t* cache, int32_t layer_begin, int32_t layer_end, 
     }
     if (e != hipSuccess) return hip_fail(e, "zsm_decode_step launch");
     return ZSM_OK;
+}
+
+int zsm_decode_step(zsm_cache_t* cache, int32_t layer_begin, int32_t layer_end, const void* q,
+                    const void* k_new, const void* v_new, float* out, int32_t* write_slot,
+                    int32_t* evicted_pos, int32_t* merged_slot, void* stream) {
+    return decode_step_impl(cache, layer_begin, layer_end, q, k_new, v_new, out, write_slot, evicted_pos, merged_slot,
+                            stream, nullptr, 0);
 }
 
 int zsm_cache_set_decode_parts(zsm_cache_t* cache, int32_t parts) {
@@ -306,6 +391,14 @@ int zsm_prefill_compress(zsm_cache_t* cache, int32_t layer, const void* Q, int32
     if (!aligned16(Q) || !aligned16(K) || !aligned16(V)) return ZSM_E_ALIGN;
     if ((reinterpret_cast<uintptr_t>(workspace) & 255) != 0) return ZSM_E_ALIGN;
     if (ws_bytes < prefill_workspace_bytes(cache->cv, T_max, W)) return ZSM_E_NOMEM;
+    if (g_debug_checks.load(std::memory_order_relaxed)) {
+        hipStream_t st = static_cast<hipStream_t>(stream);
+        const int lu = cache->cv.S * cache->cv.H;
+        rc = run_state_check(cache, st, [&] {
+            hipLaunchKernelGGL(check_empty_kernel, dim3(lu), dim3(256), 0, st, cache->cv, layer * lu, cache->dbg);
+        }, "zsm_prefill_compress state check");
+        if (rc) return rc;
+    }
     PrefillArgs a;
     a.cv = cache->cv;
     a.unit0 = layer * cache->cv.S * cache->cv.H;
@@ -370,6 +463,14 @@ int zsm_cache_import(zsm_cache_t* cache, int32_t layer, const void* K, const voi
     int rc = check_layer(cache, layer);
     if (rc) return rc;
     hipStream_t st = static_cast<hipStream_t>(stream);
+    if (g_debug_checks.load(std::memory_order_relaxed)) {
+        if ((pos && !aligned16(pos)) || (w && !aligned16(w)) || (n_seen && !aligned16(n_seen))) return ZSM_E_ALIGN;
+        const int lu0 = cache->cv.S * cache->cv.H;
+        rc = run_state_check(cache, st, [&] {
+            hipLaunchKernelGGL(check_import_kernel, dim3(lu0), dim3(256), 0, st, cache->cv, layer * lu0, pos, w, n_seen, cache->dbg);
+        }, "zsm_cache_import state check");
+        if (rc) return rc;
+    }
     rc = xfer(cache, layer, const_cast<void*>(K), const_cast<void*>(V), const_cast<float*>(Kr),
               const_cast<float*>(Vr), const_cast<float*>(s), const_cast<int32_t*>(pos),
               const_cast<int32_t*>(w), const_cast<int64_t*>(n_seen), st, true);
@@ -379,6 +480,29 @@ int zsm_cache_import(zsm_cache_t* cache, int32_t layer, const void* K, const voi
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return hip_fail(e, "zsm_cache_import recount");
     return ZSM_OK;
+}
+
+__global__ void flags_out_kernel(int32_t* flags, int32_t* out, int n, int clear) {
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= n) return;
+    if (out) out[i] = flags[i];
+    if (clear) flags[i] = 0;
+}
+
+int zsm_cache_flags(zsm_cache_t* cache, int32_t layer, int32_t* flags, int32_t clear, void* stream) {
+    int rc = check_layer(cache, layer);
+    if (rc) return rc;
+    if (!flags && !clear) return ZSM_E_NULL;
+    const int lu = cache->cv.S * cache->cv.H;
+    hipLaunchKernelGGL(flags_out_kernel, dim3((lu + 255) / 256), dim3(256), 0, static_cast<hipStream_t>(stream),
+                       cache->cv.flags + (size_t)layer * lu, flags, lu, clear ? 1 : 0);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return hip_fail(e, "zsm_cache_flags");
+    return ZSM_OK;
+}
+
+int zsm_set_debug_checks(int32_t on) {
+    return g_debug_checks.exchange(on ? 1 : 0);
 }
 
 int zsm_stream_read(const void* src, size_t bytes, float* sink, void* stream) {
@@ -414,6 +538,7 @@ const char* zsm_strerror(int status) {
         case ZSM_E_ALIGN: return "device pointer not sufficiently aligned";
         case ZSM_E_NOMEM: return "buffer or workspace too small";
         case ZSM_E_RANGE: return "layer index or range outside the cache";
+        case ZSM_E_STATE: return "the cache state breaks the call's precondition (found by the optional state checks)";
         case ZSM_E_HIP: return g_hip_msg;
         default: return "unknown status";
     }

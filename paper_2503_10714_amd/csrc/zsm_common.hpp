@@ -23,6 +23,7 @@ struct CacheView {
     int32_t* Bc;        // [S]
     int64_t* n_seen;    // [units]   tokens seen (T)
     int32_t* n_occ;     // [units]   occupied token slots
+    int32_t* flags;     // [units]   sticky condition bits (ZSM_FLAG_*), set by the kernels, never cleared by them
     float* s;           // [units][cap]
     int32_t* pos;       // [units][cap]
     int32_t* w;         // [units][cap]
@@ -37,6 +38,15 @@ struct CacheView {
     float* sp_acc;         // [sp_max_wgs][G][D]      the parts' outputs, each normalised by its own denominator
     double* sp_E;          // [sp_max_units][G][cap+1] exp(logit - C) of every slot
 };
+
+// Condition bits a kernel may raise in CacheView::flags (mirrored by include/zsm.h).
+constexpr int32_t FLAG_DECODE_SPREAD = 1;    // decode step: a softmax denominator (relative to the incoming token's own logit) reached SPREAD_FLAG_SUM
+constexpr int32_t FLAG_PREFILL_SPREAD = 2;   // prefill scoring: a row's softmax denominator (relative to its own position's logit) reached SPREAD_FLAG_SUM
+// exp(logit - reference) is evaluated in fp64, which holds e^709; differences are clamped here
+constexpr double LOGIT_SPREAD_MAX = 690.0;
+// A sum of such exponentials that reaches e^680 raises the flag: a clamped term alone exceeds it, and sums of
+// unclamped terms reach it only when some logit is within ln(number of terms) of 680 above the reference.
+constexpr double SPREAD_FLAG_SUM = 1.7e295;   // just under e^680 = 1.77e295
 
 // ---- element access -------------------------------------------------------------------
 // load_seg<KT, N>(p, out): N consecutive elements starting at p (16-byte aligned when

@@ -17,8 +17,13 @@
 // exactly rounded dot products and the eviction choice does not depend on the summation
 // order of this kernel.  The attention output uses fp32 probabilities and accumulators.
 // With fp64 exponentials no running maximum is needed: exp(z - C) cannot overflow unless a
-// logit exceeds the incoming token's by more than 690, at which the difference is clamped.
+// logit exceeds the incoming token's by more than LOGIT_SPREAD_MAX (690); there the difference
+// is clamped (the slots beyond it tie).  A softmax denominator that reaches SPREAD_FLAG_SUM
+// (e^680: one logit 680 above the reference, or many a little lower) raises the unit's
+// FLAG_DECODE_SPREAD bit, so the clamp never acts unseen.
 #pragma once
+
+#include <atomic>
 
 #include "zsm_common.hpp"
 
@@ -155,7 +160,7 @@ __device__ __forceinline__ void k_compute(const Raw<KT, EPL>* kr, int row0, int 
 #pragma unroll
                     for (int i = 0; i < LPR; ++i) a += part_w[lane * (LPR + 1) + i];
                     const double z = a * scale + addend;
-                    ev = exp(fmin(z - C[g], 690.0));
+                    ev = exp(fmin(z - C[g], LOGIT_SPREAD_MAX));
                     lsum[g] += ev;
                 }
                 et[(size_t)g * Bz + zidx0 + hr] = ev;
@@ -285,7 +290,7 @@ __device__ __forceinline__ void k_compute_gq(const Raw<KT, EPL>* kr, int row0, i
         for (int i = 0; i < Own::NVF; ++i) {
             const int row = row0 + ((v0 + i) % UH) * RPL + grp;
             if (row < nrows) {
-                const double ev = exp(fmin(pp[i] * scale - c_own, 690.0));
+                const double ev = exp(fmin(pp[i] * scale - c_own, LOGIT_SPREAD_MAX));
                 lsum_own += ev;
                 et[(size_t)g_own * Bz + zidx0 + row] = ev;
             }
@@ -334,7 +339,7 @@ __device__ __forceinline__ void k_compute_mfma4(const Raw<KT, EPL>* kr, const do
     if (row < nrows) {
 #pragma unroll
         for (int h = 0; h < NG; ++h) {
-            const double ev = exp(fmin((d0[h] + d1[h]) * scale - c_own[h], 690.0));
+            const double ev = exp(fmin((d0[h] + d1[h]) * scale - c_own[h], LOGIT_SPREAD_MAX));
             lsum_own[h] += ev;
             et_own[(size_t)4 * h * Bz + zidx0 + row] = ev;   // et_own = et + (lane / 16) * Bz
         }
@@ -665,9 +670,10 @@ __device__ __forceinline__ void decode_finish(const DecodeArgs& a, const CacheVi
     }
 }
 
-// Occupancy target: 4 waves per SIMD for G = 1 (four workgroups per compute unit, LDS permitting);
-// the per-head state of grouped queries needs more registers and its LDS footprint caps the
-// residency anyway.
+// Occupancy bound: 4 waves per SIMD for G = 1 (four workgroups per compute unit, LDS permitting).
+// Grouped queries are bounded at 2 (up to 256 registers): their per-head state needs more than
+// 128, and what they really use decides the residency (the matrix-core pass takes about 165, which
+// gives three workgroups per compute unit; the LDS footprint of a large budget caps it further).
 //
 // SPLIT = false: one workgroup per unit does everything.
 // SPLIT = true: a.parts workgroups per unit.  Part p sweeps a contiguous range of the token
@@ -678,7 +684,7 @@ __device__ __forceinline__ void decode_finish(const DecodeArgs& a, const CacheVi
 //   boundary is what makes one workgroup's scratch visible to another: fences inside one
 //   kernel cost more here than the whole sweep of a small launch).
 template <typename T, int D, int G, int NW, bool SPLIT>
-__global__ __launch_bounds__(NW * 64, (G == 1 ? 4 : (G < 2 ? 3 : 2))) void decode_kernel(DecodeArgs a) {
+__global__ __launch_bounds__(NW * 64, G == 1 ? 4 : 2) void decode_kernel(DecodeArgs a) {
     using Sh = DecodeShape<T, D, G, NW>;
     constexpr int EPL = Sh::EPL, LPR = Sh::LPR, RPL = Sh::RPL, R = Sh::R, PART = Sh::PART, NT = Sh::NT, UT = Sh::UT;
     constexpr bool QLDS = Sh::QLDS;
@@ -896,6 +902,7 @@ __global__ __launch_bounds__(NW * 64, (G == 1 ? 4 : (G < 2 ? 3 : 2))) void decod
 #pragma unroll
         for (int x = 0; x < NW; ++x) t += red64[x * G + g];
         rL[g] = SPLIT ? (t > 0.0 ? 1.0 / t : 0.0) : 1.0 / t;   // the unit's own denominator counts the incoming token: >= 1
+        if (t >= SPREAD_FLAG_SUM && tid == 0) atomicOr(cv.flags + ug, FLAG_DECODE_SPREAD);   // practically never taken
     }
 
     // ---- pass 2 (D2): sum p * v over this workgroup's slots ------------------------------
@@ -1079,12 +1086,17 @@ inline hipError_t launch_decode_dgs(const DecodeArgs& a, hipStream_t stream) {
     using Sh = DecodeShape<T, D, G, DECODE_NW>;
     const size_t lds = Sh::lds_bytes(SPLIT ? a.part_rows + a.cv.Br + 1 : a.cv.cap + 1);
     auto kern = decode_kernel<T, D, G, DECODE_NW, SPLIT>;
-    static bool attr_set = false;
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+    // The attribute is per device; bit `dev` records that it has been set there.  Two host threads that
+    // meet here for the first time may both set it (harmless: same value), neither reads a torn flag.
+    static std::atomic<unsigned long long> attr_done{0ull};
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    const unsigned long long bit = 1ull << (dev & 63);
+    if (!(attr_done.load(std::memory_order_acquire) & bit)) {
+        e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
         if (e != hipSuccess) return e;
-        attr_set = true;
+        attr_done.fetch_or(bit, std::memory_order_release);
     }
     hipLaunchKernelGGL(kern, dim3(a.n_units * (SPLIT ? a.parts : 1)), dim3(DECODE_NW * 64), lds, stream, a);
     if (SPLIT) hipLaunchKernelGGL((decode_combine_kernel<T, D, G, DECODE_NW>), dim3(a.n_units), dim3(DECODE_NW * 64), 0, stream, a);

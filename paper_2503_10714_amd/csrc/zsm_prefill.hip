@@ -43,8 +43,9 @@ __global__ void pf_convert_q(const T* __restrict__ Q, double* __restrict__ Qd, i
 
 // ---- reference logit of every query row: the row's own key (Eq. 1 with t = i) -------------
 // With fp64 exponentials a softmax row needs no running maximum, only a reference that keeps
-// exp() in range; the query's logit against its own position is one (differences are clamped
-// at 690, far outside anything a softmax in the storage precision could resolve).
+// exp() in range; the query's logit against its own position is one.  A key whose logit is more
+// than LOGIT_SPREAD_MAX (690) above it is clamped there; pf_row_combine raises the unit's
+// FLAG_PREFILL_SPREAD when a row's denominator reaches SPREAD_FLAG_SUM, so the clamp never acts unseen.
 template <typename T, int D>
 __global__ __launch_bounds__(64) void pf_self_logit(PrefillArgs a, PrefillWs ws) {
     const CacheView& cv = a.cv;
@@ -223,7 +224,7 @@ __global__ __launch_bounds__(256, MODE == 2 ? 3 : 4) void pf_score_mfma(PrefillA
                         for (int kb = 0; kb < KB; ++kb) {
                             const int t = t0 + 16 * kb + j;
                             const bool ok = valid && t <= qp;
-                            const double ev = exp(fmin(acc[rb][kb][r] * scale - rmv, 690.0));
+                            const double ev = exp(fmin(acc[rb][kb][r] * scale - rmv, LOGIT_SPREAD_MAX));
                             if (MODE != 1) lsum[rb][r] += ok ? ev : 0.0;
                             else sp[kb] += ok ? rwv * ev : 0.0;
                             if (MODE == 2 && t < Tb) ep[kb][16 * rb + 4 * r] = ev;   // masked entries are never read back
@@ -351,6 +352,7 @@ __global__ void pf_row_combine(PrefillArgs a, PrefillWs ws) {
         const size_t row = ((size_t)lu * G + g) * Wp + r;
         double L = 0.0;
         for (int x = 0; x < nt; ++x) L += pl[row * ws.nsums + x];
+        if (L >= SPREAD_FLAG_SUM) atomicOr(cv.flags + a.unit0 + lu, FLAG_PREFILL_SPREAD);   // practically never taken
         roww[row] = pow(lam, (double)(nb - 1 - r)) / ((double)G * L);
     }
     // rows that pad the last 32-row pass carry no weight

@@ -125,6 +125,7 @@ class Workload:
     lam: float = 0.98
     alpha: float = 1.0
     seed: int = MASTER_SEED
+    k_gain: float = 1.0    # every key (prompt and decode) is multiplied by this: widens the spread of the logits
     layer0: int = 0        # first layer id (for slicing a deep workload)
     seq0: int = 0
     head0: int = 0
@@ -256,6 +257,8 @@ def kv_rows(wl: Workload, layer: int, pos: torch.Tensor, *, decode: bool = False
         c = torch.where(c == 4.0, torch.zeros_like(c), c)
     K = K + (c[..., None] * (d ** 0.25)) * u[None, :, None, :]
     K = K * mult[None, :, None, :]
+    if wl.k_gain != 1.0:
+        K = K * wl.k_gain
     return to_storage(K, wl.dtype), to_storage(V, wl.dtype)
 
 

@@ -180,9 +180,52 @@ def make_cache(wl: synth.Workload, device="cuda:0"):
                  lam=wl.lam, alpha=wl.alpha, slot_capacity=wl.slot_capacity, device=device)
 
 
+def check_every_unit(wl: synth.Workload, cache, steps_done: int, layers: Optional[Sequence[int]] = None) -> None:
+    """Invariants of Alg. 1 that hold for EVERY unit at any size, checked on the device (torch ops on the
+    exported metadata): tokens seen = prompt + steps; fusion counts sum to the tokens seen (B_r > 0); a slot is
+    empty exactly where it has no position; token slots hold one token each, at distinct positions below the
+    tokens seen, the latest B_p positions among them; the occupied token slots are min(T, B_p + B_c) many (what
+    the kernels' own occupancy counter must say for them to take the right path); slots past B stay empty."""
+    from paper_2503_10714_amd import binding as zb
+    S, H, cap, Br = cache.S, cache.H, cache.cap, cache.B_r
+    dev = cache.device
+    bp, bc, _ = wl.budgets()
+    lens = torch.tensor(wl.seq_lens(), dtype=torch.int64, device=dev)[:, None]            # [S,1]
+    ntok = torch.tensor([p + c for p, c in zip(bp, bc)], dtype=torch.int64, device=dev)[:, None]
+    bpt = torch.tensor(bp, dtype=torch.int64, device=dev)[:, None]
+    pos = torch.empty(S, H, cap, dtype=torch.int32, device=dev)
+    w = torch.empty(S, H, cap, dtype=torch.int32, device=dev)
+    n_seen = torch.empty(S, H, dtype=torch.int64, device=dev)
+    idx = torch.arange(cap, device=dev)[None, None, :]
+    for l in (range(wl.n_layers) if layers is None else layers):
+        with torch.cuda.device(dev):
+            zb.zsm_cache_export(cache.handle, l, pos=pos, w=w, n_seen=n_seen)
+        tag = f"{wl.name} layer {l} after {steps_done} steps"
+        T = lens + steps_done
+        assert bool((n_seen == T).all()), f"{tag}: tokens seen"
+        occ = w > 0
+        assert bool((occ == (pos >= 0)).all()), f"{tag}: empty slots and positions disagree"
+        assert bool((pos.to(torch.int64) < T[:, :, None]).all()), f"{tag}: a position at or past the tokens seen"
+        past = idx >= (ntok[:, :, None] + Br)
+        assert bool((~occ | ~past).all()), f"{tag}: a slot past the budget is occupied"
+        if Br > 0:
+            assert bool((w.sum(-1, dtype=torch.int64) == T).all()), f"{tag}: fusion counts do not sum to the tokens seen"
+        tw, tp = w[..., Br:], pos[..., Br:].to(torch.int64)
+        assert bool((tw <= 1).all()), f"{tag}: a token slot with a fusion count above 1"
+        n_occ = (tw > 0).sum(-1)
+        assert bool((n_occ == torch.minimum(T, ntok)).all()), f"{tag}: occupied token slots"
+        # distinct positions: empty slots get distinct negative stand-ins, then a sort must be strictly increasing
+        key = torch.where(tw > 0, tp, -1 - torch.arange(cap - Br, device=dev)[None, None, :])
+        srt = torch.sort(key, dim=-1).values
+        assert bool((srt[..., 1:] > srt[..., :-1]).all()), f"{tag}: two token slots hold the same position"
+        # the latest min(B_p, T) positions are all present (nothing inside the proximity window is ever evicted)
+        n_recent = ((tw > 0) & (tp >= (T - bpt)[:, :, None])).sum(-1)
+        assert bool((n_recent == torch.minimum(T, bpt)).all()), f"{tag}: a token of the latest B_p is missing"
+
+
 def run_decode_parity(wl: synth.Workload, cache, units_by_layer: List[List[List[UnitCache]]], n_steps: int,
                       sel: Optional[Sequence[Tuple[int, int, int]]] = None, gen_device="cpu",
-                      state_every: int = 0, first_step: int = 0) -> StepStats:
+                      state_every: int = 0, first_step: int = 0, after_step=None) -> StepStats:
     """Lock-step decode of GPU cache and oracle units; all layers per launch.
 
     sel: (layer, b, h) triples to check (default: all).  state_every: also compare the
@@ -213,6 +256,8 @@ def run_decode_parity(wl: synth.Workload, cache, units_by_layer: List[List[List[
             assert sel is None, "a near tie in a sampled run cannot be re-synchronised"
             cache.import_layer(l, **pack_states(units_by_layer[l], cache.cap, cache.B_r, d, cache.kv_dtype))
         stats.steps += 1
+        if after_step is not None:
+            after_step(step + 1)
         if state_every and (step + 1) % state_every == 0 and step + 1 < first_step + n_steps:
             compare_all_state(wl, cache, units_by_layer, tol, f"after step {step}", sel)
     compare_all_state(wl, cache, units_by_layer, tol, "final", sel, stats)

@@ -47,7 +47,7 @@ def test_cache_bytes_and_config_checks(zb):
     # per-slot exponentials (fp64)
     wgs = min(units * 64, 8192)
     scratch = wgs * 8 + wgs * 128 * 4 + units * 206 * 8
-    assert kv + scratch <= n <= kv + scratch + units * 205 * 12 + 2 * units * 128 * 4 + units * 12 + 20 * 256
+    assert kv + scratch <= n <= kv + scratch + units * 205 * 12 + 2 * units * 128 * 4 + units * 16 + 22 * 256
     assert zb.zsm_cache_bytes(zb.make_config(2, 3, 4, 3, 128, 205, 1, "f16")) == 0      # G = 3
     assert zb.zsm_cache_bytes(zb.make_config(2, 3, 4, 1, 96, 205, 1, "f16")) == 0       # d = 96
     assert zb.zsm_cache_bytes(zb.make_config(2, 3, 4, 1, 128, 1, 1, "f16")) == 0        # no token slot

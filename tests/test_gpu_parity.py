@@ -345,7 +345,9 @@ def test_workload2_full_size_sampled_units():
     cache.release_workspace()
     pu.compare_all_state(wl, cache, units, pu.tol_for(wl.dtype), "after prefill", sample)
     print("[step] prefill parity ok on the sampled units", flush=True)
-    st = pu.run_decode_parity(wl, cache, units, 8, sel=sample, gen_device=DEV)
+    pu.check_every_unit(wl, cache, 0)
+    st = pu.run_decode_parity(wl, cache, units, 8, sel=sample, gen_device=DEV,
+                              after_step=lambda n: pu.check_every_unit(wl, cache, n))
     print(f"[done] workload 2 full size: unit-steps={st.unit_steps} evictions={st.evictions} near_ties={st.near_ties} "
           f"max|out err|={st.max_out_err:.2e} scores bit-equal {st.s_bit_equal}/{st.s_total}", flush=True)
     assert st.evictions == st.unit_steps
@@ -382,6 +384,166 @@ def test_full_layer_sampled_units(w, sample):
     assert st.evictions == st.unit_steps
     n_seen = cache.export_layer(0)["n_seen"].cpu()
     assert (n_seen == torch.tensor(lens)[:, None] + 6).all()
+    cache.close()
+
+
+def prompt_in_chunks(wl, layer, seqs_per_chunk):
+    """synth.prompt of a whole layer on the device, generated a few sequences at a time: the generator works in fp64
+    and its temporaries for 64 sequences of 16 K tokens would not fit beside a 42 GB cache."""
+    Qs, Ks, Vs, lens = [], [], [], []
+    for b0 in range(0, wl.n_seqs, seqs_per_chunk):
+        seqs = list(range(wl.seq0 + b0, wl.seq0 + min(wl.n_seqs, b0 + seqs_per_chunk)))
+        Q, K, V, ln = synth.prompt(wl, layer, seqs=seqs, device=DEV)
+        Qs.append(Q); Ks.append(K); Vs.append(V); lens += ln
+    if len(Ks) == 1:
+        return Qs[0], Ks[0], Vs[0], lens
+    return torch.cat(Qs), torch.cat(Ks), torch.cat(Vs), lens
+
+
+@pytest.mark.parametrize("w,sample", [(3, [(0, 0, 0), (9, 17, 9), (20, 40, 31), (31, 63, 12)]),
+                                      (4, [(0, 0, 0), (11, 7, 3), (22, 15, 7), (31, 9, 5)])])
+def test_full_depth_sampled_units(w, sample):
+    """The batched workloads at full depth, in the launch shape the benchmark times (workload 3: 32 layers x 64 ragged
+    sequences x 32 heads = 65 536 units in one launch; workload 4: 32 x 16 x 8 = 4096 units of four query heads):
+    every layer is compressed on the device, a sample of units spread over layers and sequences is recomputed by the
+    oracle from the bytes the device read, then all layers step together; after every step the invariants that hold
+    at any size are checked on EVERY unit."""
+    wl = synth.workload(w)
+    n_steps = 8
+    print(f"[case] workload {w} at full depth ({wl.n_units} units), sampled units {sample}", flush=True)
+    cache = pu.make_cache(wl, DEV)
+    units = [[[None] * wl.n_kv_heads for _ in range(wl.n_seqs)] for _ in range(wl.n_layers)]
+    for l in range(wl.n_layers):
+        Q, K, V, lens = prompt_in_chunks(wl, l, 8)
+        cache.prefill_compress(l, Q, K, V, lens)
+        pairs = [(b, h) for (ll, b, h) in sample if ll == l]
+        if pairs:
+            torch.cuda.synchronize()
+            got = pu.oracle_prefill_layer(wl, Q, K, V, lens, sel=pairs)
+            for b, h in pairs:
+                units[l][b][h] = got[b][h]
+            print(f"[step] layer {l}: oracle prefill of {pairs} done", flush=True)
+        del Q, K, V
+        if l % 8 == 7:
+            torch.cuda.synchronize()
+            print(f"[step] {l + 1} layers compressed", flush=True)
+    cache.release_workspace()
+    torch.cuda.empty_cache()
+    pu.compare_all_state(wl, cache, units, pu.tol_for(wl.dtype), "after prefill", sample)
+    pu.check_every_unit(wl, cache, 0)
+    assert cache.decode_parts() == 1       # the launch the benchmark times: one workgroup per unit, all layers at once
+    print("[step] prefill parity ok on the sampled units, invariants hold on every unit", flush=True)
+
+    def after(n):
+        pu.check_every_unit(wl, cache, n)
+        print(f"[step] decode step {n} ok", flush=True)
+
+    st = pu.run_decode_parity(wl, cache, units, n_steps, sel=sample, gen_device=DEV, after_step=after)
+    print(f"[done] workload {w} full depth: unit-steps={st.unit_steps} evictions={st.evictions} near_ties={st.near_ties} "
+          f"max|out err|={st.max_out_err:.2e} scores bit-equal {st.s_bit_equal}/{st.s_total}", flush=True)
+    assert st.evictions == st.unit_steps == n_steps * len(sample)
+    for l in range(wl.n_layers):
+        assert int(cache.flags(l).max()) == 0
+    cache.close()
+
+
+def test_wide_logit_spread_inside_the_limit():
+    """Keys 44 times larger than usual: cached logits exceed the query's own by up to ~425 (prefill rows and
+    decode steps alike), which the fp64 exponentials relative to that own logit must carry exactly: the usual
+    parity bar against the oracle (which subtracts the row maximum), and no spread flag."""
+    wl = small("wide_spread", prompt_len=300, budget=48, decode_steps=40, window=16, k_gain=44.0)
+    print(f"[case] wide logit spread: keys x{wl.k_gain}", flush=True)
+    cache, units = prefill_gpu_and_oracle(wl)
+    pu.compare_all_state(wl, cache, units, pu.tol_for(wl.dtype), "after prefill")
+    st = pu.run_decode_parity(wl, cache, units, wl.decode_steps, state_every=8)
+    assert st.evictions > 0 and st.near_ties == 0
+    assert int(cache.flags(0).max()) == 0
+    # the same once more with the step cut over workgroups (each part keeps the same reference)
+    cache2, units2 = prefill_gpu_and_oracle(wl)
+    cache2.set_decode_parts(3)
+    assert cache2.decode_parts() > 1
+    st2 = pu.run_decode_parity(wl, cache2, units2, wl.decode_steps, state_every=8)
+    assert int(cache2.flags(0).max()) == 0
+    print(f"[done] wide logit spread: max|out err| {st.max_out_err:.2e} / {st2.max_out_err:.2e}", flush=True)
+    cache.close(); cache2.close()
+
+
+def test_logit_spread_beyond_the_limit_is_reported():
+    """Keys 100 times larger: the spread passes 690, the exponentials are clamped there; the calls still return
+    normally and every unit they touched carries the matching sticky bit until it is cleared."""
+    from paper_2503_10714_amd import binding as zb
+    wl = small("too_wide", prompt_len=300, budget=48, decode_steps=4, window=16, k_gain=100.0)
+    cache = pu.make_cache(wl, DEV)
+    Q, K, V, lens = synth.prompt(wl, 0)
+    cache.prefill_compress(0, Q.to(DEV), K.to(DEV), V.to(DEV), lens)
+    f = cache.flags(0)
+    assert bool(((f & 2) != 0).all()) and bool(((f & 1) == 0).all()), f.tolist()
+    for step in range(wl.decode_steps):
+        q, k, v = synth.decode_inputs(wl, 0, step)
+        out, _ = cache.decode_step(q[None].to(DEV), k[None].to(DEV), v[None].to(DEV))
+        assert bool(torch.isfinite(out).all())
+    f = cache.flags(0, clear=True)
+    assert bool(((f & 1) != 0).any()), f.tolist()
+    assert int(cache.flags(0).max()) == 0           # cleared
+    cache.close()
+
+
+def test_state_checks_when_switched_on():
+    """zsm_set_debug_checks: a prefill into a layer that is not empty and an import of a malformed state are refused
+    with ZSM_E_STATE before anything is changed; well-formed calls go through."""
+    from paper_2503_10714_amd import binding as zb
+    wl = small("checks", n_layers=2)
+    units = oracle_states(wl)
+    cache = pu.make_cache(wl, DEV)
+    prev = zb.zsm_set_debug_checks(True)
+    try:
+        Q, K, V, lens = synth.prompt(wl, 0)
+        cache.prefill_compress(0, Q.to(DEV), K.to(DEV), V.to(DEV), lens)         # empty layer: fine
+        before = cache.export_layer(0)
+        with pytest.raises(zb.ZsmError) as e:
+            cache.prefill_compress(0, Q.to(DEV), K.to(DEV), V.to(DEV), lens)     # not empty any more
+        assert e.value.status == -8
+        after = cache.export_layer(0)
+        for key in before:
+            assert torch.equal(before[key], after[key]), key
+        good = pu.pack_states(units[1], cache.cap, cache.B_r, wl.head_dim, cache.kv_dtype)
+        cache.import_layer(1, **good)
+        for name, edit in [("count 2 in a token slot", lambda st: st["w"].__setitem__((0, 0, cache.B_r + 3), 2)),
+                           ("position without a count", lambda st: st["w"].__setitem__((0, 1, cache.B_r + 1), 0)),
+                           ("position past the tokens seen", lambda st: st["pos"].__setitem__((0, 0, cache.B_r), 10 ** 6))]:
+            bad = {k_: v_.clone() for k_, v_ in good.items()}
+            edit(bad)
+            with pytest.raises(zb.ZsmError) as e:
+                cache.import_layer(1, **bad)
+            assert e.value.status == -8, name
+        st1 = cache.export_layer(1)
+        assert torch.equal(st1["w"].cpu(), good["w"]) and torch.equal(st1["pos"].cpu(), good["pos"])   # the rejected imports changed nothing
+    finally:
+        zb.zsm_set_debug_checks(prev)
+    cache.close()
+
+
+def test_resynchronisation_after_a_permitted_flip(monkeypatch):
+    """The harness's answer to a near tie (the device may evict another token when the oracle's two lowest scores
+    differ by less than 1e-6 relative): the oracle's state is imported into the device cache and both go on together.
+    No near tie has ever occurred on the device, so this drives that path by hand: one step is reported as a permitted
+    flip, the layer is re-imported from the oracle, and every later step must still match."""
+    wl = small("resync", n_layers=2, n_kv_heads=3, n_residual=2, dtype="f16", head_dim=128, prompt_len=260, budget=60, decode_steps=24)
+    cache, units = prefill_gpu_and_oracle(wl)
+    real = pu.check_step
+    calls = {"n": 0, "forced": 0}
+
+    def flaky(*a, **kw):
+        r = real(*a, **kw)
+        calls["n"] += 1
+        if calls["n"] in (20, 75):
+            calls["forced"] += 1
+            return True
+        return r
+
+    monkeypatch.setattr(pu, "check_step", flaky)
+    st = pu.run_decode_parity(wl, cache, units, wl.decode_steps, state_every=4)
+    assert calls["forced"] == 2 and st.evictions > 0
     cache.close()
 
 
