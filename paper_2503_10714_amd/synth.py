@@ -207,28 +207,49 @@ def outlier_channels(wl: Workload, layer: int, head: int) -> List[int]:
     return out
 
 
+_CACHE: dict = {}     # small per-(layer, heads) tensors that every call for the same layer needs again
+
+
+def _cached(key, make):
+    if key not in _CACHE:
+        if len(_CACHE) > 4096:
+            _CACHE.clear()
+        _CACHE[key] = make()
+    return _CACHE[key]
+
+
 def _keys(wl: Workload, tid: int, layer: int, seqs: Sequence[int], heads: Sequence[int], device) -> torch.Tensor:
-    ks = [[_signed(key_of(wl.seed, tid, layer, b, h)) for h in heads] for b in seqs]
-    return torch.tensor(ks, dtype=torch.int64, device=device)
+    def make():
+        ks = [[_signed(key_of(wl.seed, tid, layer, b, h)) for h in heads] for b in seqs]
+        return torch.tensor(ks, dtype=torch.int64, device=device)
+    return _cached(("keys", wl.seed, tid, layer, tuple(seqs), tuple(heads), str(device)), make)
 
 
 def _boost_strength(wl: Workload, tid: int, layer: int, seqs, heads, pos: torch.Tensor, device) -> torch.Tensor:
-    """c[S,H,P]: 4 at sink positions 0..3, 3 at heavy hitters (p = 0.02), else 0."""
+    """c[S,H,P]: 4 at sink positions 0..3, 3 at heavy hitters (p = 0.02), else 0.  pos is [S,P]."""
     hk = _keys(wl, tid, layer, seqs, heads, device)[:, :, None]
-    u = uniform01(hk, pos[None, None, :], 2)
+    u = uniform01(hk, pos[:, None, :], 2)
     c = torch.where(u < 0.02, 3.0, 0.0).to(torch.float64)
-    c = torch.where(pos[None, None, :] < 4, torch.full_like(c, 4.0), c)
+    c = torch.where((pos[:, None, :] < 4).expand_as(c), torch.full_like(c, 4.0), c)
     return c
 
 
 def _dir_and_outliers(wl: Workload, layer: int, heads, device):
-    u = torch.stack([head_direction(wl, layer, h, device) for h in heads])          # [H,d]
-    mult = torch.ones(len(heads), wl.head_dim, dtype=torch.float64, device=device)
-    if wl.outliers:
-        for i, h in enumerate(heads):
-            for c in outlier_channels(wl, layer, h):
-                mult[i, c] = 8.0
-    return u, mult
+    def make():
+        u = torch.stack([head_direction(wl, layer, h, device) for h in heads])          # [H,d]
+        mult = torch.ones(len(heads), wl.head_dim, dtype=torch.float64, device=device)
+        if wl.outliers:
+            for i, h in enumerate(heads):
+                for c in outlier_channels(wl, layer, h):
+                    mult[i, c] = 8.0
+        return u, mult
+    return _cached(("dir", wl.seed, layer, tuple(heads), wl.head_dim, wl.outliers, str(device)), make)
+
+
+def _pos2d(pos: torch.Tensor, n_seqs: int, device) -> torch.Tensor:
+    """Positions as [S,P]: a 1-D tensor means the same positions for every sequence."""
+    pos = pos.to(device=device, dtype=torch.int64)
+    return pos[None, :].expand(n_seqs, -1) if pos.dim() == 1 else pos
 
 
 def kv_rows(wl: Workload, layer: int, pos: torch.Tensor, *, decode: bool = False,
@@ -236,20 +257,21 @@ def kv_rows(wl: Workload, layer: int, pos: torch.Tensor, *, decode: bool = False
             device="cpu") -> Tuple[torch.Tensor, torch.Tensor]:
     """K, V rows at the given positions: [S, H, P, d] in the storage dtype.
 
-    `pos` is an int64 tensor [P] of absolute token positions.  Prompt tokens and
-    decode-step tokens come from different streams (decode=True), both indexed by
-    absolute position, so a row does not depend on how the call was sliced.
+    `pos` is an int64 tensor of absolute token positions, [P] (the same for every
+    sequence) or [S,P] (per sequence).  Prompt tokens and decode-step tokens come from
+    different streams (decode=True), both indexed by absolute position, so a row does not
+    depend on how the call was sliced.
     """
     seqs = list(range(wl.seq0, wl.seq0 + wl.n_seqs)) if seqs is None else list(seqs)
     heads = list(range(wl.head0, wl.head0 + wl.n_kv_heads)) if heads is None else list(heads)
     layer = wl.layer0 + layer
     d = wl.head_dim
-    pos = pos.to(device=device, dtype=torch.int64)
-    ctr = pos[:, None] * d + torch.arange(d, dtype=torch.int64, device=device)[None, :]   # [P,d]
+    pos = _pos2d(pos, len(seqs), device)
+    ctr = pos[:, :, None] * d + torch.arange(d, dtype=torch.int64, device=device)[None, None, :]   # [S,P,d]
     kk = _keys(wl, TID_DK if decode else TID_K, layer, seqs, heads, device)[:, :, None, None]
     vk = _keys(wl, TID_DV if decode else TID_V, layer, seqs, heads, device)[:, :, None, None]
-    K = normal(kk, ctr[None, None])
-    V = normal(vk, ctr[None, None])
+    K = normal(kk, ctr[:, None])
+    V = normal(vk, ctr[:, None])
     u, mult = _dir_and_outliers(wl, layer, heads, device)
     c = _boost_strength(wl, TID_DHEAVY if decode else TID_HEAVY, layer, seqs, heads, pos, device)
     if decode:
@@ -265,17 +287,20 @@ def kv_rows(wl: Workload, layer: int, pos: torch.Tensor, *, decode: bool = False
 def q_rows(wl: Workload, layer: int, pos: torch.Tensor, *, decode: bool = False,
            seqs: Optional[Sequence[int]] = None, heads: Optional[Sequence[int]] = None,
            device="cpu") -> torch.Tensor:
-    """Query rows at the given positions: [S, H, G, P, d] in the storage dtype."""
+    """Query rows at the given positions ([P] or per sequence [S,P]): [S, H, G, P, d] in the storage dtype."""
     seqs = list(range(wl.seq0, wl.seq0 + wl.n_seqs)) if seqs is None else list(seqs)
     heads = list(range(wl.head0, wl.head0 + wl.n_kv_heads)) if heads is None else list(heads)
     layer = wl.layer0 + layer
     d, G = wl.head_dim, wl.q_per_kv
-    pos = pos.to(device=device, dtype=torch.int64)
-    ctr = pos[:, None] * d + torch.arange(d, dtype=torch.int64, device=device)[None, :]
+    pos = _pos2d(pos, len(seqs), device)
+    ctr = pos[:, :, None] * d + torch.arange(d, dtype=torch.int64, device=device)[None, None, :]   # [S,P,d]
     tid = TID_DQ if decode else TID_Q
-    ks = [[[_signed(key_of(wl.seed, tid, layer, b, h * G + g)) for g in range(G)] for h in heads] for b in seqs]
-    qk = torch.tensor(ks, dtype=torch.int64, device=device)[..., None, None]          # [S,H,G,1,1]
-    Q = normal(qk, ctr[None, None, None])
+
+    def make():
+        ks = [[[_signed(key_of(wl.seed, tid, layer, b, h * G + g)) for g in range(G)] for h in heads] for b in seqs]
+        return torch.tensor(ks, dtype=torch.int64, device=device)
+    qk = _cached(("qkeys", wl.seed, tid, layer, tuple(seqs), tuple(heads), G, str(device)), make)[..., None, None]   # [S,H,G,1,1]
+    Q = normal(qk, ctr[:, None, None])
     u, _ = _dir_and_outliers(wl, layer, heads, device)
     Q = Q + (d ** 0.25) * u[None, :, None, None, :]
     return to_storage(Q, wl.dtype)
@@ -295,12 +320,9 @@ def prompt(wl: Workload, layer: int, *, seqs=None, heads=None, device="cpu"):
     T = wl.prompt_len
     K, V = kv_rows(wl, layer, torch.arange(T), seqs=seqs_l, heads=heads, device=device)
     Wq = T if wl.window == 0 else min(wl.window, T)
-    qs = []
-    for b, tb in zip(seqs_l, lens):
-        n = min(Wq, tb)
-        pos = torch.arange(tb - n, tb - n + Wq)          # the tail rows are padding
-        qs.append(q_rows(wl, layer, pos, seqs=[b], heads=heads, device=device))
-    Q = torch.cat(qs, dim=0)
+    first = torch.tensor([tb - min(Wq, tb) for tb in lens])                       # position of each sequence's query row 0
+    pos = first[:, None] + torch.arange(Wq)[None, :]                              # [S,Wq]; the tail rows are padding
+    Q = q_rows(wl, layer, pos, seqs=seqs_l, heads=heads, device=device)
     return Q, K, V, lens
 
 
@@ -312,13 +334,10 @@ def decode_inputs(wl: Workload, layer: int, step: int, *, seqs=None, heads=None,
     """
     seqs_l = list(range(wl.seq0, wl.seq0 + wl.n_seqs)) if seqs is None else list(seqs)
     all_lens = dict(zip(range(wl.seq0, wl.seq0 + wl.n_seqs), wl.seq_lens()))
-    qs, ks, vs = [], [], []
-    for b in seqs_l:
-        pos = torch.tensor([all_lens[b] + step])
-        k, v = kv_rows(wl, layer, pos, decode=True, seqs=[b], heads=heads, device=device)
-        q = q_rows(wl, layer, pos, decode=True, seqs=[b], heads=heads, device=device)
-        qs.append(q[:, :, :, 0]); ks.append(k[:, :, 0]); vs.append(v[:, :, 0])
-    return torch.cat(qs), torch.cat(ks), torch.cat(vs)
+    pos = torch.tensor([[all_lens[b] + step] for b in seqs_l])            # [S,1]: every sequence at its own position
+    k, v = kv_rows(wl, layer, pos, decode=True, seqs=seqs_l, heads=heads, device=device)
+    q = q_rows(wl, layer, pos, decode=True, seqs=seqs_l, heads=heads, device=device)
+    return q[:, :, :, 0].contiguous(), k[:, :, 0].contiguous(), v[:, :, 0].contiguous()
 
 
 def decode_inputs_uniform(wl: Workload, layers: Sequence[int], steps: Sequence[int], device="cpu"):

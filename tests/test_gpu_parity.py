@@ -402,15 +402,22 @@ def prompt_in_chunks(wl, layer, seqs_per_chunk):
 
 @pytest.mark.parametrize("w,sample", [(3, [(0, 0, 0), (9, 17, 9), (20, 40, 31), (31, 63, 12)]),
                                       (4, [(0, 0, 0), (11, 7, 3), (22, 15, 7), (31, 9, 5)])])
-def test_full_depth_sampled_units(w, sample):
+def test_full_depth_sampled_units(w, sample, capsys):
     """The batched workloads at full depth, in the launch shape the benchmark times (workload 3: 32 layers x 64 ragged
     sequences x 32 heads = 65 536 units in one launch; workload 4: 32 x 16 x 8 = 4096 units of four query heads):
     every layer is compressed on the device, a sample of units spread over layers and sequences is recomputed by the
     oracle from the bytes the device read, then all layers step together; after every step the invariants that hold
     at any size are checked on EVERY unit."""
+    import time
+    t_start = time.perf_counter()
+
+    def say(msg):   # progress goes to the real stdout: this test runs for a minute or two and must not look hung
+        with capsys.disabled():
+            print(f"[{time.perf_counter() - t_start:6.1f} s] {msg}", flush=True)
+
     wl = synth.workload(w)
     n_steps = 8
-    print(f"[case] workload {w} at full depth ({wl.n_units} units), sampled units {sample}", flush=True)
+    say(f"workload {w} at full depth ({wl.n_units} units), sampled units {sample}")
     cache = pu.make_cache(wl, DEV)
     units = [[[None] * wl.n_kv_heads for _ in range(wl.n_seqs)] for _ in range(wl.n_layers)]
     for l in range(wl.n_layers):
@@ -422,25 +429,25 @@ def test_full_depth_sampled_units(w, sample):
             got = pu.oracle_prefill_layer(wl, Q, K, V, lens, sel=pairs)
             for b, h in pairs:
                 units[l][b][h] = got[b][h]
-            print(f"[step] layer {l}: oracle prefill of {pairs} done", flush=True)
+            say(f"layer {l}: oracle prefill of {pairs} done")
         del Q, K, V
         if l % 8 == 7:
             torch.cuda.synchronize()
-            print(f"[step] {l + 1} layers compressed", flush=True)
+            say(f"{l + 1} layers compressed")
     cache.release_workspace()
     torch.cuda.empty_cache()
     pu.compare_all_state(wl, cache, units, pu.tol_for(wl.dtype), "after prefill", sample)
     pu.check_every_unit(wl, cache, 0)
     assert cache.decode_parts() == 1       # the launch the benchmark times: one workgroup per unit, all layers at once
-    print("[step] prefill parity ok on the sampled units, invariants hold on every unit", flush=True)
+    say("prefill parity ok on the sampled units, invariants hold on every unit")
 
     def after(n):
         pu.check_every_unit(wl, cache, n)
-        print(f"[step] decode step {n} ok", flush=True)
+        say(f"decode step {n} ok")
 
     st = pu.run_decode_parity(wl, cache, units, n_steps, sel=sample, gen_device=DEV, after_step=after)
-    print(f"[done] workload {w} full depth: unit-steps={st.unit_steps} evictions={st.evictions} near_ties={st.near_ties} "
-          f"max|out err|={st.max_out_err:.2e} scores bit-equal {st.s_bit_equal}/{st.s_total}", flush=True)
+    say(f"workload {w} full depth done: unit-steps={st.unit_steps} evictions={st.evictions} near_ties={st.near_ties} "
+        f"max|out err|={st.max_out_err:.2e} scores bit-equal {st.s_bit_equal}/{st.s_total}")
     assert st.evictions == st.unit_steps == n_steps * len(sample)
     for l in range(wl.n_layers):
         assert int(cache.flags(l).max()) == 0
