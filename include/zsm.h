@@ -43,8 +43,10 @@ enum zsm_status {
     ZSM_E_NOMEM = -5,  /* caller's buffer or workspace is too small                    */
     ZSM_E_RANGE = -6,  /* layer index / range outside the cache                        */
     ZSM_E_HIP = -7,    /* the HIP runtime refused a launch (text via zsm_strerror)     */
-    ZSM_E_STATE = -8   /* the cache state breaks the call's precondition (only reported
+    ZSM_E_STATE = -8,  /* the cache state breaks the call's precondition (only reported
                           while zsm_set_debug_checks is on)                            */
+    ZSM_E_SCRATCH = -9 /* zsm_decode_step_static: the launch needs more scratch than
+                          the library holds                                            */
 };
 
 /* Sticky per-unit condition bits, read with zsm_cache_flags. */
@@ -173,6 +175,33 @@ int zsm_decode_step(zsm_cache_t* cache, int32_t layer_begin, int32_t layer_end,
                     const void* q, const void* k_new, const void* v_new, float* out,
                     int32_t* write_slot, int32_t* evicted_pos, int32_t* merged_slot,
                     void* stream);
+
+/*
+ * zsm_decode_step_static - zsm_decode_step for callers that cannot allocate device memory
+ * (code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc) and
+ * do not want the split launch's scratch inside their cache buffer to be what is used: the
+ * partial softmax sums, output shares and per-slot exponentials of a launch that is cut over
+ * several workgroups per unit go to an array of ZSM_STATIC_SCRATCH_BYTES that the library
+ * itself holds on every GPU it runs on, from the first call on that GPU until the process ends.
+ * Same arguments, results and launch shapes as zsm_decode_step (to fp32 rounding: identical).
+ * The call allocates and frees nothing and calls no allocating routine.
+ *   Limit: a split launch of n units in p parts needs about
+ *   n*p*G*(8 + 4*d) + n*G*(slot_capacity + 1)*8 bytes (each of the three sections rounded up to
+ *   256); beyond ZSM_STATIC_SCRATCH_BYTES the call enqueues nothing and returns ZSM_E_SCRATCH.
+ *   One layer of 32 units with 2700 slots (16 parts) needs 0.9 MB, one layer of 128 units of four
+ *   query heads with 1024 slots (4 parts) 5 MB.  A launch that is not split needs none.
+ *   Sharing: all calls on one GPU use that GPU's one array, whatever the cache or stream.  It
+ *   keeps the previous call's contents; nothing in it has to start at zero (every value a
+ *   launch reads was written by the same launch).  Calls that overlap in time on one GPU (two
+ *   streams, two host threads) race on it: serialise them, or use zsm_decode_step, whose
+ *   scratch is per cache.
+ *   The first call on a GPU resolves the array's address there; make it outside a capture.
+ */
+#define ZSM_STATIC_SCRATCH_BYTES (8u << 20)
+int zsm_decode_step_static(zsm_cache_t* cache, int32_t layer_begin, int32_t layer_end,
+                           const void* q, const void* k_new, const void* v_new, float* out,
+                           int32_t* write_slot, int32_t* evicted_pos, int32_t* merged_slot,
+                           void* stream);
 
 /*
  * zsm_cache_set_decode_parts - how many workgroups share one unit in zsm_decode_step (a

@@ -23,7 +23,7 @@ CODE_TORCH = {ZSM_F32: torch.float32, ZSM_F16: torch.float16, ZSM_BF16: torch.bf
 
 EXPORTS = [
     "zsm_cache_bytes", "zsm_cache_alloc", "zsm_cache_free", "zsm_prefill_workspace_bytes",
-    "zsm_prefill_compress", "zsm_decode_step", "zsm_cache_set_decode_parts", "zsm_decode_parts",
+    "zsm_prefill_compress", "zsm_decode_step", "zsm_decode_step_static", "zsm_cache_set_decode_parts", "zsm_decode_parts",
     "zsm_cache_export", "zsm_cache_import", "zsm_cache_flags", "zsm_set_debug_checks",
     "zsm_stream_read", "zsm_stream_copy", "zsm_strerror",
 ]
@@ -65,6 +65,8 @@ def lib() -> C.CDLL:
         L.zsm_prefill_compress.argtypes = [vp, i32, vp, i32, vp, vp, vp, i32, vp, sz, vp]
         L.zsm_decode_step.restype = C.c_int
         L.zsm_decode_step.argtypes = [vp, i32, i32, vp, vp, vp, vp, vp, vp, vp, vp]
+        L.zsm_decode_step_static.restype = C.c_int
+        L.zsm_decode_step_static.argtypes = [vp, i32, i32, vp, vp, vp, vp, vp, vp, vp, vp]
         L.zsm_cache_set_decode_parts.restype = C.c_int
         L.zsm_cache_set_decode_parts.argtypes = [vp, i32]
         L.zsm_decode_parts.restype = C.c_int
@@ -153,6 +155,13 @@ def zsm_decode_step(handle, layer_begin, layer_end, q, k_new, v_new, out, write_
     rc = lib().zsm_decode_step(handle, layer_begin, layer_end, _ptr(q), _ptr(k_new), _ptr(v_new), _ptr(out),
                                _ptr(write_slot), _ptr(evicted_pos), _ptr(merged_slot), _stream(stream))
     _check(rc, "zsm_decode_step")
+
+
+def zsm_decode_step_static(handle, layer_begin, layer_end, q, k_new, v_new, out, write_slot=None, evicted_pos=None,
+                           merged_slot=None, stream=None) -> None:
+    rc = lib().zsm_decode_step_static(handle, layer_begin, layer_end, _ptr(q), _ptr(k_new), _ptr(v_new), _ptr(out),
+                                      _ptr(write_slot), _ptr(evicted_pos), _ptr(merged_slot), _stream(stream))
+    _check(rc, "zsm_decode_step_static")
 
 
 def zsm_cache_set_decode_parts(handle, parts: int) -> None:

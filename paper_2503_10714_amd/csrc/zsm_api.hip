@@ -361,6 +361,45 @@ int zsm_decode_step(zsm_cache_t* cache, int32_t layer_begin, int32_t layer_end, 
                             stream, nullptr, 0);
 }
 
+// ---- the decode step for callers that cannot allocate: scratch held by the library -----------
+// One array per GPU, alive until the process ends.  In host code the array's name is only a handle
+// for hipGetSymbolAddress; the device address it resolves to (per device) is what kernels get.
+static __device__ __align__(256) unsigned char scratch[ZSM_STATIC_SCRATCH_BYTES];
+
+namespace {
+constexpr int MAX_DEVICES = 64;
+std::mutex g_scratch_mu;
+char* g_scratch_ptr[MAX_DEVICES] = {};
+
+// device address of `scratch` on the current device (resolved once per device)
+int static_scratch_ptr(char** out) {
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return hip_fail(e, "zsm_decode_step_static hipGetDevice");
+    if (dev < 0 || dev >= MAX_DEVICES) return ZSM_E_RANGE;
+    std::lock_guard<std::mutex> lock(g_scratch_mu);
+    if (!g_scratch_ptr[dev]) {
+        void* p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || !p) return hip_fail(e, "zsm_decode_step_static hipGetSymbolAddress");
+        g_scratch_ptr[dev] = static_cast<char*>(p);
+    }
+    *out = g_scratch_ptr[dev];
+    return ZSM_OK;
+}
+}  // namespace
+
+int zsm_decode_step_static(zsm_cache_t* cache, int32_t layer_begin, int32_t layer_end, const void* q,
+                           const void* k_new, const void* v_new, float* out, int32_t* write_slot,
+                           int32_t* evicted_pos, int32_t* merged_slot, void* stream) {
+    char* ptr = nullptr;
+    int rc = static_scratch_ptr(&ptr);
+    if (rc) return rc;
+    rc = decode_step_impl(cache, layer_begin, layer_end, q, k_new, v_new, out, write_slot, evicted_pos, merged_slot,
+                          stream, ptr, ZSM_STATIC_SCRATCH_BYTES);
+    return rc == ZSM_E_NOMEM ? ZSM_E_SCRATCH : rc;
+}
+
 int zsm_cache_set_decode_parts(zsm_cache_t* cache, int32_t parts) {
     if (!cache) return ZSM_E_NULL;
     if (parts < 0 || parts > SP_MAX_PARTS) return ZSM_E_RANGE;
@@ -539,6 +578,7 @@ const char* zsm_strerror(int status) {
         case ZSM_E_NOMEM: return "buffer or workspace too small";
         case ZSM_E_RANGE: return "layer index or range outside the cache";
         case ZSM_E_STATE: return "the cache state breaks the call's precondition (found by the optional state checks)";
+        case ZSM_E_SCRATCH: return "the launch needs more than ZSM_STATIC_SCRATCH_BYTES of library-held scratch";
         case ZSM_E_HIP: return g_hip_msg;
         default: return "unknown status";
     }
