@@ -108,6 +108,7 @@ def cpu_baseline(wl, n_units: int, n_steps: int):
     t_decode = time.perf_counter() - t0
     return {
         "value": n_units * n_steps / t_decode, "unit": "unit-steps/s", "cores": int(threads), "kind": "oracle",
+        "host_cores": os.cpu_count(), "threads_note": "cores = threads NumPy's BLAS pool used (the oracle's only parallelism); host_cores = os.cpu_count()",
         "sample": f"{n_units} units of layer 0 (T={lens[0]}, B={sub.slot_capacity}) x {n_steps} decode steps, NumPy fp64; "
                   f"their oracle prefill took {t_prefill / n_units:.2f} s per unit (not in value)",
     }
@@ -138,6 +139,10 @@ def main():
     ap.add_argument("--pmc-calibration", action="store_true",
                     help="after the run, copy a 1 GiB buffer three times with the library's plain copy kernel, so that "
                          "a counter run holds dispatches of known size to scale FETCH_SIZE / WRITE_SIZE by")
+    ap.add_argument("--prefill-layers-per-call", type=int, default=0,
+                    help="layers compressed by one zsm_prefill_compress call: 0 = one layer per call with one residual slot, "
+                         "all layers in one call with more (their sequential absorption runs one wave per unit and needs the "
+                         "units of all layers to fill the chip); the prompts of that many layers are resident at once")
     ap.add_argument("--skip-prefill", action="store_true",
                     help="fill the cache by import of synthetic rows instead of running the prefill (profiling runs)")
     args = ap.parse_args()
@@ -178,12 +183,22 @@ def main():
     if not args.skip_prefill:
         ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         tot = 0.0
-        for l in range(L):
-            Q, K, V, lens = synth.prompt(wl, l, device=dev)
+        plc = args.prefill_layers_per_call if args.prefill_layers_per_call > 0 else (L if br > 1 else 1)
+        for l0 in range(0, L, plc):
+            l1 = min(L, l0 + plc)
+            Q = K = V = None
+            for l in range(l0, l1):
+                q1, k1, v1, lens = synth.prompt(wl, l, device=dev)
+                if Q is None:
+                    Q = torch.empty((l1 - l0,) + tuple(q1.shape), dtype=q1.dtype, device=dev)
+                    K = torch.empty((l1 - l0,) + tuple(k1.shape), dtype=k1.dtype, device=dev)
+                    V = torch.empty_like(K)
+                Q[l - l0].copy_(q1); K[l - l0].copy_(k1); V[l - l0].copy_(v1)
+                del q1, k1, v1
             lens_t = torch.tensor(lens, dtype=torch.int32, device=dev)
             torch.cuda.synchronize()
             ev0.record()
-            cache.prefill_compress(l, Q, K, V, lens_t)
+            cache.prefill_compress(l0, Q, K, V, lens_t, layer_end=l1)
             ev1.record()
             torch.cuda.synchronize()
             tot += ev0.elapsed_time(ev1)
@@ -278,12 +293,17 @@ def main():
                                + (f", {parts} workgroups per unit" if parts > 1 else ", one workgroup per unit"),
                    "units": units, "slots_per_unit": wl.slot_capacity},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
-                     "traffic": traffic, "kernel": "zsm::decode_kernel", "kernel_ms": kernel_ms,
+                     "traffic": traffic,
+                     "traffic_source": (f"profiles/decode_step_cfg{args.workload}_pmc.md: rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this "
+                                        "command, scaled by a copy kernel of known size; read from that file, not measured in this run"
+                                        if traffic is not None else None),
+                     "kernel": "zsm::decode_kernel", "kernel_ms": kernel_ms,
                      "algorithmic_bytes_per_launch": bytes_launch},
         "step_ms_p10_p50_p90": [per[len(per) // 10], per[len(per) // 2], per[(9 * len(per)) // 10]],
         "tokens_per_s_cache_step_only": value / (L * H) if S == 1 else None,
         "hbm_read_ceiling_GBs": read_ceiling,
         "prefill_compress_ms_all_layers": prefill_ms,
+        "prefill_layers_per_call": (None if args.skip_prefill else plc),
         "prefill_window": (wl.window if wl.window > 0 else wl.prompt_len),
         "setup_s": setup_s,
         "device": device_info(),

@@ -86,15 +86,20 @@ int zsm_cache_alloc(const zsm_config_t* cfg, const int32_t* B_p, const int32_t* 
                     void* dev_buf, size_t dev_bytes, void* stream, zsm_cache_t** out);
 int zsm_cache_free(zsm_cache_t* cache);
 
-/* Bytes of device workspace zsm_prefill_compress needs for prompts of up to T_max
- * tokens scored from W query rows (0 on invalid arguments).  Besides scores, masks and
- * partial sums it holds up to 1 GiB of softmax numerators (8 bytes per window row and
- * key) when one unit's fit: K is then swept once for the scores instead of twice. */
-size_t zsm_prefill_workspace_bytes(const zsm_cache_t* cache, int32_t T_max, int32_t W);
+/* Bytes of device workspace a zsm_prefill_compress call over n_layers layers needs for
+ * prompts of up to T_max tokens scored from W query rows (0 on invalid arguments).  Scores,
+ * masks and partial sums grow with the units of the call (about 5 bytes per unit and prompt
+ * token, plus 16 * d bytes per unit and 1024 tokens); besides them it holds up to 1 GiB of
+ * softmax numerators (8 bytes per window row and key) when one unit's fit: K is then swept
+ * once for the scores instead of twice. */
+size_t zsm_prefill_workspace_bytes(const zsm_cache_t* cache, int32_t n_layers, int32_t T_max,
+                                   int32_t W);
 
 /*
- * zsm_prefill_compress - one-shot compression of one layer's prompts into the (empty)
- * cache of that layer.
+ * zsm_prefill_compress - one-shot compression of the prompts of layers [layer_begin,
+ * layer_end) into the (empty) cache of those layers.  Layers are independent; passing several
+ * at once only puts more units into each launch (which is what the sequential absorption for
+ * B_r >= 2 needs to fill the chip: one wave per unit).
  *   Scores: Eq. 3 unrolled over the last n_b = min(W, T_b) prompt queries, each query a
  *   causal softmax row (Eq. 1), grouped query heads pooled by their mean (appendix, GQA
  *   adaptation); W >= T_max is the full-history initialisation, a smaller W the
@@ -105,13 +110,13 @@ size_t zsm_prefill_workspace_bytes(const zsm_cache_t* cache, int32_t T_max, int3
  *   residual branch (Eq. 5, Eq. 6).
  *   Slot order afterwards: residual slots, context tokens by position, proximity tokens
  *   by position.
- *   Q          device [S, H, G, W, d]; row r of sequence b is the query at position
- *              T_b - n_b + r; rows r >= n_b are ignored.
- *   K, V       device [S, H, T_max, d]; rows >= T_b are ignored.
- *   seq_lens   device int32 [S]: T_b, 0 <= T_b <= T_max.
- *   workspace  device, 256-byte aligned, ws_bytes >= zsm_prefill_workspace_bytes().
- * The layer's cache must be empty (freshly allocated or re-imported empty); this is only
- * verified while zsm_set_debug_checks is on (ZSM_E_STATE).
+ *   Q          device [Ln, S, H, G, W, d], Ln = layer_end - layer_begin; row r of sequence b
+ *              is the query at position T_b - n_b + r; rows r >= n_b are ignored.
+ *   K, V       device [Ln, S, H, T_max, d]; rows >= T_b are ignored.
+ *   seq_lens   device int32 [S]: T_b, 0 <= T_b <= T_max (the same for every layer).
+ *   workspace  device, 256-byte aligned, ws_bytes >= zsm_prefill_workspace_bytes(Ln, ..).
+ * The layers' caches must be empty (freshly allocated or re-imported empty); this is only
+ * verified while zsm_set_debug_checks is on (ZSM_E_STATE).  S * H <= 32768 (ZSM_E_SHAPE).
  * Logit range: each softmax row (Eq. 1) is evaluated in fp64 as exp(z_t - z_self) / sum, with
  * z_self the query's logit against the key at its own position, so no running maximum is
  * kept.  This is exact as long as no counted key's logit exceeds z_self by more than 690
@@ -127,9 +132,10 @@ size_t zsm_prefill_workspace_bytes(const zsm_cache_t* cache, int32_t T_max, int3
  * unit: about a microsecond per absorbed token).  B_r <= 64 here (the decode step takes any
  * B_r); ZSM_E_SHAPE otherwise.
  */
-int zsm_prefill_compress(zsm_cache_t* cache, int32_t layer, const void* Q, int32_t W,
-                         const void* K, const void* V, const int32_t* seq_lens,
-                         int32_t T_max, void* workspace, size_t ws_bytes, void* stream);
+int zsm_prefill_compress(zsm_cache_t* cache, int32_t layer_begin, int32_t layer_end,
+                         const void* Q, int32_t W, const void* K, const void* V,
+                         const int32_t* seq_lens, int32_t T_max, void* workspace,
+                         size_t ws_bytes, void* stream);
 
 /*
  * zsm_decode_step - one fused decode step (the loop body of Alg. 1 with the attention

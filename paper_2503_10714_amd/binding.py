@@ -60,9 +60,9 @@ def lib() -> C.CDLL:
         L.zsm_cache_free.restype = C.c_int
         L.zsm_cache_free.argtypes = [vp]
         L.zsm_prefill_workspace_bytes.restype = sz
-        L.zsm_prefill_workspace_bytes.argtypes = [vp, i32, i32]
+        L.zsm_prefill_workspace_bytes.argtypes = [vp, i32, i32, i32]
         L.zsm_prefill_compress.restype = C.c_int
-        L.zsm_prefill_compress.argtypes = [vp, i32, vp, i32, vp, vp, vp, i32, vp, sz, vp]
+        L.zsm_prefill_compress.argtypes = [vp, i32, i32, vp, i32, vp, vp, vp, i32, vp, sz, vp]
         L.zsm_decode_step.restype = C.c_int
         L.zsm_decode_step.argtypes = [vp, i32, i32, vp, vp, vp, vp, vp, vp, vp, vp]
         L.zsm_decode_step_static.restype = C.c_int
@@ -140,12 +140,12 @@ def zsm_cache_free(handle) -> None:
     _check(lib().zsm_cache_free(handle), "zsm_cache_free")
 
 
-def zsm_prefill_workspace_bytes(handle, T_max: int, W: int) -> int:
-    return int(lib().zsm_prefill_workspace_bytes(handle, T_max, W))
+def zsm_prefill_workspace_bytes(handle, n_layers: int, T_max: int, W: int) -> int:
+    return int(lib().zsm_prefill_workspace_bytes(handle, n_layers, T_max, W))
 
 
-def zsm_prefill_compress(handle, layer, Q, W, K, V, seq_lens, T_max, workspace, stream=None) -> None:
-    rc = lib().zsm_prefill_compress(handle, layer, _ptr(Q), W, _ptr(K), _ptr(V), _ptr(seq_lens), T_max,
+def zsm_prefill_compress(handle, layer_begin, layer_end, Q, W, K, V, seq_lens, T_max, workspace, stream=None) -> None:
+    rc = lib().zsm_prefill_compress(handle, layer_begin, layer_end, _ptr(Q), W, _ptr(K), _ptr(V), _ptr(seq_lens), T_max,
                                     _ptr(workspace), workspace.numel() * workspace.element_size(), _stream(stream))
     _check(rc, "zsm_prefill_compress")
 
@@ -252,19 +252,26 @@ class Cache:
     @property
     def B_r(self): return self.cfg.n_residual
 
-    def prefill_compress(self, layer: int, Q, K, V, seq_lens) -> None:
+    def prefill_compress(self, layer: int, Q, K, V, seq_lens, layer_end: Optional[int] = None) -> None:
+        """One layer (Q [S,H,G,W,d], K/V [S,H,T,d]) or, with layer_end, the layers [layer, layer_end) in one call
+        (Q [Ln,S,H,G,W,d], K/V [Ln,S,H,T,d])."""
         S, H, G, d = self.S, self.H, self.G, self.d
         W, T_max = Q.shape[-2], K.shape[-2]
-        assert tuple(Q.shape) == (S, H, G, W, d) and tuple(K.shape) == (S, H, T_max, d) and K.shape == V.shape
+        lead = () if layer_end is None else (layer_end - layer,)
+        layer_end = layer + 1 if layer_end is None else layer_end
+        assert tuple(Q.shape) == lead + (S, H, G, W, d) and tuple(K.shape) == lead + (S, H, T_max, d) and K.shape == V.shape
         assert Q.dtype == self.kv_dtype and K.dtype == self.kv_dtype and V.dtype == self.kv_dtype
         if not torch.is_tensor(seq_lens):
             seq_lens = torch.tensor(list(seq_lens), dtype=torch.int32)
         seq_lens = seq_lens.to(device=self.device, dtype=torch.int32).contiguous()
-        need = zsm_prefill_workspace_bytes(self.handle, T_max, W)
+        need = zsm_prefill_workspace_bytes(self.handle, layer_end - layer, T_max, W)
+        if need == 0:
+            raise ZsmError(-2, "zsm_prefill_workspace_bytes")
         if self._ws is None or self._ws.numel() < need:
+            self._ws = None
             self._ws = torch.empty(need, dtype=torch.uint8, device=self.device)
         with torch.cuda.device(self.device):
-            zsm_prefill_compress(self.handle, layer, Q, W, K, V, seq_lens, T_max, self._ws)
+            zsm_prefill_compress(self.handle, layer, layer_end, Q, W, K, V, seq_lens, T_max, self._ws)
 
     def release_workspace(self):
         self._ws = None

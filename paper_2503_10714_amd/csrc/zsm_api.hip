@@ -414,38 +414,48 @@ int zsm_decode_parts(const zsm_cache_t* cache, int32_t layer_begin, int32_t laye
     return choose_parts(cache, (layer_end - layer_begin) * cache->cv.S * cache->cv.H, &part_rows);
 }
 
-size_t zsm_prefill_workspace_bytes(const zsm_cache_t* cache, int32_t T_max, int32_t W) {
-    if (!cache || T_max < 1 || W < 1) return 0;
-    return prefill_workspace_bytes(cache->cv, T_max, W);
+size_t zsm_prefill_workspace_bytes(const zsm_cache_t* cache, int32_t n_layers, int32_t T_max, int32_t W) {
+    if (!cache || n_layers < 1 || n_layers > cache->cfg.n_layers || T_max < 1 || W < 1) return 0;
+    return prefill_workspace_bytes(cache->cv, n_layers, T_max, W);
 }
 
-int zsm_prefill_compress(zsm_cache_t* cache, int32_t layer, const void* Q, int32_t W, const void* K,
-                         const void* V, const int32_t* seq_lens, int32_t T_max, void* workspace,
+int zsm_prefill_compress(zsm_cache_t* cache, int32_t layer_begin, int32_t layer_end, const void* Q, int32_t W,
+                         const void* K, const void* V, const int32_t* seq_lens, int32_t T_max, void* workspace,
                          size_t ws_bytes, void* stream) {
     if (!cache || !Q || !K || !V || !seq_lens || !workspace) return ZSM_E_NULL;
-    int rc = check_layer(cache, layer);
-    if (rc) return rc;
+    if (layer_begin < 0 || layer_end > cache->cfg.n_layers || layer_begin >= layer_end) return ZSM_E_RANGE;
     if (T_max < 1 || W < 1) return ZSM_E_SHAPE;
     if (cache->cfg.n_residual > 64) return ZSM_E_SHAPE;
+    const CacheView& cv = cache->cv;
+    const int n_layers = layer_end - layer_begin;
+    const int gl = prefill_group_layers(cv, n_layers);
+    if (gl < 1) return ZSM_E_SHAPE;
     if (!aligned16(Q) || !aligned16(K) || !aligned16(V)) return ZSM_E_ALIGN;
     if ((reinterpret_cast<uintptr_t>(workspace) & 255) != 0) return ZSM_E_ALIGN;
-    if (ws_bytes < prefill_workspace_bytes(cache->cv, T_max, W)) return ZSM_E_NOMEM;
+    if (ws_bytes < prefill_workspace_bytes(cv, n_layers, T_max, W)) return ZSM_E_NOMEM;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const int lu = cv.S * cv.H;
     if (g_debug_checks.load(std::memory_order_relaxed)) {
-        hipStream_t st = static_cast<hipStream_t>(stream);
-        const int lu = cache->cv.S * cache->cv.H;
-        rc = run_state_check(cache, st, [&] {
-            hipLaunchKernelGGL(check_empty_kernel, dim3(lu), dim3(256), 0, st, cache->cv, layer * lu, cache->dbg);
+        int rc = run_state_check(cache, st, [&] {
+            hipLaunchKernelGGL(check_empty_kernel, dim3(n_layers * lu), dim3(256), 0, st, cv, layer_begin * lu, cache->dbg);
         }, "zsm_prefill_compress state check");
         if (rc) return rc;
     }
-    PrefillArgs a;
-    a.cv = cache->cv;
-    a.unit0 = layer * cache->cv.S * cache->cv.H;
-    a.n_units = cache->cv.S * cache->cv.H;
-    a.Q = Q; a.K = K; a.V = V; a.seq_lens = seq_lens; a.W = W; a.T_max = T_max;
-    a.ws = static_cast<char*>(workspace);
-    hipError_t e = launch_prefill(a, static_cast<hipStream_t>(stream));
-    if (e != hipSuccess) return hip_fail(e, "zsm_prefill_compress launch");
+    const size_t es = esize(cv.dtype);
+    for (int l0 = 0; l0 < n_layers; l0 += gl) {   // groups of whole layers, each one set of launches
+        const int nl = n_layers - l0 < gl ? n_layers - l0 : gl;
+        PrefillArgs a;
+        a.cv = cv;
+        a.unit0 = (layer_begin + l0) * lu;
+        a.n_units = nl * lu;
+        a.Q = static_cast<const char*>(Q) + (size_t)l0 * lu * cv.G * W * cv.D * es;
+        a.K = static_cast<const char*>(K) + (size_t)l0 * lu * T_max * cv.D * es;
+        a.V = static_cast<const char*>(V) + (size_t)l0 * lu * T_max * cv.D * es;
+        a.seq_lens = seq_lens; a.W = W; a.T_max = T_max;
+        a.ws = static_cast<char*>(workspace);
+        hipError_t e = launch_prefill(a, st);
+        if (e != hipSuccess) return hip_fail(e, "zsm_prefill_compress launch");
+    }
     return ZSM_OK;
 }
 

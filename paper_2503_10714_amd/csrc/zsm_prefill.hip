@@ -8,6 +8,9 @@ namespace {
 
 __device__ __forceinline__ double shfl_xor_d(double v, int o) { return __shfl_xor(v, o, 64); }
 
+// a call covers the units of one or more whole layers: local unit lu = (layer * S + sequence) * H + head
+__device__ __forceinline__ int seq_of(const CacheView& cv, int lu) { return (lu / cv.H) % cv.S; }
+
 // the lengths live in device memory and cannot be checked on the host: clamp them here
 __device__ __forceinline__ int seq_len_of(const PrefillArgs& a, int b) {
     const int t = a.seq_lens[b];
@@ -50,7 +53,7 @@ template <typename T, int D>
 __global__ __launch_bounds__(64) void pf_self_logit(PrefillArgs a, PrefillWs ws) {
     const CacheView& cv = a.cv;
     const int lu = blockIdx.y;
-    const int b = lu / cv.H;
+    const int b = seq_of(cv, lu);
     const int Tb = seq_len_of(a, b);
     const int nb = a.W < Tb ? a.W : Tb;
     const int G = cv.G;
@@ -101,7 +104,7 @@ __global__ __launch_bounds__(256, MODE == 2 ? 3 : 4) void pf_score_mfma(PrefillA
     static_assert(PF_KQ % (NWV * 32) == 0, "");
     const CacheView& cv = a.cv;
     const int lu = (MODE == 2 ? ws.lu0 : 0) + blockIdx.y;   // MODE 2 launches cover units lu0, lu0 + 1, ...
-    const int b = lu / cv.H;
+    const int b = seq_of(cv, lu);
     const int Tb = seq_len_of(a, b);
     const int W = a.W, G = cv.G, Wp = ws.Wp;
     const int nb = W < Tb ? W : Tb;
@@ -276,7 +279,7 @@ __global__ __launch_bounds__(256) void pf_score_from_ev(PrefillArgs a, PrefillWs
                                                         const double* __restrict__ evs, float* __restrict__ sc) {
     const CacheView& cv = a.cv;
     const int lu = ws.lu0 + blockIdx.y;
-    const int Tb = seq_len_of(a, lu / cv.H);
+    const int Tb = seq_len_of(a, seq_of(cv, lu));
     const int nb = a.W < Tb ? a.W : Tb;
     const int qpos0 = Tb - nb;
     const int Wp = ws.Wp;
@@ -322,7 +325,7 @@ __global__ __launch_bounds__(256) void pf_score_from_ev(PrefillArgs a, PrefillWs
 // scores that passed through the fp64 accumulator (more than one pass per unit) -> fp32
 __global__ void pf_sacc_to_sc(PrefillArgs a, const double* __restrict__ sacc, int rz, float* __restrict__ sc) {
     const int lu = blockIdx.y;
-    const int Tb = seq_len_of(a, lu / a.cv.H);
+    const int Tb = seq_len_of(a, seq_of(a.cv, lu));
     const size_t zs = (size_t)gridDim.y * a.T_max;   // stride between the pass groups' arrays
     for (int t = blockIdx.x * blockDim.x + threadIdx.x; t < Tb; t += gridDim.x * blockDim.x) {
         double v = 0.0;
@@ -339,7 +342,7 @@ __global__ void pf_fill_f64(double* p, size_t n, double v) {
 __global__ void pf_row_combine(PrefillArgs a, PrefillWs ws) {
     const CacheView& cv = a.cv;
     const int lu = ws.lu0 + blockIdx.x;
-    const int b = lu / cv.H;
+    const int b = seq_of(cv, lu);
     const int Tb = seq_len_of(a, b);
     const int nb = a.W < Tb ? a.W : Tb;
     const int G = cv.G, Wp = ws.Wp;
@@ -372,7 +375,7 @@ __global__ __launch_bounds__(SEL_NT) void pf_select(PrefillArgs a, PrefillWs ws)
     const CacheView& cv = a.cv;
     const int lu = blockIdx.x;
     const int ug = a.unit0 + lu;
-    const int b = lu / cv.H;
+    const int b = seq_of(cv, lu);
     const int Tb = seq_len_of(a, b);
     const int Bp = cv.Bp[b], Bc = cv.Bc[b];
     const int ntok = Bp + Bc;
@@ -470,7 +473,7 @@ constexpr int SEL_NPT = 64;
 __global__ __launch_bounds__(SEL_NT) void pf_select_reg(PrefillArgs a, PrefillWs ws) {
     const CacheView& cv = a.cv;
     const int lu = blockIdx.x;
-    const int b = lu / cv.H;
+    const int b = seq_of(cv, lu);
     const int Tb = seq_len_of(a, b);
     const int Bp = cv.Bp[b], Bc = cv.Bc[b];
     const int ntok = Bp + Bc;
@@ -602,7 +605,7 @@ __global__ __launch_bounds__(256) void pf_gather(PrefillArgs a, PrefillWs ws) {
     const CacheView& cv = a.cv;
     const int lu = blockIdx.y;
     const int ug = a.unit0 + lu;
-    const int b = lu / cv.H;
+    const int b = seq_of(cv, lu);
     const int Tb = seq_len_of(a, b);
     const int Br = cv.Br;
     const int32_t* kept_pos = reinterpret_cast<const int32_t*>(a.ws + ws.kept_pos) + (size_t)lu * cv.cap_tok;
@@ -650,7 +653,7 @@ template <typename T, int D>
 __global__ __launch_bounds__(256) void pf_residual_partial(PrefillArgs a, PrefillWs ws) {
     const CacheView& cv = a.cv;
     const int lu = blockIdx.y;
-    const int b = lu / cv.H;
+    const int b = seq_of(cv, lu);
     const int Tb = seq_len_of(a, b);
     const int chunk = blockIdx.x;
     const int t0 = chunk * PF_RC;
@@ -708,7 +711,7 @@ __global__ __launch_bounds__(256) void pf_residual_final(PrefillArgs a, PrefillW
     const CacheView& cv = a.cv;
     const int lu = blockIdx.x;
     const int ug = a.unit0 + lu;
-    const int b = lu / cv.H;
+    const int b = seq_of(cv, lu);
     const int Tb = seq_len_of(a, b);
     const int Br = cv.Br;
     const int32_t* sel = reinterpret_cast<const int32_t*>(a.ws + ws.sel) + (size_t)lu * 4;
@@ -788,7 +791,7 @@ __global__ __launch_bounds__(64) void pf_residual_greedy(PrefillArgs a, PrefillW
     const CacheView& cv = a.cv;
     const int lu = blockIdx.x;
     const int ug = a.unit0 + lu;
-    const int b = lu / cv.H;
+    const int b = seq_of(cv, lu);
     const int Tb = seq_len_of(a, b);
     const int Br = cv.Br;
     const int lane = threadIdx.x;
@@ -949,7 +952,7 @@ __global__ __launch_bounds__(64) void pf_residual_greedy(PrefillArgs a, PrefillW
 template <typename T, int D>
 hipError_t launch_prefill_td(const PrefillArgs& a, hipStream_t st) {
     const CacheView& cv = a.cv;
-    const PrefillWs ws = prefill_ws_layout(cv, a.T_max, a.W);
+    const PrefillWs ws = prefill_ws_layout(cv, a.n_units, a.T_max, a.W);
     const size_t n_heads = (size_t)a.n_units * cv.G;
     hipLaunchKernelGGL((pf_convert_q<T>), dim3(1024), dim3(256), 0, st, reinterpret_cast<const T*>(a.Q),
                        reinterpret_cast<double*>(a.ws + ws.Qd), a.W, ws.Wp, D, n_heads);

@@ -9,10 +9,10 @@ namespace zsm {
 
 struct PrefillArgs {
     CacheView cv;
-    int32_t unit0;      // first global unit of the layer
-    int32_t n_units;    // S * H
-    const void* Q;      // [S][H][G][W][D]
-    const void* K;      // [S][H][T_max][D]
+    int32_t unit0;      // first global unit of the call's first layer
+    int32_t n_units;    // layers of this launch group * S * H
+    const void* Q;      // [layers][S][H][G][W][D]
+    const void* K;      // [layers][S][H][T_max][D]
     const void* V;
     const int32_t* seq_lens;   // [S]
     int32_t W, T_max;
@@ -40,9 +40,22 @@ struct PrefillWs {
 // rows x T_max per unit) fit this many bytes.
 constexpr size_t PF_EV_MAX = (size_t)1 << 30;
 
-inline PrefillWs prefill_ws_layout(const CacheView& cv, int T_max, int W) {
+// Units one group of launches may cover (grid dimension y of the per-unit kernels); a call with more is
+// worked off in groups of whole layers.
+constexpr int PF_MAX_GROUP_UNITS = 32768;
+
+// whole layers per launch group for a call of n_layers layers (0: a single layer has too many units)
+inline int prefill_group_layers(const CacheView& cv, int n_layers) {
+    const long long lu = (long long)cv.S * cv.H;
+    if (lu > PF_MAX_GROUP_UNITS) return 0;
+    const long long g = PF_MAX_GROUP_UNITS / lu;
+    return (int)(g < n_layers ? g : n_layers);
+}
+
+// layout for launches that cover `n_units` units at a time
+inline PrefillWs prefill_ws_layout(const CacheView& cv, int n_units, int T_max, int W) {
     PrefillWs w{};
-    const size_t units = (size_t)cv.S * cv.H;
+    const size_t units = (size_t)n_units;
     w.Wp = (W + PF_MR - 1) / PF_MR * PF_MR;
     {
         // Work of the scoring launches: (unit, key range, group of 32-row passes).  With one pass
@@ -86,8 +99,9 @@ inline PrefillWs prefill_ws_layout(const CacheView& cv, int T_max, int W) {
     return w;
 }
 
-inline size_t prefill_workspace_bytes(const CacheView& cv, int T_max, int W) {
-    return prefill_ws_layout(cv, T_max, W).total;
+inline size_t prefill_workspace_bytes(const CacheView& cv, int n_layers, int T_max, int W) {
+    const int gl = prefill_group_layers(cv, n_layers);
+    return gl > 0 ? prefill_ws_layout(cv, gl * cv.S * cv.H, T_max, W).total : 0;
 }
 
 hipError_t launch_prefill(const PrefillArgs& a, hipStream_t stream);

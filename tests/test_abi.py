@@ -78,7 +78,7 @@ def test_null_handles_and_strerror(zb):
     lib = zb.lib()
     assert lib.zsm_cache_free(None) == -1
     assert lib.zsm_decode_step(None, 0, 1, None, None, None, None, None, None, None, None) == -1
-    assert lib.zsm_prefill_workspace_bytes(None, 10, 10) == 0
+    assert lib.zsm_prefill_workspace_bytes(None, 1, 10, 10) == 0
     assert lib.zsm_stream_copy(None, None, 16, None) == -1
     for code in range(-7, 1):
         assert zb.zsm_strerror(code)

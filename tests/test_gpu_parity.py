@@ -176,6 +176,50 @@ def test_prefill_compress(case):
     cache.close()
 
 
+@pytest.mark.parametrize("case", ["three_layers_one_residual", "four_layers_three_residual_ragged", "two_layers_gqa2_evict_only"])
+def test_prefill_several_layers_in_one_call(case):
+    """A layer range compressed by ONE call (all its units in the same launches; the sequential absorption for
+    B_r >= 2 then runs one wave per unit of every layer at once): state after the call against the oracle, unit by
+    unit, and against the same layers compressed one call each on a twin cache (bit for bit)."""
+    wl = {
+        "three_layers_one_residual": lambda: small("pf_3l", n_layers=3, n_kv_heads=3, dtype="f16", head_dim=128, prompt_len=500,
+                                                   budget=64, window=32, outliers=True),
+        "four_layers_three_residual_ragged": lambda: small("pf_4l_r3", n_layers=4, n_seqs=3, n_residual=3, prompt_len=420,
+                                                           ragged=(50, 420), budget_ratio=0.15, budget=63, window=16),
+        "two_layers_gqa2_evict_only": lambda: small("pf_2l_gqa2", n_layers=2, q_per_kv=2, n_residual=0, dtype="bf16",
+                                                    prompt_len=300, budget=40, window=40),
+    }[case]()
+    L = wl.n_layers
+    print(f"[case] prefill of {L} layers in one call: {wl.name} lens={wl.seq_lens()} B_r={wl.budgets()[2]}", flush=True)
+    per_layer = [synth.prompt(wl, l) for l in range(L)]
+    lens = per_layer[0][3]
+    Q = torch.stack([p[0] for p in per_layer]).to(DEV)
+    K = torch.stack([p[1] for p in per_layer]).to(DEV)
+    V = torch.stack([p[2] for p in per_layer]).to(DEV)
+    together, single = pu.make_cache(wl, DEV), pu.make_cache(wl, DEV)
+    together.prefill_compress(0, Q, K, V, lens, layer_end=L)
+    for l in range(L):
+        single.prefill_compress(l, Q[l], K[l], V[l], lens)
+    units = [pu.oracle_prefill_layer(wl, *per_layer[l][:3], lens) for l in range(L)]
+    pu.compare_all_state(wl, together, units, pu.tol_for(wl.dtype), "after a prefill of all layers in one call")
+    for l in range(L):
+        a, b = together.export_layer(l), single.export_layer(l)
+        for key in a:
+            assert torch.equal(a[key], b[key]), f"layer {l}: {key} differs between one call and one call per layer"
+    # a range in the middle of the cache, into a fresh cache: the other layers stay empty
+    if L >= 3:
+        mid = pu.make_cache(wl, DEV)
+        mid.prefill_compress(1, Q[1:L], K[1:L], V[1:L], lens, layer_end=L)
+        assert (mid.export_layer(0)["n_seen"] == 0).all()
+        a, b = mid.export_layer(L - 1), single.export_layer(L - 1)
+        for key in a:
+            assert torch.equal(a[key], b[key]), key
+        mid.close()
+    st = pu.run_decode_parity(wl, together, units, 6)
+    assert st.near_ties == 0
+    together.close(); single.close()
+
+
 FULL_CASES = {
     "cfg0": (lambda: synth.workload(0), None),
     "cfg1": (lambda: synth.workload(1), None),
@@ -241,7 +285,7 @@ def test_error_paths_on_device():
     ws = torch.empty(16, dtype=torch.uint8, device=DEV)
     Q, K, V, lens = synth.prompt(wl, 0)
     with pytest.raises(zb.ZsmError) as e:
-        zb.zsm_prefill_compress(cache.handle, 0, Q.to(DEV), Q.shape[-2], K.to(DEV), V.to(DEV),
+        zb.zsm_prefill_compress(cache.handle, 0, 1, Q.to(DEV), Q.shape[-2], K.to(DEV), V.to(DEV),
                                 torch.tensor(lens, dtype=torch.int32, device=DEV), K.shape[-2], ws)
     assert e.value.status == -5
     # nothing above may have touched the cache
@@ -307,18 +351,19 @@ def test_prefill_workspace_size():
     GiB = 1 << 30
     # workload 2's layer: 32 units x 32 rows x 54 000 keys x 8 B = 442 MB of numerators, all kept
     c = zb.Cache(1, 1, 32, 1, 128, 1350, 1349, 1, "f16", device=DEV)
-    short = zb.zsm_prefill_workspace_bytes(c.handle, 54000, 32)
+    short = zb.zsm_prefill_workspace_bytes(c.handle, 1, 54000, 32)
     ev = 32 * 32 * 54000 * 8
     assert ev < short < ev + 200 * (1 << 20)
     # full history at the same length: no numerators kept, far smaller
-    full = zb.zsm_prefill_workspace_bytes(c.handle, 4096, 4096)
+    full = zb.zsm_prefill_workspace_bytes(c.handle, 1, 4096, 4096)
     assert full < 200 * (1 << 20)
     c.close()
     # workload 3's layer: 2048 units x 32 rows x 16 384 keys x 8 B = 8.6 GB of numerators: only 1 GiB of them at a time
     c = zb.Cache(1, 64, 32, 1, 128, [819] * 64, [819] * 64, 1, "f16", device=DEV)
-    big = zb.zsm_prefill_workspace_bytes(c.handle, 16384, 32)
+    big = zb.zsm_prefill_workspace_bytes(c.handle, 1, 16384, 32)
     assert GiB - (1 << 23) < big < GiB + 700 * (1 << 20)
-    assert zb.zsm_prefill_workspace_bytes(c.handle, 8192, 32) < big
+    assert zb.zsm_prefill_workspace_bytes(c.handle, 1, 8192, 32) < big
+    assert zb.zsm_prefill_workspace_bytes(c.handle, 2, 16384, 32) == 0            # the cache has one layer
     c.close()
 
 
