@@ -127,6 +127,10 @@ def main():
     ap.add_argument("--layers-per-launch", type=int, default=0,
                     help="0 = all layers of the workload in one launch (the headline configuration); N = one launch "
                          "per N layers, as a model that runs its layers one after the other would call it")
+    ap.add_argument("--graph", action="store_true",
+                    help="capture the launches of one step in a HIP graph (inputs in fixed buffers, refreshed by three small "
+                         "copies before every replay) and time replays instead of eager calls: what a serving loop that runs "
+                         "its layers one call each would do (use with --layers-per-launch 1)")
     ap.add_argument("--decode-parts", type=int, default=0,
                     help="workgroups per unit in the decode step: 0 = the library's choice per launch, 1 = never split, n = n")
     ap.add_argument("--window", type=int, default=None,
@@ -245,6 +249,26 @@ def main():
     for i in range(args.warmup):
         step(i)
     torch.cuda.synchronize()
+    if args.graph:
+        q_cur, k_cur, v_cur = q_all[0].clone(), k_all[0].clone(), v_all[0].clone()
+
+        def launches():
+            for l0 in range(0, L, lpl):
+                l1 = min(L, l0 + lpl)
+                zb.zsm_decode_step(cache.handle, l0, l1, q_cur[l0:l1], k_cur[l0:l1], v_cur[l0:l1], out[l0:l1],
+                                   info[0][l0:l1], info[1][l0:l1], info[2][l0:l1])
+
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):      # records the launches; nothing runs and the cache is not touched
+            launches()
+
+        def step(i):
+            q_cur.copy_(q_all[i]); k_cur.copy_(k_all[i]); v_cur.copy_(v_all[i])
+            graph.replay()
+
+        for i in range(min(5, args.warmup)):
+            step(i)
+        torch.cuda.synchronize()
     evs = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]
     t0 = time.perf_counter()
     evs[0].record()
@@ -290,7 +314,8 @@ def main():
                                   f"at most (prompts of {min(wl.seq_lens())}..{max(wl.seq_lens())} tokens, B = {min(p + c for p, c in zip(bp, bc)) + br}.."
                                   f"{max(p + c for p, c in zip(bp, bc)) + br} per sequence, B_r={br}), ")
                                + ("all layers in one launch" if lpl >= L else f"{lpl} layer(s) per launch")
-                               + (f", {parts} workgroups per unit" if parts > 1 else ", one workgroup per unit"),
+                               + (f", {parts} workgroups per unit" if parts > 1 else ", one workgroup per unit")
+                               + (", replayed from a HIP graph" if args.graph else ""),
                    "units": units, "slots_per_unit": wl.slot_capacity},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
                      "traffic": traffic,

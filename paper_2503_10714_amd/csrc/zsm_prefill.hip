@@ -3,6 +3,8 @@
 // not depend on the summation order used here.
 #include "zsm_prefill.hpp"
 
+#include <type_traits>
+
 namespace zsm {
 namespace {
 
@@ -752,32 +754,51 @@ __global__ __launch_bounds__(256) void pf_residual_final(PrefillArgs a, PrefillW
     }
 }
 
-// ---- P5 for B_r >= 2: Alg. 1's residual branch, token by token --------------------------
-// The tokens that were not kept are absorbed in position order: the first B_r open the
-// residual slots, every later one is merged into the slot with the largest key dot product
-// (Eq. 5, lowest index on ties) by the incremental mean of Eq. 6.  Each merge changes a key
-// the next token's choice depends on, so the walk is sequential per unit: one wave per unit.
-// What keeps the step short:
-//   * the prompt is walked in blocks of 16 positions whose K and V rows and keep flags are
-//     requested a block ahead (registers) and staged in LDS, so no step waits for memory;
-//   * a residual key's dot product is split over LPS = 1, 2 or 4 lanes (64 / the power of two
-//     above B_r), each with four independent fp64 accumulators; the arg-max over the keys is a
-//     DPP reduction inside 16-lane rows plus scalar reads of the row winners;
-//   * keys and values live in LDS in their fp32 storage form and are rounded to it after every
-//     merge (so the next choice sees what the stored state would give).
+// ---- P5 for B_r >= 2, block form ---------------------------------------------------------
+// The same walk (Alg. 1's residual branch token by token, Eq. 5 and Eq. 6, one wave per unit),
+// organised so that the work per token that has to wait for the previous token's merge is small:
+//   * Per block of 16 positions the dot products of all 16 tokens with all residual keys are one
+//     fp64 matrix product on the matrix cores (v_mfma_f64_16x16x4: tokens x channels times
+//     channels x keys, 16 keys per column block), and so is the block's Gram matrix x_i . x_j.
+//   * A merge changes one key: k' = (w k + x_i) / (w + 1), rounded to fp32.  For the later tokens
+//     j of the block only that key's column changes, to k' . x_j = (w (k . x_j) + x_i . x_j) / (w + 1)
+//     up to the rounding of k' to fp32, which moves the dot product by at most
+//     2^-24 |k'| |x_j|.  So the column is updated from the Gram row in a few instructions, and
+//     the error that the skipped re-evaluation leaves is bounded: each merge adds at most
+//     2^-23 * n(k') * X to the column's error, n(k') = (w n(k) + |x_i|) / (w + 1) being a running
+//     bound of the key's norm (a mean of tokens; exact when the last slot was opened) and X the
+//     largest token norm of the block.  E is the largest such error over the columns.
+//   * A choice is taken from these values only when the best exceeds the runner-up by more than
+//     2E; otherwise the token's dot products are re-evaluated from the stored fp32 keys, as
+//     they are while the residual slots are still being opened.  Choices are therefore the ones
+//     an evaluation from the stored keys gives.  Best and runner-up come from two 16-lane
+//     maxima over integer order keys of the dot products with the slot index in the low bits
+//     (v_max_i32 / v_max_u32 with DPP operands: one instruction per exchange).
+//   * Eq. 6's quotient is formed with the correctly rounded reciprocal of w + 1 and one
+//     residual correction (q0 = n r, q = q0 + (n - q0 d) r), which is the correctly rounded
+//     quotient n / d for integer d, so the stored means are what a division gives.
 constexpr int PF_RMAX = 64;   // residual slots the wave can own
-constexpr int PF_GB = 16;     // positions per staged block
+constexpr int PF_GB = 16;     // positions per block
 
+// every pattern used here reads a lane that exists, so the destination needs no prior value (bound_ctrl)
+template <int CTRL>
+__device__ __forceinline__ int dpp_mov_i(int v) { return __builtin_amdgcn_mov_dpp(v, CTRL, 0xf, 0xf, true); }
+template <int CTRL>
+__device__ __forceinline__ double dpp_mov_d(double v) {
+    return __hiloint2double(dpp_mov_i<CTRL>(__double2hiint(v)), dpp_mov_i<CTRL>(__double2loint(v)));
+}
+// the larger of two doubles that are never NaN (a compare and two selects: no canonicalisation)
+__device__ __forceinline__ double max_d(double a, double b) { return a > b ? a : b; }
 // Arg-max of (value, index) over the lanes of each 16-lane row by four DPP exchanges (lane pairs
 // i^1, i^2, i <-> 7-i, i <-> 15-i: after them every lane of a row holds the row's winner), ties to
 // the lower index; no LDS round trip and no compare chain.
 template <int CTRL>
 __device__ __forceinline__ void dpp_argmax_step(double& v, int& idx) {
-    const int lo = __builtin_amdgcn_update_dpp(0, __double2loint(v), CTRL, 0xf, 0xf, false);
-    const int hi = __builtin_amdgcn_update_dpp(0, __double2hiint(v), CTRL, 0xf, 0xf, false);
-    const int i2 = __builtin_amdgcn_update_dpp(0, idx, CTRL, 0xf, 0xf, false);
-    const double v2 = __hiloint2double(hi, lo);
-    if (v2 > v || (v2 == v && i2 < idx)) { v = v2; idx = i2; }
+    const double v2 = dpp_mov_d<CTRL>(v);
+    const int i2 = dpp_mov_i<CTRL>(idx);
+    const bool take = (v2 > v) | ((v2 == v) & (i2 < idx));
+    v = take ? v2 : v;
+    idx = take ? i2 : idx;
 }
 __device__ __forceinline__ void row_argmax(double& v, int& idx) {
     dpp_argmax_step<0xB1>(v, idx);    // quad_perm [1,0,3,2]
@@ -785,9 +806,59 @@ __device__ __forceinline__ void row_argmax(double& v, int& idx) {
     dpp_argmax_step<0x141>(v, idx);   // row_half_mirror
     dpp_argmax_step<0x140>(v, idx);   // row_mirror
 }
+__device__ __forceinline__ double row_max(double v) {
+    v = max_d(v, dpp_mov_d<0xB1>(v));
+    v = max_d(v, dpp_mov_d<0x4E>(v));
+    v = max_d(v, dpp_mov_d<0x141>(v));
+    v = max_d(v, dpp_mov_d<0x140>(v));
+    return v;
+}
+// Order key of a dot product: two 32-bit words (hi compared signed, lo unsigned) that order as the doubles do,
+// with the key's index in the six lowest bits of lo (which moves the value by less than 2^-46 of itself) so that
+// the largest key names the arg-max, the lower index winning between equal dot products.
+struct OrdKey { int hi; uint32_t lo; };
+__device__ __forceinline__ OrdKey ord_key(double v, int idx) {
+    const int h = __double2hiint(v);
+    const int sgn = h >> 31;                                  // all ones for negative values
+    OrdKey k;
+    k.hi = h ^ (sgn & 0x7fffffff);
+    k.lo = (((uint32_t)__double2loint(v) ^ (uint32_t)sgn) & ~63u) | (uint32_t)(63 - idx);
+    return k;
+}
+__device__ __forceinline__ double ord_value(int hi, uint32_t lo) {   // the (tagged) double behind a key
+    const int sgn = hi >> 31;
+    return __hiloint2double(hi ^ (sgn & 0x7fffffff), (int)(lo ^ (uint32_t)sgn));
+}
+__device__ __forceinline__ bool ord_less(const OrdKey& a, const OrdKey& b) { return a.hi < b.hi || (a.hi == b.hi && a.lo < b.lo); }
+// maximum over the 16 lanes of each row: the high words first, then the low words of the lanes that hold that high word
+template <int CTRL>
+__device__ __forceinline__ int dpp_max_i(int v) { const int o = dpp_mov_i<CTRL>(v); return o > v ? o : v; }
+template <int CTRL>
+__device__ __forceinline__ uint32_t dpp_max_u(uint32_t v) { const uint32_t o = (uint32_t)dpp_mov_i<CTRL>((int)v); return o > v ? o : v; }
+__device__ __forceinline__ OrdKey row_max_key(const OrdKey& k) {
+    int h = k.hi;
+    h = dpp_max_i<0xB1>(h); h = dpp_max_i<0x4E>(h); h = dpp_max_i<0x141>(h); h = dpp_max_i<0x140>(h);
+    uint32_t l = k.hi == h ? k.lo : 0u;
+    l = dpp_max_u<0xB1>(l); l = dpp_max_u<0x4E>(l); l = dpp_max_u<0x141>(l); l = dpp_max_u<0x140>(l);
+    return OrdKey{h, l};
+}
+__device__ __forceinline__ double readlane_d(double v, int l) {
+    return __hiloint2double(__builtin_amdgcn_readlane(__double2hiint(v), l), __builtin_amdgcn_readlane(__double2loint(v), l));
+}
 
-template <typename T, int D, int LPS>
-__global__ __launch_bounds__(64) void pf_residual_greedy(PrefillArgs a, PrefillWs ws) {
+// State of the walk that lives in registers while whole blocks are absorbed.
+template <int NCB>
+struct BlockCols {
+    double dv[NCB][4];  // dot products: lane l holds token 4r + l/16 against key 16cb + l%16 in dv[cb][r]
+    double gram[4];     // x_a . x_b: token a = 4r + l/16, token b = l%16, in gram[r]
+    int wreg[NCB];      // fusion count of key 16cb + l%16
+    double knorm[NCB];  // upper bound of that key's norm
+    double cerr[NCB];   // how far this block's updated dot products of that key may be from what the stored key gives
+    double xnorm;       // norm of token l%16 (valid in the lane whose row group l/16 is that token's: l/16 = (l%16) % 4)
+};
+
+template <typename T, int D, int NCB>
+__global__ __launch_bounds__(64, 1) void pf_residual_blocks(PrefillArgs a, PrefillWs ws) {
     const CacheView& cv = a.cv;
     const int lu = blockIdx.x;
     const int ug = a.unit0 + lu;
@@ -796,17 +867,17 @@ __global__ __launch_bounds__(64) void pf_residual_greedy(PrefillArgs a, PrefillW
     const int Br = cv.Br;
     const int lane = threadIdx.x;
     constexpr int RS = D + 4;   // padded row stride (floats): lanes reading 16 bytes of different rows hit different banks
-    constexpr int CPL = D / 64; // channels per lane in the merge
+    constexpr int CPL = D / 64; // channels per lane in the merge: CPL * lane .. CPL * lane + CPL - 1
     constexpr int EPL = 16 / sizeof(T);
-    constexpr int RL = D / EPL;               // 16-byte pieces per row
-    constexpr int NLD = PF_GB * RL / 64;      // wave-wide loads per block and array
-    static_assert(PF_GB * RL % 64 == 0, "");
+    constexpr int SPK = D / 4;                // matrix steps; lane (i = l%16, k = l/16) owns channels SPK*k .. SPK*k + SPK-1 of row i
+    constexpr int NLD = SPK / EPL;            // 16-byte pieces per lane, row and array
+    static_assert(SPK % EPL == 0 && NLD >= 1, "");
     extern __shared__ __align__(16) unsigned char smem[];
     float* Krs = reinterpret_cast<float*>(smem);            // [Br][RS]
     float* Vrs = Krs + (size_t)Br * RS;                      // [Br][RS]
     double* ktok = reinterpret_cast<double*>(Vrs + (size_t)Br * RS);   // [D]
     int* wcs = reinterpret_cast<int*>(ktok + D);             // [PF_RMAX] fusion counts
-    T* Kst = reinterpret_cast<T*>(wcs + PF_RMAX);            // [PF_GB][D] staged rows of the current block
+    T* Kst = reinterpret_cast<T*>(wcs + PF_RMAX);            // [PF_GB][D] rows of the current block
     T* Vst = Kst + PF_GB * D;
     float* s = cv.s + (size_t)ug * cv.cap;
     int32_t* pos = cv.pos + (size_t)ug * cv.cap;
@@ -817,123 +888,274 @@ __global__ __launch_bounds__(64) void pf_residual_greedy(PrefillArgs a, PrefillW
     const float* sc = reinterpret_cast<const float*>(a.ws + ws.sc) + (size_t)lu * a.T_max;
     const T* Ksrc = reinterpret_cast<const T*>(a.K) + (size_t)lu * a.T_max * D;
     const T* Vsrc = reinterpret_cast<const T*>(a.V) + (size_t)lu * a.T_max * D;
-
-    // LPS lanes per residual key (the host picks 64 / the power of two above B_r, at most 4)
-    constexpr int NS = 64 / LPS;              // lanes r, r + NS, ... share key r
-    const int r_own = lane % NS, h_own = lane / NS;
-    const bool dot_lane = r_own < Br;
-    constexpr int CH = D / LPS;               // channels per share
-    const int cbeg = h_own * CH;
+    const int ti = lane & 15, tk = lane >> 4;   // this lane's row of a block and its quarter of the channels
 
     for (int i = lane; i < Br * RS; i += 64) { Krs[i] = 0.f; Vrs[i] = 0.f; }
     for (int i = lane; i < PF_RMAX; i += 64) wcs[i] = 0;
     int n_open = 0;        // residual slots opened so far (wave-uniform)
 
-    // a block's rows and flags, requested one block ahead
+    // ---- one token the slow way: its dot products from the stored keys (Eq. 5), lane r against key r
+    auto exact_choice = [&](int i) -> int {
+        wave_sync();
+        for (int c = lane; c < D; c += 64) ktok[c] = (double)to_float(Kst[i * D + c]);
+        wave_sync();
+        double dot = -INFINITY;
+        if (lane < Br) {
+            double p0_ = 0.0, p1_ = 0.0, p2_ = 0.0, p3_ = 0.0;
+            const float* kr = Krs + lane * RS;
+#pragma unroll 4
+            for (int c = 0; c < D; c += 4) {
+                const float4 kv = *reinterpret_cast<const float4*>(kr + c);
+                p0_ = fma((double)kv.x, ktok[c + 0], p0_);
+                p1_ = fma((double)kv.y, ktok[c + 1], p1_);
+                p2_ = fma((double)kv.z, ktok[c + 2], p2_);
+                p3_ = fma((double)kv.w, ktok[c + 3], p3_);
+            }
+            dot = (p0_ + p1_) + (p2_ + p3_);
+        }
+        int rbest = lane;
+        row_argmax(dot, rbest);
+        // the four rows' winners meet in scalar registers; the lower row wins a tie (its indices are lower)
+        double bd = readlane_d(dot, 0);
+        int br = __builtin_amdgcn_readlane(rbest, 0);
+#pragma unroll
+        for (int row = 1; row < 4; ++row) {
+            const double d2 = readlane_d(dot, 16 * row);
+            const int r2 = __builtin_amdgcn_readlane(rbest, 16 * row);
+            if (d2 > bd) { bd = d2; br = r2; }
+        }
+        return br;
+    };
+
+    // ---- Eq. 6 for token i of the block into residual slot r (count wi before the merge, rinv = 1 / (wi + 1))
+    auto merge_into = [&](int i, int r, int wi, double rinv) {
+        const double wd = (double)wi, dd = wd + 1.0;
+        float kc[CPL], vc[CPL];
+#pragma unroll
+        for (int x = 0; x < CPL; ++x) {
+            kc[x] = to_float(Kst[i * D + CPL * lane + x]);
+            vc[x] = to_float(Vst[i * D + CPL * lane + x]);
+        }
+#pragma unroll
+        for (int x = 0; x < CPL; ++x) {
+            const int c = CPL * lane + x;
+            const double nk = fma(wd, (double)Krs[r * RS + c], (double)kc[x]);   // w * k is exact in fp64: this is the rounded sum
+            const double nv = fma(wd, (double)Vrs[r * RS + c], (double)vc[x]);
+            double qk = nk * rinv, qv = nv * rinv;
+            qk = fma(fma(-qk, dd, nk), rinv, qk);    // the correctly rounded quotient nk / dd
+            qv = fma(fma(-qv, dd, nv), rinv, qv);
+            Krs[r * RS + c] = (float)qk;
+            Vrs[r * RS + c] = (float)qv;
+        }
+        if (lane == 0) wcs[r] = wi + 1;
+    };
+
+    // a block's rows and flags, requested one block ahead: lane (i, k) takes its quarter of row i
     Raw<T, EPL> kreg[NLD], vreg[NLD];
     int kflag = 1;
     auto request = [&](int p0) {   // positions [p0, p0 + PF_GB); rows past the prompt read its last row
+        const int row = p0 + ti;
+        const size_t off = (size_t)(row < Tb ? row : Tb - 1) * D + SPK * tk;
 #pragma unroll
         for (int x = 0; x < NLD; ++x) {
-            const int piece = x * 64 + lane;
-            const int row = p0 + piece / RL;
-            const size_t off = (size_t)(row < Tb ? row : Tb - 1) * D + (piece % RL) * EPL;
-            kreg[x].load(Ksrc + off);
-            vreg[x].load(Vsrc + off);
+            kreg[x].load(Ksrc + off + x * EPL);
+            vreg[x].load(Vsrc + off + x * EPL);
         }
         const int t = p0 + lane;
         kflag = (lane < PF_GB && t < Tb) ? keep[t] : 1;   // 1 = not to be absorbed
     };
+
+    BlockCols<NCB> st;
+    bool fast = false;        // every residual slot is open: whole blocks go through the matrix cores
+
     if (Tb > 0) request(0);
     for (int p0 = 0; p0 < Tb; p0 += PF_GB) {
         wave_sync();   // the previous block's rows are no longer read
+        double xd[SPK];       // this lane's channels of its row, fp64: the A operand (and, for the Gram matrix, the B operand)
 #pragma unroll
         for (int x = 0; x < NLD; ++x) {
-            const int piece = x * 64 + lane;
-            *reinterpret_cast<Raw<T, EPL>*>(Kst + (size_t)piece * EPL) = kreg[x];
-            *reinterpret_cast<Raw<T, EPL>*>(Vst + (size_t)piece * EPL) = vreg[x];
+            *reinterpret_cast<Raw<T, EPL>*>(Kst + (size_t)ti * D + SPK * tk + x * EPL) = kreg[x];
+            *reinterpret_cast<Raw<T, EPL>*>(Vst + (size_t)ti * D + SPK * tk + x * EPL) = vreg[x];
+#pragma unroll
+            for (int e = 0; e < EPL; ++e) xd[x * EPL + e] = (double)kreg[x].get(e);
         }
-        unsigned long long todo = __ballot(kflag == 0);   // bit i: position p0 + i is absorbed
+        const unsigned long long todo = __ballot(kflag == 0);   // bit i: position p0 + i is absorbed
         if (p0 + PF_GB < Tb) request(p0 + PF_GB);
         wave_sync();
-        while (todo) {
-            const int i = __builtin_ctzll(todo);
-            todo &= todo - 1;
-            const int t = p0 + i;
-            float kc[CPL], vc[CPL];
+        if (todo == 0ull) continue;
+
+        if (!fast) {
+            // the residual set still has room (Alg. 1: the token opens the next slot), or the block began that way
+            unsigned long long td = todo;
+            while (td) {
+                const int i = __builtin_ctzll(td);
+                td &= td - 1;
+                if (n_open < Br) {
 #pragma unroll
-            for (int x = 0; x < CPL; ++x) {
-                kc[x] = to_float(Kst[i * D + lane + 64 * x]);
-                vc[x] = to_float(Vst[i * D + lane + 64 * x]);
+                    for (int x = 0; x < CPL; ++x) {
+                        Krs[n_open * RS + CPL * lane + x] = to_float(Kst[i * D + CPL * lane + x]);
+                        Vrs[n_open * RS + CPL * lane + x] = to_float(Vst[i * D + CPL * lane + x]);
+                    }
+                    if (lane == 0) {
+                        wcs[n_open] = 1;
+                        pos[n_open] = p0 + i;
+                        s[n_open] = sc[p0 + i];
+                    }
+                    ++n_open;
+                    wave_sync();
+                    continue;
+                }
+                const int r = exact_choice(i);
+                const int wi = wcs[r];
+                wave_sync();   // every lane has read the count
+                merge_into(i, r, wi, 1.0 / ((double)wi + 1.0));
+                wave_sync();
             }
-            if (n_open < Br) {
-                // Alg. 1: the residual set still has room, the token opens slot n_open
+            if (n_open == Br) {
+                // from the next block on: counts and reciprocals of this lane's columns, and the norm bound
+                fast = true;
+#pragma unroll
+                for (int cb = 0; cb < NCB; ++cb) {
+                    const int r = 16 * cb + ti;
+                    st.wreg[cb] = r < Br ? wcs[r] : 1;
+                    double n2 = 0.0;
+                    const float* kr = Krs + (size_t)(r < Br ? r : Br - 1) * RS;
+                    for (int c = 0; c < D; ++c) { const double x = (double)kr[c]; n2 = fma(x, x, n2); }
+                    st.knorm[cb] = sqrt(n2) * (1.0 + 1e-12);
+                }
+            }
+            continue;
+        }
+
+        // ---- whole block: all dot products and the Gram matrix on the matrix cores ----------
+        {
+            d4_t acc[NCB], gacc = d4_t{0.0, 0.0, 0.0, 0.0};
+            const float* kb[NCB];
+#pragma unroll
+            for (int cb = 0; cb < NCB; ++cb) {
+                acc[cb] = d4_t{0.0, 0.0, 0.0, 0.0};
+                const int r = 16 * cb + ti;
+                kb[cb] = Krs + (size_t)(r < Br ? r : Br - 1) * RS + SPK * tk;   // a column past B_r repeats the last key; it is masked below
+            }
+#pragma unroll
+            for (int s4 = 0; s4 < SPK; s4 += 4) {
+                float4 kv[NCB];
+#pragma unroll
+                for (int cb = 0; cb < NCB; ++cb) kv[cb] = *reinterpret_cast<const float4*>(kb[cb] + s4);
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+#pragma unroll
+                    for (int cb = 0; cb < NCB; ++cb) {
+                        const float kf = e == 0 ? kv[cb].x : (e == 1 ? kv[cb].y : (e == 2 ? kv[cb].z : kv[cb].w));
+                        acc[cb] = __builtin_amdgcn_mfma_f64_16x16x4f64(xd[s4 + e], (double)kf, acc[cb], 0, 0, 0);
+                    }
+                    gacc = __builtin_amdgcn_mfma_f64_16x16x4f64(xd[s4 + e], xd[s4 + e], gacc, 0, 0, 0);
+                }
+            }
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                st.gram[r] = gacc[r];
+#pragma unroll
+                for (int cb = 0; cb < NCB; ++cb) st.dv[cb][r] = acc[cb][r];
+            }
+        }
+        // token norms (the Gram diagonal: token t against itself sits in lane 16 * (t % 4) + t, register t / 4) and the largest one
+        double xmax = 0.0;
+        {
+            double n2 = 0.0;
+#pragma unroll
+            for (int r = 0; r < 4; ++r) n2 = (ti == 4 * r + tk) ? st.gram[r] : n2;   // x_t . x_t of token t = l%16, where it exists
+            st.xnorm = sqrt(n2) * (1.0 + 1e-12);
+            n2 = row_max(st.xnorm);
+            xmax = max_d(max_d(readlane_d(n2, 0), readlane_d(n2, 16)), max_d(readlane_d(n2, 32), readlane_d(n2, 48)));
+        }
+        // 2^-24 |k'| |x| for the rounding of a merged key to fp32, doubled for the fp64 arithmetic around it
+        const double err_unit = 1.1920928955078125e-07 * xmax;
+        double emax = 0.0;    // largest error of a column so far in this block (wave-uniform)
+#pragma unroll
+        for (int cb = 0; cb < NCB; ++cb) st.cerr[cb] = 0.0;
+
+        // token I of the block (compile-time: it selects registers and lane patterns)
+        auto token_step = [&](auto Ic) {
+            constexpr int I = decltype(Ic)::value;
+            constexpr int R = I / 4, RG = I % 4;
+            if (!((todo >> I) & 1ull)) return;
+            // this lane's best and second best over its columns (keys 16cb + l%16), then over the 16 lanes of the row
+            const OrdKey none{(int)0x80000000, 0u};           // below every value
+            OrdKey m1 = none, m2 = none;
+#pragma unroll
+            for (int cb = 0; cb < NCB; ++cb) {
+                const int idx = 16 * cb + ti;
+                OrdKey v = ord_key(st.dv[cb][R], idx);
+                if (idx >= Br) v = none;
+                const bool up = ord_less(m1, v);
+                const OrdKey lo = up ? m1 : v;                 // the smaller of the two
+                m1 = up ? v : m1;
+                m2 = ord_less(m2, lo) ? lo : m2;
+            }
+            const OrdKey w1 = row_max_key(m1);
+            const bool mine = m1.hi == w1.hi && m1.lo == w1.lo;   // keys are distinct: equality names the winner's lane
+            const OrdKey w2 = row_max_key(mine ? m2 : m1);
+            const int h1 = __builtin_amdgcn_readlane(w1.hi, 16 * RG), h2 = __builtin_amdgcn_readlane(w2.hi, 16 * RG);
+            const uint32_t l1 = (uint32_t)__builtin_amdgcn_readlane((int)w1.lo, 16 * RG), l2 = (uint32_t)__builtin_amdgcn_readlane((int)w2.lo, 16 * RG);
+            const double d1 = ord_value(h1, l1), d2 = ord_value(h2, l2);
+            int rbest = 63 - (int)(l1 & 63u);
+            // every value is within emax of what the stored keys give, and the tag bits move it by less than 2^-46 of itself
+            if (!(d1 - d2 > 2.0 * emax + 3e-14 * (fabs(d1) + fabs(d2)))) rbest = exact_choice(I);
+            const int cbs = rbest >> 4, col = rbest & 15;
+            const bool is_col = ti == col;
+#pragma unroll
+            for (int cb = 0; cb < NCB; ++cb) {
+                if (cb != cbs) continue;      // wave-uniform
+                const int wi = __builtin_amdgcn_readlane(st.wreg[cb], col);   // the key's count, from a lane that owns the column
+                const double wd = (double)wi, dd = wd + 1.0;
+                // Eq. 6: the rows are requested first, the arithmetic that does not need them runs meanwhile
+                float kc[CPL], vc[CPL], ko[CPL], vo[CPL];
 #pragma unroll
                 for (int x = 0; x < CPL; ++x) {
-                    Krs[n_open * RS + lane + 64 * x] = kc[x];
-                    Vrs[n_open * RS + lane + 64 * x] = vc[x];
+                    kc[x] = to_float(Kst[I * D + CPL * lane + x]);
+                    vc[x] = to_float(Vst[I * D + CPL * lane + x]);
+                    ko[x] = Krs[rbest * RS + CPL * lane + x];
+                    vo[x] = Vrs[rbest * RS + CPL * lane + x];
                 }
-                if (lane == n_open) {
-                    wcs[n_open] = 1;
-                    pos[n_open] = t;
-                    s[n_open] = sc[t];
+                const double ri = 1.0 / dd;                   // correctly rounded
+                // the column's dot products with the block's later tokens: (w d + x_I . x_j) / (w + 1)
+#pragma unroll
+                for (int r = R; r < 4; ++r) {
+                    const double gb = dpp_mov_d<0x150 + I>(st.gram[r]);   // row broadcast of lane I: x_(4r + l/16) . x_I
+                    const double nd = fma(wd, st.dv[cb][r], gb) * ri;
+                    st.dv[cb][r] = is_col ? nd : st.dv[cb][r];
                 }
-                ++n_open;
-                wave_sync();
-                continue;
-            }
+                // the merged key's norm bound, and what the skipped re-evaluation of its column may now be off by
+                const double xn = readlane_d(st.xnorm, 16 * RG + I);
+                const double kn = fma(wd, st.knorm[cb], xn) * ri * (1.0 + 2.4e-7);
+                const double ce = st.cerr[cb] + err_unit * kn;
+                st.knorm[cb] = is_col ? kn : st.knorm[cb];
+                st.cerr[cb] = is_col ? ce : st.cerr[cb];
+                st.wreg[cb] = is_col ? wi + 1 : st.wreg[cb];
+                emax = max_d(emax, readlane_d(st.cerr[cb], col));
 #pragma unroll
-            for (int x = 0; x < CPL; ++x) ktok[lane + 64 * x] = (double)kc[x];
-            wave_sync();
-            // Eq. 5: k_r . k_t, this lane's share of the channels
-            double dot = 0.0;
-            if (dot_lane) {
-                double p0_ = 0.0, p1_ = 0.0, p2_ = 0.0, p3_ = 0.0;
-                const float* kr = Krs + r_own * RS + cbeg;
-                const double* kt = ktok + cbeg;
-#pragma unroll
-                for (int c = 0; c < CH; c += 4) {
-                    const float4 kv = *reinterpret_cast<const float4*>(kr + c);
-                    p0_ = fma((double)kv.x, kt[c + 0], p0_);
-                    p1_ = fma((double)kv.y, kt[c + 1], p1_);
-                    p2_ = fma((double)kv.z, kt[c + 2], p2_);
-                    p3_ = fma((double)kv.w, kt[c + 3], p3_);
+                for (int x = 0; x < CPL; ++x) {
+                    const int c = CPL * lane + x;
+                    const double nk = fma(wd, (double)ko[x], (double)kc[x]);   // w * k is exact in fp64: this is the rounded sum
+                    const double nv = fma(wd, (double)vo[x], (double)vc[x]);
+                    double qk = nk * ri, qv = nv * ri;
+                    qk = fma(fma(-qk, dd, nk), ri, qk);    // the correctly rounded quotient nk / dd
+                    qv = fma(fma(-qv, dd, nv), ri, qv);
+                    Krs[rbest * RS + c] = (float)qk;
+                    Vrs[rbest * RS + c] = (float)qv;
                 }
-                dot = (p0_ + p1_) + (p2_ + p3_);
+                if (lane == 0) wcs[rbest] = wi + 1;
             }
-            // the shares of one key meet (lanes r, r + NS, ...); then the arg-max over the keys: lanes
-            // 0 .. NS-1 hold one key's dot product each (-inf past B_r), rows of 16 lanes reduce by DPP,
-            // the row winners meet through scalar reads
-#pragma unroll
-            for (int o = NS * (LPS >> 1); o >= NS; o >>= 1) dot += __shfl_xor(dot, o, 64);
-            double dv = lane < Br ? dot : -INFINITY;
-            int rbest = lane;
-            row_argmax(dv, rbest);
-#pragma unroll
-            for (int row = 1; row < NS / 16; ++row) {
-                const double d2 = __hiloint2double(__builtin_amdgcn_readlane(__double2hiint(dv), 16 * row),
-                                                   __builtin_amdgcn_readlane(__double2loint(dv), 16 * row));
-                const int r2 = __builtin_amdgcn_readlane(rbest, 16 * row);
-                const double d0 = __hiloint2double(__builtin_amdgcn_readlane(__double2hiint(dv), 0),
-                                                   __builtin_amdgcn_readlane(__double2loint(dv), 0));
-                const int r0 = __builtin_amdgcn_readlane(rbest, 0);
-                // row 0 accumulates the winner (its indices are lower: a tie stays with it)
-                const bool take = d2 > d0;
-                if (lane < 16) { dv = take ? d2 : dv; rbest = take ? r2 : rbest; }
-            }
-            rbest = __builtin_amdgcn_readfirstlane(rbest);
-            const int wi = wcs[rbest];
-            const double wd = (double)wi;
-#pragma unroll
-            for (int x = 0; x < CPL; ++x) {
-                const int c = lane + 64 * x;
-                const double k0 = (double)Krs[rbest * RS + c], v0 = (double)Vrs[rbest * RS + c];
-                Krs[rbest * RS + c] = (float)(__dadd_rn(__dmul_rn(wd, k0), (double)kc[x]) / (wd + 1.0));
-                Vrs[rbest * RS + c] = (float)(__dadd_rn(__dmul_rn(wd, v0), (double)vc[x]) / (wd + 1.0));
-            }
-            wave_sync();   // every lane has read the count
-            if (lane == 0) wcs[rbest] = wi + 1;
-        }
+        };
+        token_step(std::integral_constant<int, 0>{});  token_step(std::integral_constant<int, 1>{});
+        token_step(std::integral_constant<int, 2>{});  token_step(std::integral_constant<int, 3>{});
+        token_step(std::integral_constant<int, 4>{});  token_step(std::integral_constant<int, 5>{});
+        token_step(std::integral_constant<int, 6>{});  token_step(std::integral_constant<int, 7>{});
+        token_step(std::integral_constant<int, 8>{});  token_step(std::integral_constant<int, 9>{});
+        token_step(std::integral_constant<int, 10>{}); token_step(std::integral_constant<int, 11>{});
+        token_step(std::integral_constant<int, 12>{}); token_step(std::integral_constant<int, 13>{});
+        token_step(std::integral_constant<int, 14>{}); token_step(std::integral_constant<int, 15>{});
     }
     wave_sync();
     // write the residual slots back; slots never opened are empty
@@ -994,9 +1216,10 @@ hipError_t launch_prefill_td(const PrefillArgs& a, hipStream_t st) {
     } else if (cv.Br > 1) {
         const size_t lds = sizeof(float) * 2 * (size_t)cv.Br * (D + 4) + sizeof(double) * D + sizeof(int) * PF_RMAX +
                            2 * PF_GB * D * sizeof(T);
-        // lanes per residual key: 64 / the power of two above B_r, at most 4
-        void (*kern)(PrefillArgs, PrefillWs) = cv.Br > 32 ? pf_residual_greedy<T, D, 1>
-                                               : (cv.Br > 16 ? pf_residual_greedy<T, D, 2> : pf_residual_greedy<T, D, 4>);
+        // column blocks of 16 residual keys
+        void (*kern)(PrefillArgs, PrefillWs) = cv.Br > 48 ? pf_residual_blocks<T, D, 4>
+                                               : (cv.Br > 32 ? pf_residual_blocks<T, D, 3>
+                                                  : (cv.Br > 16 ? pf_residual_blocks<T, D, 2> : pf_residual_blocks<T, D, 1>));
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, 96 * 1024);
         if (e != hipSuccess) return e;
         hipLaunchKernelGGL(kern, dim3(a.n_units), dim3(64), lds, st, a, ws);
