@@ -142,6 +142,9 @@ PREFILL_CASES = {
                                             head_dim=128, q_per_kv=2, outliers=True),
     "residual_not_filled": lambda: small("pf_res_not_filled", n_residual=8, prompt_len=45, budget=48, window=8),
     "residual_64_bf16": lambda: small("pf_res64", n_residual=64, prompt_len=700, budget=200, dtype="bf16", head_dim=128),
+    # three and two column blocks of residual keys in the block form of the absorption, fp32 / d = 64 operands
+    "residual_40_f32_d128": lambda: small("pf_res40", n_residual=40, prompt_len=900, budget=120, head_dim=128, window=16),
+    "residual_20_f16_d64": lambda: small("pf_res20", n_residual=20, prompt_len=1500, budget=100, dtype="f16", window=32, outliers=True),
     # more candidates than the selection kernel holds in registers (65 536): its histogram fallback
     "long_prompt": lambda: small("pf_long_prompt", n_kv_heads=1, prompt_len=70000, budget=3000, window=16),
     # several 32-row passes per unit (grouped queries x a 48-row window): scores pass through the fp64 accumulator

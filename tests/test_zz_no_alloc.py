@@ -28,14 +28,15 @@ def _step_both(wl, ref, sta, step):
     L, S, H, G, d = wl.n_layers, wl.n_seqs, wl.n_kv_heads, wl.q_per_kv, wl.head_dim
     qs, ks, vs = zip(*[synth.decode_inputs(wl, l, step) for l in range(L)])
     q, k, v = torch.stack(qs).to(DEV), torch.stack(ks).to(DEV), torch.stack(vs).to(DEV)
-    out_r = torch.empty(L, S, H, G, d, dtype=torch.float32, device=DEV)
+    out_r = torch.full((L, S, H, G, d), float("nan"), dtype=torch.float32, device=DEV)
     out_s = torch.full_like(out_r, float("nan"))
     info_r = tuple(torch.empty(L, S, H, dtype=torch.int32, device=DEV) for _ in range(3))
     info_s = tuple(torch.full((L, S, H), -7, dtype=torch.int32, device=DEV) for _ in range(3))
     zb.zsm_decode_step(ref.handle, 0, L, q, k, v, out_r, *info_r)
     zb.zsm_decode_step_static(sta.handle, 0, L, q, k, v, out_s, *info_s)
     torch.cuda.synchronize()
-    assert torch.equal(out_s, out_r), f"step {step}: outputs differ by {(out_s - out_r).abs().max().item():.3e}"
+    assert torch.equal(out_s, out_r), (f"{wl.name} step {step}: outputs differ by {(out_s - out_r).abs().max().item():.3e}; not written: "
+                                       f"static {torch.isnan(out_s).float().mean().item():.3f}, ordinary {torch.isnan(out_r).float().mean().item():.3f}")
     for a, b in zip(info_s, info_r):
         assert torch.equal(a, b), f"step {step}: decisions differ"
 
