@@ -347,8 +347,10 @@ __device__ __forceinline__ void k_compute_mfma4(const Raw<KT, EPL>* kr, const do
 }
 
 // Pass 1 for rows that may be empty: load only the occupied ones (an empty slot may hold any
-// bit pattern), then k_compute.
-template <typename KT, int UU, int D, int G, int EPL, int LPR, int RPL, bool QLDS>
+// bit pattern), then k_compute.  LOADALL requests every row without waiting for its occupancy
+// (one memory round trip instead of two); what an empty row yields is never used: k_compute
+// stores 0 for it.
+template <typename KT, int UU, int D, int G, int EPL, int LPR, int RPL, bool QLDS, bool LOADALL = false>
 __device__ __forceinline__ void k_tile_masked(const KT* __restrict__ Kb, int row0, int nrows, int zidx0,
                                               const int32_t* __restrict__ posb, const int32_t* __restrict__ wb,
                                               double alpha, double scale, const Query<G, EPL, QLDS>& qq,
@@ -356,13 +358,17 @@ __device__ __forceinline__ void k_tile_masked(const KT* __restrict__ Kb, int row
                                               double* part_w, int lane) {
     const int grp = lane / LPR, seg = lane % LPR;
     Raw<KT, EPL> kr[UU];
+    if constexpr (LOADALL) {
+        tile_load<KT, UU, D, EPL, LPR, RPL>(kr, Kb, row0, nrows, lane);
+    } else {
 #pragma unroll
-    for (int u = 0; u < UU; ++u) {
-        const int r = row0 + u * RPL + grp;
-        if (r < nrows && (posb == nullptr || posb[r] >= 0) && (wb == nullptr || wb[r] > 0))
-            kr[u].load(Kb + (size_t)r * D + seg * EPL);
-        else
-            kr[u].zero();
+        for (int u = 0; u < UU; ++u) {
+            const int r = row0 + u * RPL + grp;
+            if (r < nrows && (posb == nullptr || posb[r] >= 0) && (wb == nullptr || wb[r] > 0))
+                kr[u].load(Kb + (size_t)r * D + seg * EPL);
+            else
+                kr[u].zero();
+        }
     }
     k_compute<KT, UU, true, D, G, EPL, LPR, RPL, QLDS>(kr, row0, nrows, zidx0, posb, wb, alpha, scale, qq, C, lsum, et,
                                                        Bz, part_w, lane);
@@ -618,12 +624,34 @@ __device__ __forceinline__ void decode_finish(const DecodeArgs& a, const CacheVi
                 // Eq. 5: the residual key with the largest dot product, lowest index on ties
                 double bd = -INFINITY;
                 br = 0x7fffffff;
-                for (int r = wave; r < Br; r += NW) {
-                    double p = 0.0;
-                    for (int ch = lane; ch < D; ch += 64)
-                        p = fma((double)Kr[r * D + ch], (double)to_float(Kt[(size_t)ct * D + ch]), p);
-                    p = wave_sum(p);
-                    if (p > bd) { bd = p; br = r; }
+                // A wave takes rows wave, wave + NW, ...; the rows of a batch are all requested
+                // before the first is used, so a batch costs one memory round trip, not one per row.
+                constexpr int CPL = (D + 63) / 64, RB = 8;
+                float kt[CPL];
+#pragma unroll
+                for (int x = 0; x < CPL; ++x) {
+                    const int ch = lane + 64 * x;
+                    kt[x] = ch < D ? to_float(Kt[(size_t)ct * D + ch]) : 0.f;
+                }
+                for (int r0 = wave; r0 < Br; r0 += NW * RB) {
+                    float kr[RB][CPL];
+#pragma unroll
+                    for (int y = 0; y < RB; ++y) {
+                        const int r = r0 + y * NW < Br ? r0 + y * NW : Br - 1;
+#pragma unroll
+                        for (int x = 0; x < CPL; ++x) {
+                            const int ch = lane + 64 * x;
+                            kr[y][x] = ch < D ? Kr[r * D + ch] : 0.f;
+                        }
+                    }
+#pragma unroll
+                    for (int y = 0; y < RB; ++y) {
+                        double p = 0.0;
+#pragma unroll
+                        for (int x = 0; x < CPL; ++x) p = fma((double)kr[y][x], (double)kt[x], p);
+                        p = wave_sum(p);
+                        if (r0 + y * NW < Br && p > bd) { bd = p; br = r0 + y * NW; }
+                    }
                 }
                 if (lane == 0) { dotw[wave] = bd; misc[4 + wave] = br; }
                 __syncthreads();
@@ -822,14 +850,18 @@ __global__ __launch_bounds__(NW * 64, G == 1 ? 4 : 2) void decode_kernel(DecodeA
         }
     }
 
+    // Residual rows are dealt to the waves RU wave-wide loads at a time (wave x takes loads RU*x ..
+    // RU*x + RU - 1, then RU*NW further on): up to RU*NW*RPL residual slots cost each wave one
+    // memory round trip per pass.
+    constexpr int RU = 2;
     // ---- pass 1 (D1): logits of this workgroup's slots, exp(logit - C) into LDS ---------
     // Residual slots (fp32 rows, log-count term) and the incoming token itself come first: their
     // few rows are requested while the wave's first K tile is still on its way, so their round
     // trip hides behind that one instead of standing alone at the end of the pass.
     if (part == 0) {
-        for (int t = wave; t * RPL < Br; t += NW)
-            k_tile_masked<float, 1, D, G, EPL, LPR, RPL, QLDS>(Kr, t * RPL, Br, 0, nullptr, w, alpha, scale, qq, C, lsum,
-                                                               et, Bz, part_w, klane);
+        for (int t = RU * wave; t * RPL < Br; t += RU * NW)
+            k_tile_masked<float, RU, D, G, EPL, LPR, RPL, QLDS, true>(Kr, t * RPL, Br, 0, nullptr, w, alpha, scale, qq, C,
+                                                                      lsum, et, Bz, part_w, klane);
         if (wave == NW - 1)
             k_tile_masked<T, 1, D, G, EPL, LPR, RPL, QLDS>(knew, 0, 1, znew, nullptr, nullptr, alpha, scale, qq, C, lsum,
                                                            et, Bz, part_w, klane);
@@ -871,14 +903,16 @@ __global__ __launch_bounds__(NW * 64, G == 1 ? 4 : 2) void decode_kernel(DecodeA
     // The wave's first tile of residual V rows and (last wave) the incoming token's V row are
     // requested before the barrier, so their round trip passes while the waves meet; rows whose
     // probability is exactly 0 (empty slots among them) are not loaded.  This wave wrote their
-    // exponentials itself (same tile assignment in both passes).
+    // exponentials itself (the first of the loads pass 1 dealt to it).
     constexpr bool VPRE = G <= 4;   // eight query heads leave no registers for it: their rows are loaded where they are used
-    Raw<float, EPL> vres;
+    constexpr bool VPRE2 = G <= 2;  // the wave's second load of residual rows is requested ahead too
+    Raw<float, EPL> vres, vres2;
     Raw<T, EPL> vnw;
     vres.zero();
+    vres2.zero();
     vnw.zero();
     if (VPRE && part == 0) {
-        const int r = wave * RPL + grp;
+        const int r = RU * wave * RPL + grp;
         bool any = false;
         if (r < Br) {
 #pragma unroll
@@ -912,7 +946,16 @@ __global__ __launch_bounds__(NW * 64, G == 1 ? 4 : 2) void decode_kernel(DecodeA
 #pragma unroll
         for (int e = 0; e < EPL; ++e) acc[g][e] = 0.f;
     if (VPRE && part == 0) {
-        if (wave * RPL < Br) v_compute<float, 1, D, G, EPL, LPR, RPL>(&vres, wave * RPL, Br, 0, rL, acc, et, Bz, lane);
+        // the wave's second load of residual V rows: requested now (every wave's exponentials are
+        // visible after the barrier), used after the sweep of the token rows
+        const int r2 = (RU * wave + 1) * RPL + grp;
+        bool any2 = false;
+        if (VPRE2 && r2 < Br) {
+#pragma unroll
+            for (int g = 0; g < G; ++g) any2 = any2 || (et[(size_t)g * Bz + r2] != 0.0);
+        }
+        if (any2) vres2.load(Vr + (size_t)r2 * D + seg * EPL);
+        if (RU * wave * RPL < Br) v_compute<float, 1, D, G, EPL, LPR, RPL>(&vres, RU * wave * RPL, Br, 0, rL, acc, et, Bz, lane);
         if (wave == NW - 1) v_compute<T, 1, D, G, EPL, LPR, RPL>(&vnw, 0, 1, znew, rL, acc, et, Bz, lane);
     }
     if (full) {
@@ -931,9 +974,17 @@ __global__ __launch_bounds__(NW * 64, G == 1 ? 4 : 2) void decode_kernel(DecodeA
             v_tile_masked<T, 1, D, G, EPL, LPR, RPL>(Vt, r0, row_e, zt, rL, acc, et, Bz, lane);
     }
     __builtin_amdgcn_s_setprio(0);
-    if (part == 0) {   // residual tiles beyond the waves' first ones (more than NW * RPL residual slots)
-        for (int t = wave + (VPRE ? NW : 0); t * RPL < Br; t += NW)
+    if (part == 0) {
+        if (VPRE2 && (RU * wave + 1) * RPL < Br)
+            v_compute<float, 1, D, G, EPL, LPR, RPL>(&vres2, (RU * wave + 1) * RPL, Br, 0, rL, acc, et, Bz, lane);
+        // the residual loads not requested ahead
+        for (int t = VPRE ? 0 : wave; t * RPL < Br; t += VPRE ? 1 : NW) {
+            if (VPRE) {   // loads 0 .. RU*NW - 1 belong to wave t / RU; the later ones go round
+                const int own = t < RU * NW ? t / RU : t % NW;
+                if (own != wave || (t < RU * NW && (t % RU == 0 || (VPRE2 && t % RU == 1)))) continue;
+            }
             v_tile_masked<float, 1, D, G, EPL, LPR, RPL>(Vr, t * RPL, Br, 0, rL, acc, et, Bz, lane);
+        }
         if (!VPRE && wave == NW - 1)
             v_tile_masked<T, 1, D, G, EPL, LPR, RPL>(vnew, 0, 1, znew, rL, acc, et, Bz, lane);
     }
