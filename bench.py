@@ -75,42 +75,58 @@ def device_info():
     return info
 
 
-def cpu_baseline(wl, n_units: int, n_steps: int):
-    """The CPU oracle, as it stands, on a bounded sample of the same workload: `n_units`
-    units (layer 0, heads 0..) through their own prefill, then `n_steps` timed decode steps."""
+def cpu_baseline(wl, n_units: int, n_steps: int, numpy_units: int = 2, numpy_steps: int = 16):
+    """The CPU oracle, as it stands, on a bounded sample of the same workload: `n_units` units (layer 0,
+    heads 0..) through their own prefill, then `n_steps` timed decode steps in the plain-C oracle (one OpenMP
+    thread per unit).  The NumPy oracle is timed beside it on a smaller sample."""
     import numpy as np
     import torch
+    from oracle import zsmerge_oracle_c as oc
     from oracle.zsmerge_oracle import UnitCache
     from paper_2503_10714_amd import synth
-    try:
-        from threadpoolctl import threadpool_info
-        threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
-    except Exception:
-        threads = 1
     sub = wl.sliced(n_layers=1, n_kv_heads=n_units)
     dev = "cuda:0" if torch.cuda.is_available() else "cpu"
     Q, K, V, lens = synth.prompt(sub, 0, device=dev)
     f = lambda t: t.detach().to("cpu").to(torch.float64).numpy()
     bp, bc, br = sub.budgets()
-    units = []
-    t0 = time.perf_counter()
-    for h in range(n_units):
-        u = UnitCache(sub.head_dim, sub.q_per_kv, bp[0], bc[0], br, lam=float(np.float32(sub.lam)), alpha=sub.alpha)
-        u.prefill_compress(f(Q[0, h]), f(K[0, h, :lens[0]]), f(V[0, h, :lens[0]]))
-        units.append(u)
-    t_prefill = time.perf_counter() - t0
+    lam, alpha = float(np.float32(sub.lam)), float(np.float32(sub.alpha))
+    T0, G, d = lens[0], sub.q_per_kv, sub.head_dim
     q, k, v = synth.decode_inputs_uniform(sub, [0], list(range(n_steps)), device=dev)
     q, k, v = f(q), f(k), f(v)
+
+    cb = oc.BatchCache(n_units, d, G, bp[0], bc[0], br, lam=lam, alpha=alpha)
+    t0 = time.perf_counter()
+    cb.prefill_compress(f(Q[0]), f(K[0, :, :T0]), f(V[0, :, :T0]))
+    t_prefill = time.perf_counter() - t0
     t0 = time.perf_counter()
     for s in range(n_steps):
+        cb.decode_step(q[s, 0, 0], k[s, 0, 0], v[s, 0, 0])
+    t_decode = time.perf_counter() - t0
+
+    try:
+        from threadpoolctl import threadpool_info
+        blas_threads = max([p.get("num_threads", 1) for p in threadpool_info() if p.get("user_api") == "blas"] or [1])
+    except Exception:
+        blas_threads = 1
+    units = []
+    for h in range(numpy_units):
+        u = UnitCache(d, G, bp[0], bc[0], br, lam=lam, alpha=alpha)
+        u.prefill_compress(f(Q[0, h]), f(K[0, h, :T0]), f(V[0, h, :T0]))
+        units.append(u)
+    t0 = time.perf_counter()
+    for s in range(numpy_steps):
         for h, u in enumerate(units):
             u.decode_step(q[s, 0, 0, h], k[s, 0, 0, h], v[s, 0, 0, h])
-    t_decode = time.perf_counter() - t0
+    t_numpy = time.perf_counter() - t0
     return {
-        "value": n_units * n_steps / t_decode, "unit": "unit-steps/s", "cores": int(threads), "kind": "oracle",
-        "host_cores": os.cpu_count(), "threads_note": "cores = threads NumPy's BLAS pool used (the oracle's only parallelism); host_cores = os.cpu_count()",
-        "sample": f"{n_units} units of layer 0 (T={lens[0]}, B={sub.slot_capacity}) x {n_steps} decode steps, NumPy fp64; "
-                  f"their oracle prefill took {t_prefill / n_units:.2f} s per unit (not in value)",
+        "value": n_units * n_steps / t_decode, "unit": "unit-steps/s", "cores": int(min(oc.threads(), n_units)), "kind": "oracle",
+        "host_cores": os.cpu_count(),
+        "threads_note": "cores = OpenMP threads of the C oracle that had a unit to work on; host_cores = os.cpu_count()",
+        "sample": f"{n_units} units of layer 0 (T={T0}, B={sub.slot_capacity}) x {n_steps} decode steps, plain C fp64 "
+                  f"(oracle/zsmerge_oracle_c.c, gcc -O2 -fopenmp); their oracle prefill took {t_prefill / n_units:.2f} s per unit "
+                  f"(not in value)",
+        "numpy_oracle": {"value": numpy_units * numpy_steps / t_numpy, "unit": "unit-steps/s", "cores": int(blas_threads),
+                         "sample": f"{numpy_units} of the same units x {numpy_steps} steps, NumPy fp64 (oracle/zsmerge_oracle.py)"},
     }
 
 
@@ -122,8 +138,8 @@ def main():
     ap.add_argument("--workload", type=int, default=2)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-units", type=int, default=32,
-                    help="units of layer 0 the CPU oracle is timed on (32 = one full layer of workload 2, about 20 s)")
-    ap.add_argument("--cpu-steps", type=int, default=512)
+                    help="units of layer 0 the CPU oracle is timed on (32 = one full layer of workload 2; with the default steps about 10 s of CPU work)")
+    ap.add_argument("--cpu-steps", type=int, default=2048)
     ap.add_argument("--layers-per-launch", type=int, default=0,
                     help="0 = all layers of the workload in one launch (the headline configuration); N = one launch "
                          "per N layers, as a model that runs its layers one after the other would call it")
@@ -144,9 +160,10 @@ def main():
                     help="after the run, copy a 1 GiB buffer three times with the library's plain copy kernel, so that "
                          "a counter run holds dispatches of known size to scale FETCH_SIZE / WRITE_SIZE by")
     ap.add_argument("--prefill-layers-per-call", type=int, default=0,
-                    help="layers compressed by one zsm_prefill_compress call: 0 = one layer per call with one residual slot, "
-                         "all layers in one call with more (their sequential absorption runs one wave per unit and needs the "
-                         "units of all layers to fill the chip); the prompts of that many layers are resident at once")
+                    help="layers compressed by one zsm_prefill_compress call; the prompts of that many layers are resident "
+                         "at once.  0 = as many as keep them under 64 GiB (a call of many layers has no launch gaps between "
+                         "its layers' kernels, and the sequential absorption of several residual slots, one wave per unit, "
+                         "needs the units of many layers to fill the chip)")
     ap.add_argument("--skip-prefill", action="store_true",
                     help="fill the cache by import of synthetic rows instead of running the prefill (profiling runs)")
     args = ap.parse_args()
@@ -187,7 +204,9 @@ def main():
     if not args.skip_prefill:
         ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         tot = 0.0
-        plc = args.prefill_layers_per_call if args.prefill_layers_per_call > 0 else (L if br > 1 else 1)
+        # default: as many layers per call as keep the resident prompts (K and V) under 64 GiB
+        per_layer = 2 * S * H * max(wl.seq_lens()) * d * e
+        plc = args.prefill_layers_per_call if args.prefill_layers_per_call > 0 else max(1, min(L, (64 << 30) // per_layer))
         for l0 in range(0, L, plc):
             l1 = min(L, l0 + plc)
             Q = K = V = None

@@ -24,6 +24,7 @@
 #pragma once
 
 #include <atomic>
+#include <type_traits>
 
 #include "zsm_common.hpp"
 
@@ -52,25 +53,30 @@ struct DecodeShape {
     static constexpr int UT = 4;                 // wave-wide loads per tile (two tiles are in flight)
     static constexpr int UH = 4;                 // loads per reduction granule
     static constexpr int R = UT * RPL;           // rows per wave tile
-    static constexpr int PART = UH * RPL * (LPR + 1);   // doubles of partial-dot staging per wave
+    static constexpr int RU = 2;                 // wave-wide loads of residual rows a wave requests together
     static constexpr int NT = NW * 64;
     // pass 1 of full tiles on the 4x4x4 fp64 matrix instruction: four query heads, 16 keys of 16 pieces each per tile
     static constexpr bool MFMA4 = (G == 4 || G == 8) && sizeof(T) == 2 && D == 128;   // G / 4 groups of four heads
+    // doubles of partial-dot staging per wave (the matrix path stages only its masked tiles: at most RU loads)
+    static constexpr int PART = (MFMA4 ? RU : UH) * RPL * (LPR + 1);
     // queries live in LDS instead of registers (G * EPL doubles per lane); the matrix path keeps its own
-    // operand registers and leaves the LDS copy to the masked tiles
+    // operand registers and leaves the LDS copy, in fp32 (exact: the queries have the cache's element
+    // type), to the masked tiles
     static constexpr bool QLDS = G > 4 || MFMA4;
-    // one LDS region serves the partial-dot staging of pass 1 and, after pass 2, the waves' partial outputs
+    using QE = typename std::conditional<MFMA4, float, double>::type;
+    static constexpr size_t QBYTES = QLDS ? sizeof(QE) * G * D : 0;
+    // one LDS region serves the partial-dot staging and the queries of pass 1 and, after pass 2, the
+    // waves' partial outputs
     static constexpr size_t STAGE_A = sizeof(double) * NW * PART, STAGE_B = sizeof(float) * NW * G * D;
-    static constexpr size_t STAGE = STAGE_A > STAGE_B ? STAGE_A : STAGE_B;
+    static constexpr size_t STAGE = STAGE_A + QBYTES > STAGE_B ? STAGE_A + QBYTES : STAGE_B;
     static_assert(LPR >= 1 && LPR <= 64 && 64 % LPR == 0, "row must split over a wave");
 
     // dynamic LDS bytes when `nz` slots (the incoming token counted) keep their exp(logit - C) in LDS
     __host__ __device__ static size_t lds_bytes(int nz) {
         size_t n = 0;
         n += sizeof(double) * G * (size_t)nz;          // et
-        n += STAGE;                                    // part (pass 1) / accw (after pass 2)
+        n += STAGE;                                    // part and queries (pass 1) / accw (after pass 2)
         n += sizeof(double) * NW * G;                  // red64
-        n += sizeof(double) * (QLDS ? G * D : 0);      // qlds
         n += sizeof(unsigned long long) * NW;          // keyw
         n += sizeof(double) * NW;                      // dotw
         n += sizeof(int) * (4 + NW);                   // misc
@@ -79,14 +85,14 @@ struct DecodeShape {
 };
 
 // The G query vectors, fp64: this lane's segment in registers, or all of them in LDS.
-template <int G, int EPL, bool QLDS>
+template <int G, int EPL, bool QLDS, typename QE = double>
 struct Query {
     double r[QLDS ? 1 : G][EPL];
-    const double* lds;    // [G][D] when QLDS
+    const QE* lds;    // [G][D] when QLDS
     __device__ __forceinline__ void get(int g, int seg, int D, double* out) const {
         if (QLDS) {
 #pragma unroll
-            for (int e = 0; e < EPL; ++e) out[e] = lds[g * D + seg * EPL + e];
+            for (int e = 0; e < EPL; ++e) out[e] = (double)lds[g * D + seg * EPL + e];
         } else {
 #pragma unroll
             for (int e = 0; e < EPL; ++e) out[e] = r[QLDS ? 0 : g][e];
@@ -118,10 +124,10 @@ __device__ __forceinline__ void tile_load(Raw<KT, EPL>* dst, const KT* __restric
 // exist.  For every existing row the holder lane stores exp(logit - C) (0 for an empty row) at
 // et[g][zidx0 + row] and adds it to lsum[g].  posb / wb (MASKED only) mark empty rows (pos < 0, w == 0); wb also adds
 // alpha*log(w) to the logit (Eq. 4).
-template <typename KT, int UU, bool MASKED, int D, int G, int EPL, int LPR, int RPL, bool QLDS>
+template <typename KT, int UU, bool MASKED, int D, int G, int EPL, int LPR, int RPL, bool QLDS, typename QQ>
 __device__ __forceinline__ void k_compute(const Raw<KT, EPL>* kr, int row0, int nrows, int zidx0,
                                           const int32_t* __restrict__ posb, const int32_t* __restrict__ wb,
-                                          double alpha, double scale, const Query<G, EPL, QLDS>& qq,
+                                          double alpha, double scale, const QQ& qq,
                                           const double* C, double* lsum, double* et, int Bz,
                                           double* part_w, int lane) {
     constexpr int UH = UU < 4 ? UU : 4;
@@ -262,9 +268,9 @@ struct GqOwn {
 
 // One full tile (4 wave-wide loads, every row occupied): exp(logit - C) of this lane's (row, head)
 // sums into et, their total into lsum_own.  c_own = C[GqOwn::head(seg)].
-template <typename KT, int D, int G, int EPL, int LPR, int RPL, bool QLDS>
+template <typename KT, int D, int G, int EPL, int LPR, int RPL, bool QLDS, typename QQ>
 __device__ __forceinline__ void k_compute_gq(const Raw<KT, EPL>* kr, int row0, int nrows, int zidx0, double scale,
-                                             const Query<G, EPL, QLDS>& qq, double c_own, double& lsum_own,
+                                             const QQ& qq, double c_own, double& lsum_own,
                                              double* et, int Bz, int lane) {
     using Own = GqOwn<G, LPR>;
     constexpr int UH = Own::UH;
@@ -350,10 +356,10 @@ __device__ __forceinline__ void k_compute_mfma4(const Raw<KT, EPL>* kr, const do
 // bit pattern), then k_compute.  LOADALL requests every row without waiting for its occupancy
 // (one memory round trip instead of two); what an empty row yields is never used: k_compute
 // stores 0 for it.
-template <typename KT, int UU, int D, int G, int EPL, int LPR, int RPL, bool QLDS, bool LOADALL = false>
+template <typename KT, int UU, int D, int G, int EPL, int LPR, int RPL, bool QLDS, bool LOADALL = false, typename QQ>
 __device__ __forceinline__ void k_tile_masked(const KT* __restrict__ Kb, int row0, int nrows, int zidx0,
                                               const int32_t* __restrict__ posb, const int32_t* __restrict__ wb,
-                                              double alpha, double scale, const Query<G, EPL, QLDS>& qq,
+                                              double alpha, double scale, const QQ& qq,
                                               const double* C, double* lsum, double* et, int Bz,
                                               double* part_w, int lane) {
     const int grp = lane / LPR, seg = lane % LPR;
@@ -750,10 +756,11 @@ __global__ __launch_bounds__(NW * 64, G == 1 ? 4 : 2) void decode_kernel(DecodeA
     extern __shared__ __align__(16) unsigned char smem[];
     double* et = reinterpret_cast<double*>(smem);                 // [G][Bz] exp(logit - C) per slot
     double* part_s = et + (size_t)G * Bz;                         // [NW][PART], pass 1 only
-    float* accw = reinterpret_cast<float*>(part_s);               // [NW][G][D], after pass 2 (same memory)
+    using QE = typename Sh::QE;
+    QE* qlds = reinterpret_cast<QE*>(part_s + NW * PART);         // [G][D] (QLDS only), pass 1 only
+    float* accw = reinterpret_cast<float*>(part_s);               // [NW][G][D], after pass 2 (the memory of the two above)
     double* red64 = reinterpret_cast<double*>(reinterpret_cast<unsigned char*>(part_s) + Sh::STAGE);   // [NW][G]
-    double* qlds = red64 + NW * G;                                // [G][D] (QLDS only)
-    unsigned long long* keyw = reinterpret_cast<unsigned long long*>(qlds + (QLDS ? G * D : 0));   // [NW]
+    unsigned long long* keyw = reinterpret_cast<unsigned long long*>(red64 + NW * G);   // [NW]
     double* dotw = reinterpret_cast<double*>(keyw + NW);          // [NW]
     int* misc = reinterpret_cast<int*>(dotw + NW);                // [4 + NW]
 
@@ -782,10 +789,10 @@ __global__ __launch_bounds__(NW * 64, G == 1 ? 4 : 2) void decode_kernel(DecodeA
     const double alpha = (double)cv.alpha;
 
     if (tid == 0) { misc[0] = -1; misc[2] = 0x7fffffff; }
-    Query<G, EPL, QLDS> qq;
+    Query<G, EPL, QLDS, QE> qq;
     qq.lds = qlds;
     if (QLDS) {
-        for (int i = tid; i < G * D; i += NT) qlds[i] = (double)to_float(qp[i]);
+        for (int i = tid; i < G * D; i += NT) qlds[i] = (QE)to_float(qp[i]);
         __syncthreads();
     } else {
 #pragma unroll
@@ -853,7 +860,7 @@ __global__ __launch_bounds__(NW * 64, G == 1 ? 4 : 2) void decode_kernel(DecodeA
     // Residual rows are dealt to the waves RU wave-wide loads at a time (wave x takes loads RU*x ..
     // RU*x + RU - 1, then RU*NW further on): up to RU*NW*RPL residual slots cost each wave one
     // memory round trip per pass.
-    constexpr int RU = 2;
+    constexpr int RU = Sh::RU;
     // ---- pass 1 (D1): logits of this workgroup's slots, exp(logit - C) into LDS ---------
     // Residual slots (fp32 rows, log-count term) and the incoming token itself come first: their
     // few rows are requested while the wave's first K tile is still on its way, so their round
@@ -1134,9 +1141,10 @@ constexpr int DECODE_NW = 4;
 
 template <typename T, int D, int G, bool SPLIT>
 inline hipError_t launch_decode_dgs(const DecodeArgs& a, hipStream_t stream) {
-    using Sh = DecodeShape<T, D, G, DECODE_NW>;
+    constexpr int NWK = DECODE_NW;
+    using Sh = DecodeShape<T, D, G, NWK>;
     const size_t lds = Sh::lds_bytes(SPLIT ? a.part_rows + a.cv.Br + 1 : a.cv.cap + 1);
-    auto kern = decode_kernel<T, D, G, DECODE_NW, SPLIT>;
+    auto kern = decode_kernel<T, D, G, NWK, SPLIT>;
     // The attribute is per device; bit `dev` records that it has been set there.  Two host threads that
     // meet here for the first time may both set it (harmless: same value), neither reads a torn flag.
     static std::atomic<unsigned long long> attr_done{0ull};
@@ -1149,7 +1157,7 @@ inline hipError_t launch_decode_dgs(const DecodeArgs& a, hipStream_t stream) {
         if (e != hipSuccess) return e;
         attr_done.fetch_or(bit, std::memory_order_release);
     }
-    hipLaunchKernelGGL(kern, dim3(a.n_units * (SPLIT ? a.parts : 1)), dim3(DECODE_NW * 64), lds, stream, a);
+    hipLaunchKernelGGL(kern, dim3(a.n_units * (SPLIT ? a.parts : 1)), dim3(NWK * 64), lds, stream, a);
     if (SPLIT) hipLaunchKernelGGL((decode_combine_kernel<T, D, G, DECODE_NW>), dim3(a.n_units), dim3(DECODE_NW * 64), 0, stream, a);
     return hipGetLastError();
 }

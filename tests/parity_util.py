@@ -1,7 +1,8 @@
 """Shared machinery of the GPU-vs-oracle parity tests.
 
 The GPU side is called through the C ABI (paper_2503_10714_amd.binding); the oracle side
-is oracle/zsmerge_oracle.py.  Both get the same bytes: inputs are generated once (on the
+is oracle/zsmerge_oracle.py (unit by unit) or oracle/zsmerge_oracle_c.c (every unit of a layer
+at once).  Both get the same bytes: inputs are generated once (on the
 device the test says) and copied.
 
 Tolerances (the benchmark definition's): slot indices, counts, positions and eviction
@@ -278,3 +279,132 @@ def compare_all_state(wl, cache, units_by_layer, tol, where, sel=None, stats: Op
                 occ = u.w > 0
                 stats.s_total += int(occ.sum())
                 stats.s_bit_equal += int((g[b, h, :u.B][occ] == u.s[occ].astype(np.float32)).sum())
+
+
+# ---------------------------------------------------------------------------------------
+# every unit of a layer at once, against the plain-C oracle (oracle/zsmerge_oracle_c.c)
+# ---------------------------------------------------------------------------------------
+
+def new_c_oracle_layer(wl: synth.Workload):
+    """The C oracle's state for the S x H units of one layer, unit (b, h) at index b * H + h."""
+    from oracle import zsmerge_oracle_c as oc
+    bp, bc, br = wl.budgets()
+    H = wl.n_kv_heads
+    return oc.BatchCache(wl.n_seqs * H, wl.head_dim, wl.q_per_kv, np.repeat(bp, H), np.repeat(bc, H), br,
+                         lam=lam32(wl.lam), alpha=lam32(wl.alpha), cap=wl.slot_capacity)
+
+
+def c_oracle_prefill_layer(wl: synth.Workload, Q, K, V, lens: Sequence[int]):
+    """C-oracle prefill of every unit of one layer from the tensors the device got.
+    Returns (state, prompt scores [S*H, T_max])."""
+    S, H, T_max, d = K.shape
+    W = Q.shape[3]
+    assert min(lens) >= W, "the batched oracle call takes one window length for all units"
+    cb = new_c_oracle_layer(wl)
+    s = cb.prefill_compress(np64(Q).reshape(S * H, wl.q_per_kv, W, d), np64(K).reshape(S * H, T_max, d),
+                            np64(V).reshape(S * H, T_max, d), np.repeat(np.asarray(lens), H))
+    return cb, s
+
+
+def pack_c_state(cb, S: int, H: int, kv_dtype: torch.dtype) -> Dict[str, torch.Tensor]:
+    """C-oracle state of one layer -> the import arrays (CPU tensors)."""
+    Br, cap, d = cb.B_r, cb.cap, cb.d
+    t = lambda a, *shape: torch.from_numpy(np.ascontiguousarray(a)).reshape(S, H, *shape)
+    return dict(K=t(cb.K[:, Br:], cap - Br, d).to(torch.float32).to(kv_dtype), V=t(cb.V[:, Br:], cap - Br, d).to(torch.float32).to(kv_dtype),
+                Kr=t(cb.K[:, :Br], Br, d).to(torch.float32), Vr=t(cb.V[:, :Br], Br, d).to(torch.float32),
+                s=t(cb.s, cap).to(torch.float32), pos=t(cb.pos, cap).to(torch.int32), w=t(cb.w, cap).to(torch.int32),
+                n_seen=t(cb.n_seen))
+
+
+def compare_layer_with_c_oracle(gpu: Dict[str, torch.Tensor], cb, tol: float, where: str,
+                                stats: Optional[StepStats] = None, prompt_scores: Optional[np.ndarray] = None) -> List[int]:
+    """Exported device state of one layer against the C oracle's, every unit: integers and token rows exact, residual
+    rows and scores within tol.  With `prompt_scores` (right after the prefill) a unit may hold other tokens than the
+    oracle's where the oracle's own scores of the tokens in question lie within TIE_REL of its selection boundary;
+    the indices of such units are returned (the caller brings the two sides together again)."""
+    n, cap, Br, d = cb.n, cb.cap, cb.B_r, cb.d
+    g = {k: v.cpu() for k, v in gpu.items()}
+    gp = g["pos"].reshape(n, cap).numpy().astype(np.int64)
+    gw = g["w"].reshape(n, cap).numpy().astype(np.int64)
+    gs = np64(g["s"]).reshape(n, cap)
+    assert (g["n_seen"].reshape(n).numpy() == cb.n_seen).all(), f"{where}: tokens seen differ"
+    occ = cb.w > 0
+    same = (gw == cb.w).all(axis=1) & ((gp == cb.pos) | ~occ).all(axis=1)
+    flipped = []
+    for u in np.flatnonzero(~same):
+        assert prompt_scores is not None, f"{where} unit {u}: slots differ at {np.flatnonzero((gw[u] != cb.w[u]) | ((gp[u] != cb.pos[u]) & occ[u]))[:8]}"
+        B = Br + int(cb.B_p[u] + cb.B_c[u])
+        dev_set = set(gp[u, Br:B][gw[u, Br:B] > 0].tolist())
+        or_set = set(cb.pos[u, Br:B][occ[u, Br:B]].tolist())
+        T = int(cb.n_seen[u])
+        ctx = [t for t in or_set if t < T - int(cb.B_p[u])]
+        s_b = min(prompt_scores[u, t] for t in ctx)             # lowest score the oracle kept
+        for t in dev_set ^ or_set:
+            rel = abs(prompt_scores[u, t] - s_b) / max(abs(s_b), 1e-300)
+            assert rel < TIE_REL, f"{where} unit {u}: position {t} (s={prompt_scores[u, t]:.9e}) kept by one side only, boundary score {s_b:.9e}, rel gap {rel:.2e}"
+        assert len(dev_set) == len(or_set), f"{where} unit {u}: {len(dev_set)} tokens kept, oracle {len(or_set)}"
+        flipped.append(int(u))
+    ok = same
+    tokocc = occ[:, Br:] & ok[:, None]
+    gK = np64(g["K"]).reshape(n, cap - Br, d)
+    assert (gK[tokocc] == cb.K[:, Br:][tokocc]).all(), f"{where}: token K rows differ"
+    del gK
+    gV = np64(g["V"]).reshape(n, cap - Br, d)
+    assert (gV[tokocc] == cb.V[:, Br:][tokocc]).all(), f"{where}: token V rows differ"
+    del gV
+    if Br:
+        ro = occ[:, :Br] & ok[:, None]
+        dk = np.abs(np64(g["Kr"]).reshape(n, Br, d) - cb.K[:, :Br])[ro]
+        dv = np.abs(np64(g["Vr"]).reshape(n, Br, d) - cb.V[:, :Br])[ro]
+        if dk.size:
+            assert dk.max() <= tol and dv.max() <= tol, f"{where}: residual K/V off by {dk.max():.3e}/{dv.max():.3e}"
+    m = occ & ok[:, None]
+    ds = np.abs(gs - cb.s)[m]
+    if ds.size:
+        assert ds.max() <= tol, f"{where}: scores off by {ds.max():.3e}"
+    if stats is not None:
+        stats.s_total += int(m.sum())
+        stats.s_bit_equal += int((gs[m].astype(np.float32) == cb.s[m].astype(np.float32)).sum())
+    return flipped
+
+
+def decode_step_with_c_oracle(wl: synth.Workload, cache, cbs, step: int, stats: StepStats, gen_device="cpu") -> None:
+    """One decode step of every unit of every layer on the device (one launch) and in the C oracle; outputs within
+    tolerance, decisions equal for every unit (or, inside the near-tie band of the oracle's own scores, brought
+    together again by handing the oracle's state of that layer to the device)."""
+    L, S, H, G, d = wl.n_layers, wl.n_seqs, wl.n_kv_heads, wl.q_per_kv, wl.head_dim
+    n = S * H
+    tol = tol_for(wl.dtype)
+    dev = cache.device
+    qs, ks, vs = [], [], []
+    for l in range(L):
+        q, k, v = synth.decode_inputs(wl, l, step, device=gen_device)
+        qs.append(q); ks.append(k); vs.append(v)
+    q = torch.stack(qs).to(dev); k = torch.stack(ks).to(dev); v = torch.stack(vs).to(dev)
+    out, (ws, ep, ms) = cache.decode_step(q, k, v)
+    out_c = out.cpu().numpy().astype(np.float64).reshape(L, n, G, d)
+    ws_c, ep_c, ms_c = (x.cpu().numpy().reshape(L, n) for x in (ws, ep, ms))
+    qc, kc, vc = np64(q).reshape(L, n, G, d), np64(k).reshape(L, n, d), np64(v).reshape(L, n, d)
+    for l in range(L):
+        o, ws_o, ev_o, mg_o, _, cand, cand_s, cand_pos = cbs[l].decode_step(qc[l], kc[l], vc[l], debug=True)
+        err = float(np.abs(out_c[l] - o).max())
+        stats.max_out_err = max(stats.max_out_err, err)
+        assert err <= tol, f"{wl.name} step {step} layer {l}: attention output off by {err:.3e} (tol {tol})"
+        stats.unit_steps += n
+        stats.evictions += int((ev_o >= 0).sum())
+        stats.merges += int((mg_o >= 0).sum())
+        same = (ep_c[l] == ev_o) & (ws_c[l] == ws_o)
+        assert (ms_c[l][same] == mg_o[same]).all(), f"{wl.name} step {step} layer {l}: merged slots differ"
+        for u in np.flatnonzero(~same):
+            tag = f"{wl.name} step {step} layer {l} unit {u}"
+            ep_d = int(ep_c[l, u])
+            assert ev_o[u] >= 0 and ep_d >= 0, f"{tag}: write_slot/evicted_pos {ws_c[l, u]}/{ep_d} vs {ws_o[u]}/{ev_o[u]}"
+            cp = cand_pos[u, :cand[u, 0]].tolist()
+            assert ep_d in cp, f"{tag}: device evicted position {ep_d}, which is not a candidate"
+            s_dev, s_best = float(cand_s[u, cp.index(ep_d)]), float(cand_s[u, cp.index(int(ev_o[u]))])
+            rel = abs(s_dev - s_best) / max(abs(s_best), 1e-300)
+            assert rel < TIE_REL, f"{tag}: device evicted pos {ep_d} (s={s_dev:.9e}) but the lowest score is pos {ev_o[u]} (s={s_best:.9e}), rel gap {rel:.2e}"
+            stats.near_ties += 1
+        if not same.all():
+            cache.import_layer(l, **pack_c_state(cbs[l], S, H, cache.kv_dtype))
+    stats.steps += 1

@@ -406,6 +406,109 @@ def test_workload2_full_size_sampled_units():
     cache.close()
 
 
+@pytest.mark.parametrize("w,cut", [(2, {}), (4, dict(n_layers=8)), (3, dict(n_layers=1, n_seqs=16))])
+def test_full_size_every_unit(w, cut, capsys):
+    """EVERY unit recomputed by the plain-C oracle from the bytes the device read: the prefill compression of every
+    layer (each slot's position, count, row and score) and 6 decode steps of the all-layer launch (each unit's output
+    and decisions at every step, the whole state at the end).  Workload 2 as the benchmark launches it (1024 units,
+    32 layers per launch); workload 4 at full per-unit size with 8 of its 32 layers (1024 units of four query heads
+    each); workload 3 with one layer of 16 of its 64 ragged sequences (512 units)."""
+    wl = synth.workload(w).sliced(**cut)
+
+    def say(msg):
+        with capsys.disabled():
+            print(msg, flush=True)
+
+    say(f"[case] workload {w} {cut}, all {wl.n_units} units against the C oracle")
+    cache = pu.make_cache(wl, DEV)
+    tol = pu.tol_for(wl.dtype)
+    stats = pu.StepStats()
+    cbs, flips = [], 0
+    for l in range(wl.n_layers):
+        Q, K, V, lens = synth.prompt(wl, l, device=DEV)
+        cache.prefill_compress(l, Q, K, V, lens)
+        torch.cuda.synchronize()
+        cb, s_prompt = pu.c_oracle_prefill_layer(wl, Q, K, V, lens)
+        del Q, K, V
+        flipped = pu.compare_layer_with_c_oracle(cache.export_layer(l), cb, tol, f"workload {w} after prefill, layer {l}",
+                                                 stats, prompt_scores=s_prompt)
+        if flipped:     # a boundary token inside the tie band: go on from the oracle's state
+            flips += len(flipped)
+            cache.import_layer(l, **pu.pack_c_state(cb, wl.n_seqs, wl.n_kv_heads, cache.kv_dtype))
+        cbs.append(cb)
+        if l % 4 == 3 or l == wl.n_layers - 1:
+            say(f"[step] prefill parity ok on every unit of layers 0..{l} (selection ties so far: {flips})")
+    cache.release_workspace()
+    assert flips <= 2
+    n_steps = 6
+    for step in range(n_steps):
+        pu.decode_step_with_c_oracle(wl, cache, cbs, step, stats, gen_device=DEV)
+        say(f"[step] decode step {step}: every unit's output and decisions ok (near ties so far: {stats.near_ties})")
+    for l in range(wl.n_layers):
+        pu.compare_layer_with_c_oracle(cache.export_layer(l), cbs[l], tol, f"workload {w} after {n_steps} steps, layer {l}", stats)
+    say(f"[done] workload {w}, every unit: unit-steps={stats.unit_steps} evictions={stats.evictions} near_ties={stats.near_ties} "
+        f"max|out err|={stats.max_out_err:.2e} scores bit-equal {stats.s_bit_equal}/{stats.s_total}")
+    assert stats.unit_steps == wl.n_units * n_steps and stats.evictions == stats.unit_steps
+    assert stats.near_ties <= 2
+    cache.close()
+
+
+def test_workload2_with_27_residual_slots_every_unit(capsys):
+    """Workload 2 with the residual budget at the recommended share (27 of 2700 slots), all 32 layers compressed by
+    one call: the sequential absorption of the 51 300 dropped tokens of each unit (Alg. 1's residual branch with
+    Eq. 5 and Eq. 6 token by token) must leave, in EVERY one of the 1024 units, the counts the C oracle's walk
+    leaves (exactly) and its merged rows (to tolerance); then 4 decode steps with eviction and merge in every unit."""
+    wl = synth.workload(2).sliced(n_residual=27)
+    L = wl.n_layers
+
+    def say(msg):
+        with capsys.disabled():
+            print(msg, flush=True)
+
+    say(f"[case] workload 2 with 27 residual slots, all {wl.n_units} units against the C oracle")
+    cache = pu.make_cache(wl, DEV)
+    tol = pu.tol_for(wl.dtype)
+    stats = pu.StepStats()
+    Q = K = V = None
+    for l in range(L):
+        q1, k1, v1, lens = synth.prompt(wl, l, device=DEV)
+        if Q is None:
+            Q = torch.empty((L,) + tuple(q1.shape), dtype=q1.dtype, device=DEV)
+            K = torch.empty((L,) + tuple(k1.shape), dtype=k1.dtype, device=DEV)
+            V = torch.empty_like(K)
+        Q[l].copy_(q1); K[l].copy_(k1); V[l].copy_(v1)
+        del q1, k1, v1
+    cache.prefill_compress(0, Q, K, V, lens, layer_end=L)
+    torch.cuda.synchronize()
+    say("[step] device prefill of all layers done")
+    cbs, flips = [], 0
+    for l in range(L):
+        cb, s_prompt = pu.c_oracle_prefill_layer(wl, Q[l], K[l], V[l], lens)
+        flipped = pu.compare_layer_with_c_oracle(cache.export_layer(l), cb, tol, f"27 residual slots after prefill, layer {l}",
+                                                 stats, prompt_scores=s_prompt)
+        if flipped:
+            flips += len(flipped)
+            cache.import_layer(l, **pu.pack_c_state(cb, wl.n_seqs, wl.n_kv_heads, cache.kv_dtype))
+        cbs.append(cb)
+        if l % 4 == 3:
+            say(f"[step] prefill parity ok on every unit of layers 0..{l} (selection ties so far: {flips})")
+    del Q, K, V
+    cache.release_workspace()
+    assert flips <= 2
+    n_steps = 4
+    for step in range(n_steps):
+        pu.decode_step_with_c_oracle(wl, cache, cbs, step, stats, gen_device=DEV)
+        say(f"[step] decode step {step}: every unit's output and decisions ok (near ties so far: {stats.near_ties})")
+    for l in range(L):
+        pu.compare_layer_with_c_oracle(cache.export_layer(l), cbs[l], tol, f"27 residual slots after {n_steps} steps, layer {l}", stats)
+    say(f"[done] workload 2 with 27 residual slots, every unit: unit-steps={stats.unit_steps} evictions={stats.evictions} "
+        f"merges={stats.merges} near_ties={stats.near_ties} max|out err|={stats.max_out_err:.2e} "
+        f"scores bit-equal {stats.s_bit_equal}/{stats.s_total}")
+    assert stats.merges == stats.unit_steps == wl.n_units * n_steps
+    assert stats.near_ties <= 2
+    cache.close()
+
+
 @pytest.mark.parametrize("w,sample", [(3, [(0, 0, 0), (0, 17, 9), (0, 40, 31), (0, 63, 12)]),
                                       (4, [(0, 0, 0), (0, 7, 3), (0, 15, 7)])])
 def test_full_layer_sampled_units(w, sample):

@@ -13,9 +13,24 @@ import numpy as np
 import pytest
 from scipy.special import softmax as sp_softmax
 
+import sys
+
+from oracle import zsmerge_oracle as oracle_py
+from oracle import zsmerge_oracle_c as oracle_c
 from oracle.zsmerge_oracle import UnitCache, prompt_scores, full_attention_row
 
 GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+
+@pytest.fixture(params=["python", "c"], autouse=True)
+def oracle_under_test(request, monkeypatch):
+    """Every pin runs twice: against the NumPy oracle and against the plain-C one (same
+    interface).  The tests name the three entry points as module globals; this swaps them."""
+    impl = oracle_py if request.param == "python" else oracle_c
+    me = sys.modules[__name__]
+    for name in ("UnitCache", "prompt_scores", "full_attention_row"):
+        monkeypatch.setattr(me, name, getattr(impl, name))
+    return request.param
 
 
 def rnd(seed, *shape):
