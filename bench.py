@@ -139,7 +139,7 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-units", type=int, default=32,
                     help="units of layer 0 the CPU oracle is timed on (32 = one full layer of workload 2; with the default steps about 10 s of CPU work)")
-    ap.add_argument("--cpu-steps", type=int, default=2048)
+    ap.add_argument("--cpu-steps", type=int, default=8192)
     ap.add_argument("--layers-per-launch", type=int, default=0,
                     help="0 = all layers of the workload in one launch (the headline configuration); N = one launch "
                          "per N layers, as a model that runs its layers one after the other would call it")
