@@ -264,14 +264,19 @@ class Cache:
         if not torch.is_tensor(seq_lens):
             seq_lens = torch.tensor(list(seq_lens), dtype=torch.int32)
         seq_lens = seq_lens.to(device=self.device, dtype=torch.int32).contiguous()
-        need = zsm_prefill_workspace_bytes(self.handle, layer_end - layer, T_max, W)
+        self.reserve_workspace(layer_end - layer, T_max, W)
+        with torch.cuda.device(self.device):
+            zsm_prefill_compress(self.handle, layer, layer_end, Q, W, K, V, seq_lens, T_max, self._ws)
+
+    def reserve_workspace(self, n_layers: int, T_max: int, W: int) -> None:
+        """Hold a workspace large enough for prefill calls of `n_layers` layers (allocated here, ahead of the call,
+        by whoever does not want the allocation inside a timed region)."""
+        need = zsm_prefill_workspace_bytes(self.handle, n_layers, T_max, W)
         if need == 0:
             raise ZsmError(-2, "zsm_prefill_workspace_bytes")
         if self._ws is None or self._ws.numel() < need:
             self._ws = None
             self._ws = torch.empty(need, dtype=torch.uint8, device=self.device)
-        with torch.cuda.device(self.device):
-            zsm_prefill_compress(self.handle, layer, layer_end, Q, W, K, V, seq_lens, T_max, self._ws)
 
     def release_workspace(self):
         self._ws = None

@@ -72,6 +72,21 @@ inline PrefillWs prefill_ws_layout(const CacheView& cv, int n_units, int T_max, 
         const size_t ev_unit = sizeof(double) * cv.G * w.Wp * (size_t)T_max;          // exponentials of one unit
         w.store_e = !w.fold && ev_unit <= PF_EV_MAX && units > 0;
         w.ev_units = w.store_e ? (int)(PF_EV_MAX / ev_unit < units ? PF_EV_MAX / ev_unit : units) : 0;
+        if (w.store_e && (size_t)w.ev_units < units) {
+            // Several batches: a batch of u units is scored by u * (wgs / (u * rz)) * rz workgroups, one round of
+            // at most `wgs` resident ones.  Take the batch size (at least half the largest that fits) that wastes the
+            // fewest workgroup slots, the ragged last batch counted.
+            const int wgs1 = PF_SCORE_WGS / 4 * 3;
+            double best = -1.0;
+            int best_u = w.ev_units;
+            for (int u = w.ev_units; u >= (w.ev_units + 1) / 2; --u) {
+                const int per_unit = w.rz * (wgs1 / (u * w.rz) > 0 ? wgs1 / (u * w.rz) : 1);   // workgroups per unit
+                const int nb = (int)(units / u), rem = (int)(units % u);
+                const double f = ((double)nb * u + rem) * per_unit / ((double)(nb + (rem ? 1 : 0)) * wgs1);
+                if (f > best + 1e-9) { best = f; best_u = u; }
+            }
+            w.ev_units = best_u;
+        }
         const size_t su = w.store_e ? (size_t)w.ev_units : units;                     // units per scoring launch
         // one round of workgroups: 4 per compute unit, 3 for the sweep that also stores its exponentials (more registers)
         const int wgs = w.store_e ? PF_SCORE_WGS / 4 * 3 : PF_SCORE_WGS;
