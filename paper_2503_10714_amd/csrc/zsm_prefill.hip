@@ -857,15 +857,28 @@ struct BlockCols {
     double xnorm;       // norm of token l%16 (valid in the lane whose row group l/16 is that token's: l/16 = (l%16) % 4)
 };
 
+// bytes of LDS one wave (one unit) of pf_residual_blocks needs
+template <typename T, int D>
+inline size_t pf_residual_blocks_lds(int Br) {
+    const size_t n = sizeof(float) * 2 * (size_t)Br * (D + 4) + sizeof(double) * D + sizeof(int) * PF_RMAX + 2 * PF_GB * D * sizeof(T);
+    return (n + 15) & ~(size_t)15;
+}
+
+// One wave per unit, `blockDim.x / 64` units per workgroup.  The waves of a workgroup never meet (no barrier, a region
+// of LDS each): they are put in one workgroup because its waves are dealt to the four SIMDs of a compute unit one
+// each, while single-wave workgroups were seen to share SIMDs from the third per compute unit on (the walk of 1024
+// units then took 55 ms instead of the 37 ms of 512 units: two waves on one SIMD take turns on its matrix core).
 template <typename T, int D, int NCB>
-__global__ __launch_bounds__(64, 1) void pf_residual_blocks(PrefillArgs a, PrefillWs ws) {
+__global__ __launch_bounds__(256, 1) void pf_residual_blocks(PrefillArgs a, PrefillWs ws, int lds_per_wave) {
     const CacheView& cv = a.cv;
-    const int lu = blockIdx.x;
+    const int wave_in_wg = __builtin_amdgcn_readfirstlane((int)threadIdx.x >> 6);
+    const int lu = blockIdx.x * ((int)blockDim.x >> 6) + wave_in_wg;
+    if (lu >= a.n_units) return;
     const int ug = a.unit0 + lu;
     const int b = seq_of(cv, lu);
     const int Tb = seq_len_of(a, b);
     const int Br = cv.Br;
-    const int lane = threadIdx.x;
+    const int lane = threadIdx.x & 63;
     constexpr int RS = D + 4;   // padded row stride (floats): lanes reading 16 bytes of different rows hit different banks
     constexpr int CPL = D / 64; // channels per lane in the merge: CPL * lane .. CPL * lane + CPL - 1
     constexpr int EPL = 16 / sizeof(T);
@@ -873,7 +886,7 @@ __global__ __launch_bounds__(64, 1) void pf_residual_blocks(PrefillArgs a, Prefi
     constexpr int NLD = SPK / EPL;            // 16-byte pieces per lane, row and array
     static_assert(SPK % EPL == 0 && NLD >= 1, "");
     extern __shared__ __align__(16) unsigned char smem[];
-    float* Krs = reinterpret_cast<float*>(smem);            // [Br][RS]
+    float* Krs = reinterpret_cast<float*>(smem + (size_t)wave_in_wg * lds_per_wave);   // [Br][RS]
     float* Vrs = Krs + (size_t)Br * RS;                      // [Br][RS]
     double* ktok = reinterpret_cast<double*>(Vrs + (size_t)Br * RS);   // [D]
     int* wcs = reinterpret_cast<int*>(ktok + D);             // [PF_RMAX] fusion counts
@@ -1214,15 +1227,15 @@ hipError_t launch_prefill_td(const PrefillArgs& a, hipStream_t st) {
         hipLaunchKernelGGL((pf_residual_partial<T, D>), dim3(ws.nchunks, a.n_units), dim3(256), 0, st, a, ws);
         hipLaunchKernelGGL((pf_residual_final<D>), dim3(a.n_units), dim3(256), 0, st, a, ws);
     } else if (cv.Br > 1) {
-        const size_t lds = sizeof(float) * 2 * (size_t)cv.Br * (D + 4) + sizeof(double) * D + sizeof(int) * PF_RMAX +
-                           2 * PF_GB * D * sizeof(T);
+        const size_t lds = pf_residual_blocks_lds<T, D>(cv.Br);
+        const int wpg = 4 * lds <= 160 * 1024 ? 4 : (2 * lds <= 160 * 1024 ? 2 : 1);   // units per workgroup
         // column blocks of 16 residual keys
-        void (*kern)(PrefillArgs, PrefillWs) = cv.Br > 48 ? pf_residual_blocks<T, D, 4>
-                                               : (cv.Br > 32 ? pf_residual_blocks<T, D, 3>
-                                                  : (cv.Br > 16 ? pf_residual_blocks<T, D, 2> : pf_residual_blocks<T, D, 1>));
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, 96 * 1024);
+        void (*kern)(PrefillArgs, PrefillWs, int) = cv.Br > 48 ? pf_residual_blocks<T, D, 4>
+                                                    : (cv.Br > 32 ? pf_residual_blocks<T, D, 3>
+                                                       : (cv.Br > 16 ? pf_residual_blocks<T, D, 2> : pf_residual_blocks<T, D, 1>));
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
         if (e != hipSuccess) return e;
-        hipLaunchKernelGGL(kern, dim3(a.n_units), dim3(64), lds, st, a, ws);
+        hipLaunchKernelGGL(kern, dim3((a.n_units + wpg - 1) / wpg), dim3(64 * wpg), wpg * lds, st, a, ws, (int)lds);
     }
     return hipGetLastError();
 }

@@ -36,6 +36,15 @@ DECODE_CASES = {
                                     prompt_len=300, budget=101, decode_steps=40, outliers=True),
     "gqa2_d64_f16": lambda: small("gqa2_d64_f16", dtype="f16", q_per_kv=2),
     "gqa8_f32_d128": lambda: small("gqa8_f32_d128", q_per_kv=8, head_dim=128, budget=33, prompt_len=120),
+    # many residual slots: more residual rows than the waves request ahead in one go (two wave-wide loads each), and
+    # more than one batch of rows per wave in the Eq. 5 dot products; with 1, 4 and 8 query heads (the row handling
+    # of pass 2 differs between them)
+    "residual_40_f16": lambda: small("residual_40_f16", n_residual=40, dtype="f16", head_dim=128, prompt_len=400,
+                                     budget=120, decode_steps=48, outliers=True),
+    "residual_20_f32_gqa4": lambda: small("residual_20_f32_gqa4", n_residual=20, q_per_kv=4, head_dim=128, prompt_len=300,
+                                          budget=90, decode_steps=40, outliers=True),
+    "residual_12_bf16_gqa8": lambda: small("residual_12_bf16_gqa8", n_residual=12, dtype="bf16", q_per_kv=8, head_dim=128,
+                                           prompt_len=300, budget=80, decode_steps=40, outliers=True),
     "fills_up": lambda: small("fills_up", prompt_len=20, budget=48, decode_steps=60, window=8),       # T < B: free slots first
     "empty_start": lambda: small("empty_start", prompt_len=0, budget=24, decode_steps=50, n_residual=2, window=4),
     "ragged_multi_layer": lambda: small("ragged_multi_layer", n_layers=2, n_seqs=3, dtype="f16", head_dim=128,
@@ -80,7 +89,8 @@ def test_decode_from_oracle_state(case):
 
 # (case, workgroups per unit): the split step must give the oracle's decisions and outputs whatever the cut
 SPLIT_CASES = [("cfg1", 4), ("cfg1", 13), ("three_residual_f16", 2), ("alpha_half_bf16_gqa4", 3), ("gqa8_f32_d128", 2),
-               ("fills_up", 2), ("gqa4_f16_many_tiles", 2), ("gqa8_bf16_d128", 3), ("empty_start", 3), ("ragged_multi_layer", 5), ("evict_only", 3), ("cfg0", 3)]
+               ("fills_up", 2), ("gqa4_f16_many_tiles", 2), ("gqa8_bf16_d128", 3), ("empty_start", 3), ("ragged_multi_layer", 5), ("evict_only", 3), ("cfg0", 3),
+               ("residual_40_f16", 3), ("residual_20_f32_gqa4", 2)]
 
 
 @pytest.mark.parametrize("case,parts", SPLIT_CASES)
