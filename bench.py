@@ -154,6 +154,8 @@ def main():
                          "the full-history initialisation)")
     ap.add_argument("--n-residual", type=int, default=None,
                     help="override the workload's number of residual slots B_r (B stays the same, B_c shrinks)")
+    ap.add_argument("--budget", type=int, default=None,
+                    help="override the workload's budget B (slots per unit at the full prompt length)")
     ap.add_argument("--q-per-kv", type=int, default=None,
                     help="override the workload's number of query heads per KV head G (same KV heads, G times the queries)")
     ap.add_argument("--pmc-calibration", action="store_true",
@@ -189,6 +191,8 @@ def main():
         wl = wl.sliced(window=args.window)
     if args.q_per_kv is not None:
         wl = wl.sliced(q_per_kv=args.q_per_kv)
+    if args.budget is not None:
+        wl = wl.sliced(budget=args.budget)
     if wl.ragged is not None and not args.skip_prefill:
         print("bench.py: a ragged workload is a parity-test case; its decode step can be timed with --skip-prefill "
               "(slots filled by import, inputs of all sequences drawn at the same positions)", file=sys.stderr)

@@ -220,8 +220,13 @@ int choose_parts(const zsm_cache_t* cache, int n_units, int* part_rows) {
     parts = parts > 1 ? parts : 1;
     auto rows_of = [&](int p) { return (ntiles + p - 1) / p * R; };
     auto lds_need = [&](int p) { return p > 1 ? lds_of(rows_of(p) + v.Br + 1) : lds_of(v.cap + 1); };
-    if (cache->parts == 0)                                       // a capacity one workgroup's LDS cannot hold: more parts
+    if (cache->parts == 0 && lds_need(parts) > 160 * 1024) {
+        // a capacity one workgroup's LDS cannot hold: more parts, and then as many as let the compute unit hold the
+        // workgroups its registers allow (4 of a single query head, 3 of four heads, 2 otherwise)
         while (lds_need(parts) > 160 * 1024 && parts < hi) ++parts;
+        const size_t want = v.G == 1 ? 4 : (v.G == 4 ? 3 : 2);
+        while (160 * 1024 / lds_need(parts) < want && parts < hi && parts < ntiles / (2 * DECODE_NW)) ++parts;
+    }
     if (lds_need(parts) > 160 * 1024) return ZSM_E_SHAPE;
     *part_rows = parts > 1 ? rows_of(parts) : 0;
     return parts;

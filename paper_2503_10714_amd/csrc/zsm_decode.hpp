@@ -718,7 +718,7 @@ __device__ __forceinline__ void decode_finish(const DecodeArgs& a, const CacheVi
 //   boundary is what makes one workgroup's scratch visible to another: fences inside one
 //   kernel cost more here than the whole sweep of a small launch).
 template <typename T, int D, int G, int NW, bool SPLIT>
-__global__ __launch_bounds__(NW * 64, G == 1 ? 4 : 2) void decode_kernel(DecodeArgs a) {
+__global__ __launch_bounds__(NW * 64, G == 1 ? 4 : (NW == 12 ? 3 : 2)) void decode_kernel(DecodeArgs a) {
     using Sh = DecodeShape<T, D, G, NW>;
     constexpr int EPL = Sh::EPL, LPR = Sh::LPR, RPL = Sh::RPL, R = Sh::R, PART = Sh::PART, NT = Sh::NT, UT = Sh::UT;
     constexpr bool QLDS = Sh::QLDS;
@@ -1138,10 +1138,51 @@ __global__ __launch_bounds__(NW * 64) void decode_combine_kernel(DecodeArgs a) {
 
 // Host side: pick the instantiation for (D, G) and launch.
 constexpr int DECODE_NW = 4;
+constexpr size_t DECODE_LDS_MAX = 160 * 1024;   // LDS of one compute unit
+
+// Waves per workgroup.  Four, unless the per-slot values of one workgroup (G * (slots + 1) * 8 bytes of LDS) leave
+// room for fewer workgroups per compute unit than the registers would allow waves: then a workgroup of 8, 12 or 16
+// waves keeps the compute unit's SIMDs supplied with loads in flight (measured at four query heads and B = 2700,
+// where only one workgroup fits: 0.336 ms with 4 waves, 0.285 with 8, 0.281 with 12; a single query head at
+// B = 12000: 1.25 ms with 4 waves, 1.08 with 16).  Where two or more workgroups of four waves fit they stay: at
+// B = 6000 two of them stream as fast as sixteen waves do, and with three resident, as at four query heads and
+// B = 1024, larger workgroups lose to the serial stretches of a unit.
+template <typename T, int D, int G, bool SPLIT, int NWK>
+inline hipError_t launch_decode_nw(const DecodeArgs& a, hipStream_t stream);
+
+// waves a compute unit holds of this kernel by its registers (the launch bound's waves per SIMD, times four)
+template <typename T, int D, int G>
+constexpr int decode_cu_waves() { return G == 1 ? 16 : ((G == 4 && DecodeShape<T, D, G, DECODE_NW>::MFMA4) ? 12 : 8); }
+
+template <typename T, int D, int G, int NWK>
+inline int decode_resident_waves(int nz) {
+    const size_t lds = DecodeShape<T, D, G, NWK>::lds_bytes(nz);
+    if (lds > DECODE_LDS_MAX) return 0;
+    const int by_lds = (int)(DECODE_LDS_MAX / lds) * NWK, by_regs = decode_cu_waves<T, D, G>() / NWK * NWK;
+    return by_lds < by_regs ? by_lds : by_regs;
+}
 
 template <typename T, int D, int G, bool SPLIT>
 inline hipError_t launch_decode_dgs(const DecodeArgs& a, hipStream_t stream) {
-    constexpr int NWK = DECODE_NW;
+    if constexpr (!SPLIT) {
+        const int nz = a.cv.cap + 1;
+        const int w4 = decode_resident_waves<T, D, G, 4>(nz), w8 = decode_resident_waves<T, D, G, 8>(nz);
+        constexpr int NWX = G == 1 ? 16 : 12;   // the largest workgroup of this kernel, where it has one
+        constexpr bool HAS_X = decode_cu_waves<T, D, G>() >= NWX;
+        int wx = 0;
+        if constexpr (HAS_X) wx = decode_resident_waves<T, D, G, NWX>(nz);
+        if (w4 <= 4 && (w8 > w4 || wx > w4)) {   // two resident workgroups of four waves already stream at the full rate
+            if constexpr (HAS_X) {
+                if (wx > w8) return launch_decode_nw<T, D, G, SPLIT, NWX>(a, stream);
+            }
+            return launch_decode_nw<T, D, G, SPLIT, 8>(a, stream);
+        }
+    }
+    return launch_decode_nw<T, D, G, SPLIT, DECODE_NW>(a, stream);
+}
+
+template <typename T, int D, int G, bool SPLIT, int NWK>
+inline hipError_t launch_decode_nw(const DecodeArgs& a, hipStream_t stream) {
     using Sh = DecodeShape<T, D, G, NWK>;
     const size_t lds = Sh::lds_bytes(SPLIT ? a.part_rows + a.cv.Br + 1 : a.cv.cap + 1);
     auto kern = decode_kernel<T, D, G, NWK, SPLIT>;

@@ -45,6 +45,17 @@ DECODE_CASES = {
                                           budget=90, decode_steps=40, outliers=True),
     "residual_12_bf16_gqa8": lambda: small("residual_12_bf16_gqa8", n_residual=12, dtype="bf16", q_per_kv=8, head_dim=128,
                                            prompt_len=300, budget=80, decode_steps=40, outliers=True),
+    # budgets whose per-slot values fill most of a compute unit's LDS: the step then runs with workgroups of 8, 12 or
+    # 16 waves instead of 4 (one resident workgroup has to keep all SIMDs busy)
+    "wide_wg12_gqa4_f16": lambda: small("wide_wg12_gqa4_f16", dtype="f16", q_per_kv=4, head_dim=128, n_kv_heads=2, n_residual=5,
+                                        prompt_len=3000, budget=2700, decode_steps=10, outliers=True),
+    "wide_wg8_g1_b16000": lambda: small("wide_wg8_g1_b16000", dtype="f16", head_dim=128, n_kv_heads=1, prompt_len=16200, budget=16000,
+                                        decode_steps=6, outliers=True),
+    "wide_wg16_g1_b12000": lambda: small("wide_wg16_g1_b12000", dtype="bf16", head_dim=128, n_kv_heads=1, n_residual=3,
+                                         prompt_len=12300, budget=12000, decode_steps=6, outliers=True),
+    "wide_wg8_gqa2_f32_d64": lambda: small("wide_wg8_gqa2_f32_d64", q_per_kv=2, prompt_len=6200, budget=6000, decode_steps=6),
+    "wide_wg8_gqa8_bf16": lambda: small("wide_wg8_gqa8_bf16", dtype="bf16", q_per_kv=8, head_dim=128, n_kv_heads=1,
+                                        prompt_len=1800, budget=1500, decode_steps=8, outliers=True),
     "fills_up": lambda: small("fills_up", prompt_len=20, budget=48, decode_steps=60, window=8),       # T < B: free slots first
     "empty_start": lambda: small("empty_start", prompt_len=0, budget=24, decode_steps=50, n_residual=2, window=4),
     "ragged_multi_layer": lambda: small("ragged_multi_layer", n_layers=2, n_seqs=3, dtype="f16", head_dim=128,
