@@ -30,6 +30,12 @@
  * and to the lowest index for Eq. 5; grouped queries have their own softmax each and pool
  * their probabilities by the plain mean; an unused residual slot takes no part in the softmax.
  *
+ * The sets of Alg. 1 are not kept as lists here (the Python oracle does that, literally): a token
+ * enters the proximity set when it arrives and positions only grow, so the proximity set is the
+ * B_p most recent tokens and the context set the other retained ones; the state is the per-slot
+ * arrays alone and the sets are read off the positions at every step.  That the two statements
+ * agree step by step is itself tested (tests/test_oracle_c.py).
+ *
  * Parity pins: tests/test_oracle_pins.py runs every pin against this file as well as against
  * the Python oracle, and tests/test_oracle_c.py compares the two on random workloads.
  */
@@ -51,10 +57,6 @@ typedef struct {
     double *s;           /* [n][cap]      scores, fp32 values */
     int64_t *n_seen;     /* [n]           T: tokens seen so far */
     const int32_t *B_p, *B_c; /* [n] */
-    /* the sets of Alg. 1 as lists of slot numbers */
-    int32_t *kp;         /* [n][cap]  proximity set, a FIFO: oldest at index head, ring of length cap */
-    int32_t *kc;         /* [n][cap]  context set */
-    int32_t *sets;       /* [n][4]    kp head, kp length, kc length, residual slots in use */
 } zso_batch;
 
 static double store32(double x) { return (double)(float)x; }
@@ -72,17 +74,16 @@ static int absorb(const zso_batch *b, int u, const double *k, const double *v, i
     double *K = b->K + (size_t)u * b->cap * d, *V = b->V + (size_t)u * b->cap * d;
     int64_t *w = b->w + (size_t)u * b->cap, *ps = b->pos + (size_t)u * b->cap;
     double *sc = b->s + (size_t)u * b->cap;
-    int32_t *sets = b->sets + (size_t)u * 4;
     if (b->B_r == 0) return -1;
-    if (sets[3] + 1 <= b->B_r) {
-        const int r = sets[3]++;
+    for (int r = 0; r < b->B_r; ++r) {      /* the lowest unused residual slot, if there is one */
+        if (w[r] != 0) continue;
         for (int i = 0; i < d; ++i) { K[(size_t)r * d + i] = store32(k[i]); V[(size_t)r * d + i] = store32(v[i]); }
         w[r] = 1; ps[r] = pos; sc[r] = s;
         return r;
     }
     int best = 0;
     double bd = dot(K, k, d);
-    for (int r = 1; r < sets[3]; ++r) {
+    for (int r = 1; r < b->B_r; ++r) {
         const double p = dot(K + (size_t)r * d, k, d);
         if (p > bd) { bd = p; best = r; }
     }
@@ -93,6 +94,13 @@ static int absorb(const zso_batch *b, int u, const double *k, const double *v, i
     }
     w[best] += 1;
     return best;
+}
+
+typedef struct { int64_t pos; int32_t slot; } placed;
+
+static int by_position(const void *x, const void *y) {
+    const placed *a = (const placed *)x, *b = (const placed *)y;
+    return a->pos < b->pos ? -1 : (a->pos > b->pos ? 1 : 0);
 }
 
 /* One pass of Alg. 1's loop body for unit u.  a_dbg [G][cap + 1] (probabilities by slot, the
@@ -107,7 +115,6 @@ static int decode_unit(const zso_batch *b, int u, const double *q, const double 
     double *K = b->K + (size_t)u * cap * d, *V = b->V + (size_t)u * cap * d;
     int64_t *w = b->w + (size_t)u * cap, *ps = b->pos + (size_t)u * cap;
     double *sc = b->s + (size_t)u * cap;
-    int32_t *kp = b->kp + (size_t)u * cap, *kc = b->kc + (size_t)u * cap, *sets = b->sets + (size_t)u * 4;
     const int64_t T = b->n_seen[u];
     if (B > cap || B_p < 1) return -1;
 
@@ -150,43 +157,44 @@ static int decode_unit(const zso_batch *b, int u, const double *q, const double 
     const double s_new = store32(abar[B] / (double)G);
     free(z); free(abar);
 
-    /* Alg. 1: the token joins the proximity set, its oldest member is demoted to the context
-     * set, and the context set, if it overflows, loses its member of lowest (score, position) */
+    /* Alg. 1: the token joins the proximity set; with it the set holds the new token and the
+     * B_p - 1 most recent retained ones, every other retained token belongs to the context set,
+     * and the context set, if it now has more than B_c members, loses the one of lowest
+     * (score, position). */
     int freed = -1, ev = -1, merged = -1;
     if (cand_dbg) cand_dbg[0] = 0;
-    int kp_len = sets[1] + 1;             /* the new token counts, its slot is not known yet */
-    if (kp_len > B_p) {
-        const int old = kp[sets[0]];
-        sets[0] = (sets[0] + 1) % cap;
-        kp_len -= 1;
-        kc[sets[2]++] = old;
-        if (sets[2] > B_c) {
-            int ci = 0;
-            for (int x = 1; x < sets[2]; ++x) {
-                const int j = kc[x], c = kc[ci];
-                if (sc[j] < sc[c] || (sc[j] == sc[c] && ps[j] < ps[c])) ci = x;
-            }
-            if (cand_dbg) {
-                cand_dbg[0] = sets[2];
-                for (int x = 0; x < sets[2]; ++x) {
-                    cand_dbg[1 + x] = kc[x];
-                    if (cand_s_dbg) cand_s_dbg[x] = sc[kc[x]];
-                    if (cand_pos_dbg) cand_pos_dbg[x] = ps[kc[x]];
-                }
-            }
-            const int c_hat = kc[ci];
-            for (int x = ci; x + 1 < sets[2]; ++x) kc[x] = kc[x + 1];
-            sets[2] -= 1;
-            ev = (int)ps[c_hat];
-            double *kcopy = (double *)malloc(sizeof(double) * 2 * (size_t)d);
-            if (!kcopy) return -2;
-            memcpy(kcopy, K + (size_t)c_hat * d, sizeof(double) * d);
-            memcpy(kcopy + d, V + (size_t)c_hat * d, sizeof(double) * d);
-            merged = absorb(b, u, kcopy, kcopy + d, ps[c_hat], sc[c_hat]);
-            free(kcopy);
-            freed = c_hat;
+    int n_tok = 0;
+    placed *tok = (placed *)malloc(sizeof(placed) * (size_t)(B > 0 ? B : 1));
+    if (!tok) return -2;
+    for (int j = b->B_r; j < B; ++j)
+        if (w[j] > 0) { tok[n_tok].pos = ps[j]; tok[n_tok].slot = j; ++n_tok; }
+    const int n_ctx = n_tok - (B_p - 1);          /* members of the context set after the demotion */
+    if (n_ctx > B_c) {
+        qsort(tok, (size_t)n_tok, sizeof(placed), by_position);   /* oldest first: the context set is tok[0 .. n_ctx) */
+        int ci = 0;
+        for (int x = 1; x < n_ctx; ++x) {
+            const int j = tok[x].slot, c = tok[ci].slot;
+            if (sc[j] < sc[c] || (sc[j] == sc[c] && ps[j] < ps[c])) ci = x;
         }
+        if (cand_dbg) {
+            cand_dbg[0] = n_ctx;
+            for (int x = 0; x < n_ctx; ++x) {
+                cand_dbg[1 + x] = tok[x].slot;
+                if (cand_s_dbg) cand_s_dbg[x] = sc[tok[x].slot];
+                if (cand_pos_dbg) cand_pos_dbg[x] = ps[tok[x].slot];
+            }
+        }
+        const int c_hat = tok[ci].slot;
+        ev = (int)ps[c_hat];
+        double *kcopy = (double *)malloc(sizeof(double) * 2 * (size_t)d);
+        if (!kcopy) { free(tok); return -2; }
+        memcpy(kcopy, K + (size_t)c_hat * d, sizeof(double) * d);
+        memcpy(kcopy + d, V + (size_t)c_hat * d, sizeof(double) * d);
+        merged = absorb(b, u, kcopy, kcopy + d, ps[c_hat], sc[c_hat]);
+        free(kcopy);
+        freed = c_hat;
     }
+    free(tok);
     if (freed < 0) {
         for (int j = b->B_r; j < B; ++j)
             if (w[j] == 0) { freed = j; break; }
@@ -195,8 +203,6 @@ static int decode_unit(const zso_batch *b, int u, const double *q, const double 
     memcpy(K + (size_t)freed * d, k_new, sizeof(double) * d);
     memcpy(V + (size_t)freed * d, v_new, sizeof(double) * d);
     ps[freed] = T; w[freed] = 1; sc[freed] = s_new;
-    kp[(sets[0] + kp_len - 1) % cap] = freed;
-    sets[1] = kp_len;
     b->n_seen[u] = T + 1;
     *write_slot = freed; *evicted_pos = ev; *merged_slot = merged;
     return 0;
@@ -222,38 +228,6 @@ int zso_decode_step(const zso_batch *b, const double *q, const double *k_new, co
 #pragma omp critical
             err = e;
         }
-    }
-    return err;
-}
-
-/* Rebuild the sets of Alg. 1 from a state given slot by slot: the proximity set is a FIFO of
- * arrivals and positions only grow, so it holds the B_p most recent token slots; the context set
- * holds the other occupied token slots; residual slots are opened in index order. */
-int zso_rebuild_sets(const zso_batch *b) {
-    int err = 0;
-#pragma omp parallel for schedule(dynamic, 1)
-    for (int u = 0; u < b->n_units; ++u) {
-        const int cap = b->cap, B_p = b->B_p[u], B = b->B_r + B_p + b->B_c[u];
-        const int64_t *w = b->w + (size_t)u * cap, *ps = b->pos + (size_t)u * cap;
-        int32_t *kp = b->kp + (size_t)u * cap, *kc = b->kc + (size_t)u * cap, *sets = b->sets + (size_t)u * 4;
-        if (B > cap) { err = -1; continue; }
-        int n = 0;
-        int32_t *tok = kc;     /* occupied token slots, then sorted by position (insertion sort: n is small or nearly sorted) */
-        for (int j = b->B_r; j < B; ++j)
-            if (w[j] > 0) tok[n++] = j;
-        for (int x = 1; x < n; ++x) {
-            const int j = tok[x];
-            int y = x - 1;
-            while (y >= 0 && ps[tok[y]] > ps[j]) { tok[y + 1] = tok[y]; --y; }
-            tok[y + 1] = j;
-        }
-        const int n_p = n < B_p ? n : B_p;
-        for (int x = 0; x < n_p; ++x) kp[x] = tok[n - n_p + x];
-        sets[0] = 0; sets[1] = n_p; sets[2] = n - n_p;
-        int nr = 0;
-        for (int r = 0; r < b->B_r; ++r)
-            if (w[r] > 0) ++nr;
-        sets[3] = nr;
     }
     return err;
 }
@@ -311,8 +285,9 @@ static int prefill_unit(const zso_batch *b, int u, int W, int T, const double *Q
                         double *s) {
     const int d = b->d, cap = b->cap;
     const int B_p = b->B_p[u], B_c = b->B_c[u], n_tok = B_p + B_c;
-    int32_t *kp = b->kp + (size_t)u * cap, *kc = b->kc + (size_t)u * cap, *sets = b->sets + (size_t)u * 4;
-    if (b->B_r + n_tok > cap || W > T || b->n_seen[u] != 0 || sets[1] || sets[2] || sets[3]) return -1;
+    if (b->B_r + n_tok > cap || W > T || b->n_seen[u] != 0) return -1;
+    for (int j = 0; j < cap; ++j)
+        if (b->w[(size_t)u * cap + j] != 0) return -1;          /* the cache must be empty */
     int e = zso_prompt_scores(b->G, W, T, d, Qw, K, b->lam, b->scale, s);
     if (e) return e;
     char *kept = (char *)calloc((size_t)T, 1);
@@ -337,10 +312,9 @@ static int prefill_unit(const zso_batch *b, int u, int W, int T, const double *Q
     /* context tokens by position, then the proximity tokens, from the first token slot on */
     int j = b->B_r, c = 0;
     for (int t = 0; t < T - n_prox; ++t)
-        if (kept[t]) { put_token(b, u, j, K + (size_t)t * d, V + (size_t)t * d, t, s[t]); kc[c++] = j++; }
+        if (kept[t]) { put_token(b, u, j++, K + (size_t)t * d, V + (size_t)t * d, t, s[t]); ++c; }
     if (c != n_ctx) { free(kept); return -4; }
-    for (int t = T - n_prox; t < T; ++t) { put_token(b, u, j, K + (size_t)t * d, V + (size_t)t * d, t, s[t]); kp[t - (T - n_prox)] = j++; }
-    sets[0] = 0; sets[1] = n_prox; sets[2] = n_ctx;
+    for (int t = T - n_prox; t < T; ++t) put_token(b, u, j++, K + (size_t)t * d, V + (size_t)t * d, t, s[t]);
     for (int t = 0; t < T; ++t)
         if (!kept[t]) absorb(b, u, K + (size_t)t * d, V + (size_t)t * d, t, s[t]);
     b->n_seen[u] = T;

@@ -29,7 +29,7 @@ class _Batch(C.Structure):
     _fields_ = [("n_units", C.c_int32), ("d", C.c_int32), ("G", C.c_int32), ("B_r", C.c_int32), ("cap", C.c_int32),
                 ("pad_", C.c_int32), ("lam", C.c_double), ("alpha", C.c_double), ("scale", C.c_double),
                 ("K", _dp), ("V", _dp), ("pos", _lp), ("w", _lp), ("s", _dp), ("n_seen", _lp),
-                ("B_p", _ip), ("B_c", _ip), ("kp", _ip), ("kc", _ip), ("sets", _ip)]
+                ("B_p", _ip), ("B_c", _ip)]
 
 
 def build() -> str:
@@ -50,11 +50,10 @@ def lib():
             build()
         L = C.CDLL(LIB)
         L.zso_decode_step.argtypes = [C.POINTER(_Batch), _dp, _dp, _dp, _dp, _ip, _ip, _ip, _dp, _ip, _dp, _lp]
-        L.zso_rebuild_sets.argtypes = [C.POINTER(_Batch)]
         L.zso_prompt_scores.argtypes = [C.c_int, C.c_int, C.c_int, C.c_int, _dp, _dp, C.c_double, C.c_double, _dp]
         L.zso_prefill_compress.argtypes = [C.POINTER(_Batch), C.c_int, C.c_int, _ip, _dp, _dp, _dp, _dp]
         L.zso_full_attention_row.argtypes = [C.c_int, C.c_int, _dp, _dp, _dp, C.c_double, _dp, _dp]
-        for f in (L.zso_decode_step, L.zso_rebuild_sets, L.zso_prompt_scores, L.zso_prefill_compress,
+        for f in (L.zso_decode_step, L.zso_prompt_scores, L.zso_prefill_compress,
                   L.zso_full_attention_row, L.zso_threads):
             f.restype = C.c_int
         _lib = L
@@ -96,13 +95,9 @@ class BatchCache:
         self.w = np.zeros((n, cp), dtype=np.int64)
         self.s = np.zeros((n, cp))
         self.n_seen = np.zeros(n, dtype=np.int64)
-        self.kp = np.zeros((n, cp), dtype=np.int32)
-        self.kc = np.zeros((n, cp), dtype=np.int32)
-        self.sets = np.zeros((n, 4), dtype=np.int32)
         self._b = _Batch(n, d, G, B_r, cp, 0, self.lam, self.alpha, self.scale, _d(self.K), _d(self.V),
                          self.pos.ctypes.data_as(_lp), self.w.ctypes.data_as(_lp), _d(self.s),
-                         self.n_seen.ctypes.data_as(_lp), self.B_p.ctypes.data_as(_ip), self.B_c.ctypes.data_as(_ip),
-                         self.kp.ctypes.data_as(_ip), self.kc.ctypes.data_as(_ip), self.sets.ctypes.data_as(_ip))
+                         self.n_seen.ctypes.data_as(_lp), self.B_p.ctypes.data_as(_ip), self.B_c.ctypes.data_as(_ip))
 
     def decode_step(self, q, k_new, v_new, debug: bool = False):
         """q [n, G, d], k_new, v_new [n, d] -> out [n, G, d], write_slot, evicted_pos, merged_slot [n]
@@ -123,11 +118,6 @@ class BatchCache:
         if e:
             raise RuntimeError(f"zso_decode_step: error {e}")
         return (out, ws, ev, mg, a, cand, cs, cp) if debug else (out, ws, ev, mg)
-
-    def rebuild_sets(self):
-        e = lib().zso_rebuild_sets(C.byref(self._b))
-        if e:
-            raise RuntimeError(f"zso_rebuild_sets: error {e}")
 
     def prefill_compress(self, Qw, K, V, T: Optional[Sequence[int]] = None):
         """Qw [n, G, W, d]; K, V [n, T_max, d]; T [n] prompt lengths (default: all T_max).
@@ -161,18 +151,25 @@ class UnitCache:
 
     n_seen = property(lambda self: int(self._b.n_seen[0]))
 
+    # The sets of Alg. 1, read off the state as the C code does: retained tokens by position, the B_p most recent
+    # are the proximity set (oldest first), the others the context set; the residual slots in use.
+    def _tokens_by_position(self):
+        tok = [j for j in range(self.B_r, self.B) if self.w[j] > 0]
+        return sorted(tok, key=lambda j: self.pos[j])
+
     @property
     def Kp(self):
-        h, n = int(self._b.sets[0, 0]), int(self._b.sets[0, 1])
-        return [int(self._b.kp[0, (h + i) % self._b.cap]) for i in range(n)]
+        tok = self._tokens_by_position()
+        return tok[max(0, len(tok) - self.B_p):]
 
     @property
     def Kc(self):
-        return [int(x) for x in self._b.kc[0, :int(self._b.sets[0, 2])]]
+        tok = self._tokens_by_position()
+        return tok[:max(0, len(tok) - self.B_p)]
 
     @property
     def Kr(self):
-        return list(range(int(self._b.sets[0, 3])))
+        return [r for r in range(self.B_r) if self.w[r] > 0]
 
     def decode_step(self, q, k_new, v_new):
         occ = np.flatnonzero(self.w > 0)
@@ -202,7 +199,6 @@ class UnitCache:
         self.K[:], self.V[:] = K, V
         self.pos[:], self.w[:], self.s[:] = pos, w, s
         self._b.n_seen[0] = int(n_seen)
-        self._b.rebuild_sets()
 
 
 def prompt_scores(Qw, K, lam, scale):
