@@ -154,6 +154,12 @@ def main():
                          "the full-history initialisation)")
     ap.add_argument("--n-residual", type=int, default=None,
                     help="override the workload's number of residual slots B_r (B stays the same, B_c shrinks)")
+    ap.add_argument("--settle-seconds", type=float, default=5.0,
+                    help="idle time between the set-up and the warm-up steps.  Generating 28 GB of synthetic prompts in fp64 "
+                         "and scoring them leaves the chip, for a second or two, in a state in which every kernel (the plain "
+                         "streaming read included) runs about 4 %% slower; a decode that has been running for a few seconds "
+                         "is not in that state (16 384 steps right after the set-up average what 512 steps do after this "
+                         "pause).  0 = start at once")
     ap.add_argument("--budget", type=int, default=None,
                     help="override the workload's budget B (slots per unit at the full prompt length)")
     ap.add_argument("--q-per-kv", type=int, default=None,
@@ -267,6 +273,8 @@ def main():
     info = tuple(torch.empty(L, S, H, dtype=torch.int32, device=dev) for _ in range(3))
     torch.cuda.synchronize()
     setup_s = time.perf_counter() - t_setup
+    if args.settle_seconds > 0:
+        time.sleep(args.settle_seconds)
 
     lpl = args.layers_per_launch if args.layers_per_launch > 0 else L
     cache.set_decode_parts(args.decode_parts)
@@ -360,7 +368,7 @@ def main():
         "tokens_per_s_cache_step_only": value / (L * H) if S == 1 else None,
         "hbm_read_ceiling_GBs": read_ceiling,
         "prefill_compress_ms_all_layers": prefill_ms,
-        "prefill_layers_per_call": (None if args.skip_prefill else plc),
+        "prefill_layers_per_call": (None if args.skip_prefill else plc), "settle_seconds": args.settle_seconds,
         "prefill_window": (wl.window if wl.window > 0 else wl.prompt_len),
         "setup_s": setup_s,
         "device": device_info(),
