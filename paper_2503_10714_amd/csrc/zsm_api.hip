@@ -130,8 +130,8 @@ __global__ __launch_bounds__(256) void stream_read_kernel(const uint4* __restric
     float acc = 0.f;
     const size_t stride = (size_t)gridDim.x * blockDim.x;
     for (size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x; i < n16; i += stride) {
-        const uint4 v = src[i];
-        acc += __uint_as_float(v.x ^ v.y ^ v.z ^ v.w);
+        const u32x4_t v = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t*>(src) + i);   // read once: the fastest plain read on this chip
+        acc += __uint_as_float(v[0] ^ v[1] ^ v[2] ^ v[3]);
     }
     acc = wave_sum(acc);
     if ((threadIdx.x & 63) == 0 && acc == 123.456f) sink[0] = acc;   // practically never taken; keeps the loads live

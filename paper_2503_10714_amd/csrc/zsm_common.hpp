@@ -89,6 +89,10 @@ __device__ __forceinline__ void load_seg(const bf16_t* p, float* out) {
     }
 }
 
+// load_nt: the same load marked non-temporal, for rows that are read once per kernel and whole (a wave-wide load
+// covers complete rows): the lines then pass through the caches without displacing anything, which on this chip
+// raises the rate of a streaming sweep by about an eighth.  Not for loads that take a row in pieces at different
+// times (the line has to stay for the later pieces).
 // Raw<KT, N>: the register image of N consecutive elements (N * sizeof(KT) is a multiple
 // of 16): loaded with 16-byte loads, converted element by element only where it is used.
 typedef float f32x4_t __attribute__((ext_vector_type(4)));
@@ -102,6 +106,10 @@ template <int N> struct Raw<float, N> {
 #pragma unroll
         for (int i = 0; i < N / 4; ++i) v[i] = reinterpret_cast<const f32x4_t*>(p)[i];
     }
+    __device__ __forceinline__ void load_nt(const float* p) {
+#pragma unroll
+        for (int i = 0; i < N / 4; ++i) v[i] = __builtin_nontemporal_load(reinterpret_cast<const f32x4_t*>(p) + i);
+    }
     __device__ __forceinline__ void zero() {
 #pragma unroll
         for (int i = 0; i < N / 4; ++i) v[i] = f32x4_t{0.f, 0.f, 0.f, 0.f};
@@ -113,6 +121,10 @@ template <int N> struct Raw<f16_t, N> {
     __device__ __forceinline__ void load(const f16_t* p) {
 #pragma unroll
         for (int i = 0; i < N / 8; ++i) v[i] = reinterpret_cast<const f16x8_t*>(p)[i];
+    }
+    __device__ __forceinline__ void load_nt(const f16_t* p) {
+#pragma unroll
+        for (int i = 0; i < N / 8; ++i) v[i] = __builtin_nontemporal_load(reinterpret_cast<const f16x8_t*>(p) + i);
     }
     __device__ __forceinline__ void zero() {
 #pragma unroll
@@ -127,6 +139,10 @@ template <int N> struct Raw<bf16_t, N> {
     __device__ __forceinline__ void load(const bf16_t* p) {
 #pragma unroll
         for (int i = 0; i < N / 8; ++i) v[i] = reinterpret_cast<const u32x4_t*>(p)[i];
+    }
+    __device__ __forceinline__ void load_nt(const bf16_t* p) {
+#pragma unroll
+        for (int i = 0; i < N / 8; ++i) v[i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t*>(p) + i);
     }
     __device__ __forceinline__ void zero() {
 #pragma unroll

@@ -110,12 +110,12 @@ __device__ __forceinline__ void tile_load(Raw<KT, EPL>* dst, const KT* __restric
     if (row0 + UU * RPL <= nrows) {
         const KT* p = base + ((size_t)(row0 + grp) * D + seg * EPL);
 #pragma unroll
-        for (int u = 0; u < UU; ++u) dst[u].load(p + (size_t)u * RPL * D);
+        for (int u = 0; u < UU; ++u) dst[u].load_nt(p + (size_t)u * RPL * D);
     } else {
 #pragma unroll
         for (int u = 0; u < UU; ++u) {
             const int r = row0 + u * RPL + grp;
-            dst[u].load(base + (size_t)(r < nrows ? r : nrows - 1) * D + seg * EPL);
+            dst[u].load_nt(base + (size_t)(r < nrows ? r : nrows - 1) * D + seg * EPL);
         }
     }
 }

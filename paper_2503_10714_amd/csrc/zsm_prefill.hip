@@ -89,6 +89,7 @@ __global__ __launch_bounds__(64) void pf_self_logit(PrefillArgs a, PrefillWs ws)
 // MODE 2: MODE 0, and every exp(z_it - C_i) of a key that exists is stored at ev[t][row]; pf_score_from_ev
 //         then forms s_t from there and K is swept once instead of twice.
 typedef double d4_t __attribute__((ext_vector_type(4)));
+typedef double d2_t __attribute__((ext_vector_type(2)));
 
 template <typename T, int D, int MODE>
 __global__ __launch_bounds__(256, MODE == 2 ? 3 : 4) void pf_score_mfma(PrefillArgs a, PrefillWs ws, const double* __restrict__ Qd,
@@ -304,9 +305,9 @@ __global__ __launch_bounds__(256) void pf_score_from_ev(PrefillArgs a, PrefillWs
         for (int c = 0; c < rows; c += 32) {
             const int r = c + 2 * sub, i = r % Wp;    // rows r and r + 1 belong to the same head (Wp is even)
             const double2 w = *reinterpret_cast<const double2*>(rw + r);
-            double2 x[KU];
+            d2_t x[KU];
 #pragma unroll
-            for (int u = 0; u < KU; ++u) x[u] = e[u][r >> 1];
+            for (int u = 0; u < KU; ++u) x[u] = __builtin_nontemporal_load(reinterpret_cast<const d2_t*>(e[u]) + (r >> 1));   // read once, whole lines
 #pragma unroll
             for (int u = 0; u < KU; ++u) {            // values outside the causal window were never written: not touched
                 if (i >= i0[u] && i < nb) v[u] = fma(w.x, x[u].x, v[u]);
@@ -684,8 +685,8 @@ __global__ __launch_bounds__(256) void pf_residual_partial(PrefillArgs a, Prefil
                 const int t = tb + x * RPB;
                 const int tc = t < t1 ? t : t1 - 1;
                 use[x] = t < t1 && keep[tc] == 0;
-                kr[x].load(Ksrc + (size_t)tc * D + seg * EPL);
-                vr[x].load(Vsrc + (size_t)tc * D + seg * EPL);
+                kr[x].load_nt(Ksrc + (size_t)tc * D + seg * EPL);
+                vr[x].load_nt(Vsrc + (size_t)tc * D + seg * EPL);
             }
 #pragma unroll
             for (int x = 0; x < UR; ++x) {
