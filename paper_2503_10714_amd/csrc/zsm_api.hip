@@ -564,7 +564,8 @@ int zsm_stream_read(const void* src, size_t bytes, float* sink, void* stream) {
     if (!aligned16(src)) return ZSM_E_ALIGN;
     if (bytes % 16) return ZSM_E_SHAPE;
     if (bytes == 0) return ZSM_OK;
-    hipLaunchKernelGGL(stream_read_kernel, dim3(256 * 16), dim3(256), 0, static_cast<hipStream_t>(stream),
+    // 8 workgroups per compute unit: the fastest of the grid sizes tried (1024 to 8192) for a 1.5 GB buffer
+    hipLaunchKernelGGL(stream_read_kernel, dim3(256 * 8), dim3(256), 0, static_cast<hipStream_t>(stream),
                        static_cast<const uint4*>(src), bytes / 16, sink);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return hip_fail(e, "zsm_stream_read");
