@@ -59,7 +59,8 @@ typedef struct {
     int32_t n_layers;       /* L                                                        */
     int32_t n_seqs;         /* S: sequences in the batch                                */
     int32_t n_kv_heads;     /* H: KV heads per layer                                    */
-    int32_t q_per_kv;       /* G: query heads sharing one KV head (1, 2, 4 or 8)        */
+    int32_t q_per_kv;       /* G: query heads sharing one KV head, 1 to 8 (3 runs the   */
+                            /* kernels of 4, and 5 to 7 those of 8, at their cost)      */
     int32_t head_dim;       /* d: 64 or 128                                             */
     int32_t slot_capacity;  /* slot stride: max over sequences of B_r + B_c + B_p       */
     int32_t n_residual;     /* B_r (0 = pure eviction, Sec. 3.2)                        */

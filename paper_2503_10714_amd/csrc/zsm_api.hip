@@ -43,7 +43,7 @@ bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 
 bool config_ok(const zsm_config_t* c) {
     if (!c) return false;
     if (c->n_layers < 1 || c->n_seqs < 1 || c->n_kv_heads < 1) return false;
-    if (!(c->q_per_kv == 1 || c->q_per_kv == 2 || c->q_per_kv == 4 || c->q_per_kv == 8)) return false;
+    if (c->q_per_kv < 1 || c->q_per_kv > 8) return false;
     if (!(c->head_dim == 64 || c->head_dim == 128)) return false;
     if (c->n_residual < 0 || c->slot_capacity < c->n_residual + 1) return false;
     if (!(c->lambda >= 0.f && c->lambda <= 1.f) || !(c->alpha >= 0.f && c->alpha <= 1.f)) return false;
@@ -98,7 +98,7 @@ Layout make_layout(const zsm_config_t& c) {
     l.Vt = o; o += up256(esize(c.kv_dtype) * units * (cap - Br) * D);
     l.sp_max_units = (int)(units < (size_t)SP_MAX_UNITS ? units : (size_t)SP_MAX_UNITS);
     l.sp_max_wgs = l.sp_max_units * SP_MAX_PARTS < SP_MAX_WGS ? l.sp_max_units * SP_MAX_PARTS : SP_MAX_WGS;
-    const SplitScratch sp = split_scratch(l.sp_max_wgs, l.sp_max_units, c.q_per_kv, D, cap);
+    const SplitScratch sp = split_scratch(l.sp_max_wgs, l.sp_max_units, decode_compiled_heads(c.q_per_kv), D, cap);
     l.sp_L = o + sp.L; l.sp_acc = o + sp.acc; l.sp_E = o + sp.E;
     o += sp.total;
     l.total = o;
@@ -224,7 +224,7 @@ int choose_parts(const zsm_cache_t* cache, int n_units, int* part_rows) {
         // a capacity one workgroup's LDS cannot hold: more parts, and then as many as let the compute unit hold the
         // workgroups its registers allow (4 of a single query head, 3 of four heads, 2 otherwise)
         while (lds_need(parts) > 160 * 1024 && parts < hi) ++parts;
-        const size_t want = v.G == 1 ? 4 : (v.G == 4 ? 3 : 2);
+        const size_t want = v.G == 1 ? 4 : (decode_compiled_heads(v.G) == 4 ? 3 : 2);
         while (160 * 1024 / lds_need(parts) < want && parts < hi && parts < ntiles / (2 * DECODE_NW)) ++parts;
     }
     if (lds_need(parts) > 160 * 1024) return ZSM_E_SHAPE;
@@ -336,7 +336,7 @@ static int decode_step_impl(zsm_cache_t* cache, int32_t layer_begin, int32_t lay
     DecodeArgs a;
     a.cv = v;
     if (scratch && parts > 1) {
-        const SplitScratch sp = split_scratch((size_t)n_units * parts, n_units, v.G, v.D, v.cap);
+        const SplitScratch sp = split_scratch((size_t)n_units * parts, n_units, decode_compiled_heads(v.G), v.D, v.cap);
         if (sp.total > scratch_bytes) return ZSM_E_NOMEM;
         a.cv.sp_L = reinterpret_cast<double*>(scratch + sp.L);
         a.cv.sp_acc = reinterpret_cast<float*>(scratch + sp.acc);

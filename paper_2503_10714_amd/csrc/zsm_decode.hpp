@@ -445,6 +445,19 @@ __device__ __forceinline__ void prio_from_progress(int done, int total) {
     else __builtin_amdgcn_s_setprio(3);
 }
 
+// Query heads per KV head.  The kernels are compiled for G = 1, 2, 4, 8; a cache with another number Gr of query
+// heads (3, 5, 6, 7) runs the next larger one: the heads past the last read the last head's query again, their
+// 1/L is set to 0 (so they add nothing to Eq. 3's head mean) and their outputs are not written.
+template <int G>
+__device__ __forceinline__ int real_heads(const CacheView& cv) { return G == 1 ? 1 : cv.G; }
+
+// mean over the Gr heads of a sum over them (appendix, grouped-query adaptation): the oracle's sum / Gr
+template <int G>
+__device__ __forceinline__ double head_mean(double sum, int Gr) {
+    if constexpr (G == 1) return sum;
+    return Gr == G ? sum / (double)G : sum / (double)Gr;   // a power of two: an exact multiplication
+}
+
 // Everything of a unit's cache that the end of a step touches.
 template <typename T>
 struct UnitRefs {
@@ -537,6 +550,7 @@ __device__ __forceinline__ void decode_finish(const DecodeArgs& a, const CacheVi
                                               unsigned long long* keyw, double* dotw, int* misc) {
     constexpr int NT = NW * 64, MCH = DECODE_MCH;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int Gr = real_heads<G>(cv);
     T* Kt = u.Kt; T* Vt = u.Vt;
     float* Kr = u.Kr; float* Vr = u.Vr;
     float* s = u.s; int32_t* pos = u.pos; int32_t* w = u.w;
@@ -575,7 +589,7 @@ __device__ __forceinline__ void decode_finish(const DecodeArgs& a, const CacheVi
 #pragma unroll
                     for (int g = 0; g < G; ++g)
                         pm += ((GE > 0 && base == 0) ? pre.ej[GE > 0 ? k : 0][GE > 0 ? g : 0] : et[(size_t)g * Bz + j]) * rL[g];
-                    pm /= (double)G;
+                    pm = head_mean<G>(pm, Gr);
                     const float sn = (float)(lam * (double)pre.sj[k] + pm);
                     sn4[c4] = sn;
                     if (!pre.vec) s[j] = sn;
@@ -692,7 +706,7 @@ __device__ __forceinline__ void decode_finish(const DecodeArgs& a, const CacheVi
         double pm = 0.0;
 #pragma unroll
         for (int g = 0; g < G; ++g) pm += e_new[g] * rL[g];
-        pm /= (double)G;
+        pm = head_mean<G>(pm, Gr);
         pos[c] = (int32_t)Tseen;
         w[c] = 1;
         s[c] = (float)pm;
@@ -723,6 +737,7 @@ __global__ __launch_bounds__(NW * 64, G == 1 ? 4 : (NW == 12 ? 3 : 2)) void deco
     constexpr int EPL = Sh::EPL, LPR = Sh::LPR, RPL = Sh::RPL, R = Sh::R, PART = Sh::PART, NT = Sh::NT, UT = Sh::UT;
     constexpr bool QLDS = Sh::QLDS;
     const CacheView& cv = a.cv;
+    const int Gr = real_heads<G>(cv);
     const int lu = SPLIT ? (int)blockIdx.x / a.parts : (int)blockIdx.x;
     const int part = SPLIT ? (int)blockIdx.x % a.parts : 0;
     const int ug = a.unit0 + lu;
@@ -779,7 +794,7 @@ __global__ __launch_bounds__(NW * 64, G == 1 ? 4 : (NW == 12 ? 3 : 2)) void deco
         if constexpr (MF) tile_load_mfma4<T, UT, D, EPL>(bufA, Kt, wave * R, cv.cap_tok, lane);
         else tile_load<T, UT, D, EPL, LPR, RPL>(bufA, Kt, wave * R, cv.cap_tok, klane);
     }
-    const T* qp = reinterpret_cast<const T*>(a.q) + (size_t)lu * G * D;
+    const T* qp = reinterpret_cast<const T*>(a.q) + (size_t)lu * Gr * D;
     const T* knew = reinterpret_cast<const T*>(a.k_new) + (size_t)lu * D;
     const T* vnew = reinterpret_cast<const T*>(a.v_new) + (size_t)lu * D;
     const long long Tseen = cv.n_seen[ug];
@@ -792,13 +807,13 @@ __global__ __launch_bounds__(NW * 64, G == 1 ? 4 : (NW == 12 ? 3 : 2)) void deco
     Query<G, EPL, QLDS, QE> qq;
     qq.lds = qlds;
     if (QLDS) {
-        for (int i = tid; i < G * D; i += NT) qlds[i] = (QE)to_float(qp[i]);
+        for (int i = tid; i < G * D; i += NT) qlds[i] = (QE)to_float(qp[(i / D < Gr ? i / D : Gr - 1) * D + i % D]);
         __syncthreads();
     } else {
 #pragma unroll
         for (int g = 0; g < (QLDS ? 1 : G); ++g) {
             float qf[EPL];
-            load_seg<EPL>(qp + g * D + kseg * EPL, qf);
+            load_seg<EPL>(qp + (g < Gr ? g : Gr - 1) * D + kseg * EPL, qf);
 #pragma unroll
             for (int e = 0; e < EPL; ++e) qq.r[g][e] = (double)qf[e];
         }
@@ -812,7 +827,8 @@ __global__ __launch_bounds__(NW * 64, G == 1 ? 4 : (NW == 12 ? 3 : 2)) void deco
 #pragma unroll
             for (int u = 0; u < UT; ++u) {
                 float qf[EPL];
-                load_seg<EPL>(qp + (4 * h + (lane & 3)) * D + (4 * u + (lane >> 4)) * EPL, qf);
+                const int hq = 4 * h + (lane & 3);
+                load_seg<EPL>(qp + (hq < Gr ? hq : Gr - 1) * D + (4 * u + (lane >> 4)) * EPL, qf);
 #pragma unroll
                 for (int e = 0; e < EPL; ++e) qa[h][u][e] = (double)qf[e];
             }
@@ -943,6 +959,7 @@ __global__ __launch_bounds__(NW * 64, G == 1 ? 4 : (NW == 12 ? 3 : 2)) void deco
 #pragma unroll
         for (int x = 0; x < NW; ++x) t += red64[x * G + g];
         rL[g] = SPLIT ? (t > 0.0 ? 1.0 / t : 0.0) : 1.0 / t;   // the unit's own denominator counts the incoming token: >= 1
+        if (G > 1 && g >= Gr) rL[g] = 0.0;
         if (t >= SPREAD_FLAG_SUM && tid == 0) atomicOr(cv.flags + ug, FLAG_DECODE_SPREAD);   // practically never taken
     }
 
@@ -1015,11 +1032,11 @@ __global__ __launch_bounds__(NW * 64, G == 1 ? 4 : (NW == 12 ? 3 : 2)) void deco
     }
     __syncthreads();
     if (!SPLIT) {
-        for (int idx = tid; idx < G * D; idx += NT) {
+        for (int idx = tid; idx < Gr * D; idx += NT) {
             float o = 0.f;
 #pragma unroll
             for (int x = 0; x < NW; ++x) o += accw[x * G * D + idx];
-            a.out[(size_t)lu * G * D + idx] = o;
+            a.out[(size_t)lu * Gr * D + idx] = o;
         }
         decode_finish<T, D, G, NW, 0>(a, cv, u, lu, ug, Bp, Br, B, Tseen, nocc, full, et, Bz, rL, pre, keyw, dotw, misc);
         return;
@@ -1064,6 +1081,7 @@ __global__ __launch_bounds__(NW * 64) void decode_combine_kernel(DecodeArgs a) {
     const int b = (ug / cv.H) % cv.S;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int Br = cv.Br, P = a.parts;
+    const int Gr = real_heads<G>(cv);
     __shared__ unsigned long long keyw[NW];
     __shared__ double dotw[NW];
     __shared__ int misc[4 + NW];
@@ -1106,11 +1124,11 @@ __global__ __launch_bounds__(NW * 64) void decode_combine_kernel(DecodeArgs a) {
     __syncthreads();
     double rL[G];
 #pragma unroll
-    for (int g = 0; g < G; ++g) rL[g] = 1.0 / Lsum[g];   // part 0 counted the incoming token: the sum is >= 1
+    for (int g = 0; g < G; ++g) rL[g] = (G > 1 && g >= Gr) ? 0.0 : 1.0 / Lsum[g];   // part 0 counted the incoming token: the sum is >= 1
 #pragma unroll
     for (int x = 0; x < OPT; ++x) {
         const int idx = x * NT + tid;
-        if (idx >= G * D) break;
+        if (idx >= Gr * D) break;
         const int g = idx / D;
         double rl = 0.0;
 #pragma unroll
@@ -1131,7 +1149,7 @@ __global__ __launch_bounds__(NW * 64) void decode_combine_kernel(DecodeArgs a) {
             for (int y = 0; y < 4; ++y) o = fmaf((float)(Lp[p + y][g] * rl), v[y], o);
         }
         for (; p < P; ++p) o = fmaf((float)(Lp[p][g] * rl), cv.sp_acc[(size_t)(wg0 + p) * G * D + idx], o);
-        a.out[(size_t)lu * G * D + idx] = o;
+        a.out[(size_t)lu * Gr * D + idx] = o;
     }
     decode_finish<T, D, G, NW, G>(a, cv, u, lu, ug, Bp, Br, B, Tseen, nocc, full, Eu, BzG, rL, pre, keyw, dotw, misc);
 }
@@ -1214,9 +1232,12 @@ inline size_t decode_lds_dg(int nz) { return DecodeShape<T, D, G, DECODE_NW>::ld
 // rows of one wave tile for a K/V element size (the unit the parts of a split step are cut in)
 inline int decode_tile_rows(int D, int esize) { return DecodeShape<float, 64, 1, DECODE_NW>::UT * (64 / (D * esize / 16)); }
 
+// the compiled number of query heads that serves a cache with G of them (1..8)
+inline int decode_compiled_heads(int G) { return G <= 2 ? G : (G <= 4 ? 4 : 8); }
+
 template <typename T>
 inline hipError_t launch_decode_t(const DecodeArgs& a, hipStream_t stream) {
-    const int D = a.cv.D, G = a.cv.G;
+    const int D = a.cv.D, G = decode_compiled_heads(a.cv.G);
 #define ZSM_CASE(DD, GG) if (D == DD && G == GG) return launch_decode_dg<T, DD, GG>(a, stream);
     ZSM_CASE(64, 1) ZSM_CASE(64, 2) ZSM_CASE(64, 4) ZSM_CASE(64, 8)
     ZSM_CASE(128, 1) ZSM_CASE(128, 2) ZSM_CASE(128, 4) ZSM_CASE(128, 8)
@@ -1226,7 +1247,8 @@ inline hipError_t launch_decode_t(const DecodeArgs& a, hipStream_t stream) {
 
 // LDS bytes of a launch that keeps `nz` per-slot values per query head in LDS
 template <typename T>
-inline size_t decode_lds_t(int D, int G, int nz) {
+inline size_t decode_lds_t(int D, int Gr, int nz) {
+    const int G = decode_compiled_heads(Gr);
 #define ZSM_CASE(DD, GG) if (D == DD && G == GG) return decode_lds_dg<T, DD, GG>(nz);
     ZSM_CASE(64, 1) ZSM_CASE(64, 2) ZSM_CASE(64, 4) ZSM_CASE(64, 8)
     ZSM_CASE(128, 1) ZSM_CASE(128, 2) ZSM_CASE(128, 4) ZSM_CASE(128, 8)

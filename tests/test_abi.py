@@ -48,7 +48,10 @@ def test_cache_bytes_and_config_checks(zb):
     wgs = min(units * 64, 8192)
     scratch = wgs * 8 + wgs * 128 * 4 + units * 206 * 8
     assert kv + scratch <= n <= kv + scratch + units * 205 * 12 + 2 * units * 128 * 4 + units * 16 + 22 * 256
-    assert zb.zsm_cache_bytes(zb.make_config(2, 3, 4, 3, 128, 205, 1, "f16")) == 0      # G = 3
+    assert zb.zsm_cache_bytes(zb.make_config(2, 3, 4, 9, 128, 205, 1, "f16")) == 0      # G = 9
+    assert zb.zsm_cache_bytes(zb.make_config(2, 3, 4, 0, 128, 205, 1, "f16")) == 0      # G = 0
+    # three query heads run the kernels of four: the same scratch, hence the same cache size
+    assert zb.zsm_cache_bytes(zb.make_config(2, 3, 4, 3, 128, 205, 1, "f16")) == zb.zsm_cache_bytes(zb.make_config(2, 3, 4, 4, 128, 205, 1, "f16"))
     assert zb.zsm_cache_bytes(zb.make_config(2, 3, 4, 1, 96, 205, 1, "f16")) == 0       # d = 96
     assert zb.zsm_cache_bytes(zb.make_config(2, 3, 4, 1, 128, 1, 1, "f16")) == 0        # no token slot
     assert zb.zsm_cache_bytes(zb.make_config(2, 3, 4, 1, 128, 205, 1, "f16", lam=1.5)) == 0

@@ -56,6 +56,16 @@ DECODE_CASES = {
     "wide_wg8_gqa2_f32_d64": lambda: small("wide_wg8_gqa2_f32_d64", q_per_kv=2, prompt_len=6200, budget=6000, decode_steps=6),
     "wide_wg8_gqa8_bf16": lambda: small("wide_wg8_gqa8_bf16", dtype="bf16", q_per_kv=8, head_dim=128, n_kv_heads=1,
                                         prompt_len=1800, budget=1500, decode_steps=8, outliers=True),
+    # group sizes that are no power of two run the kernels of the next one (3 -> 4, 5..7 -> 8): the heads past the
+    # last must count neither in Eq. 3's head mean nor in the outputs.  Vector path, matrix path (full and masked
+    # tiles), many residual slots, fp32 keys
+    "gqa3_f32_d64": lambda: small("gqa3_f32_d64", q_per_kv=3, n_residual=2, prompt_len=300, budget=70, outliers=True),
+    "gqa7_bf16_d128": lambda: small("gqa7_bf16_d128", dtype="bf16", q_per_kv=7, head_dim=128, n_kv_heads=2, n_residual=3,
+                                    prompt_len=400, budget=150, decode_steps=48, outliers=True),
+    "gqa5_f16_fills_up": lambda: small("gqa5_f16_fills_up", dtype="f16", q_per_kv=5, head_dim=128, prompt_len=30,
+                                       budget=64, decode_steps=60, window=8),
+    "gqa6_f32_d128": lambda: small("gqa6_f32_d128", q_per_kv=6, head_dim=128, n_residual=12, budget=60, prompt_len=200,
+                                   alpha=0.5),
     "fills_up": lambda: small("fills_up", prompt_len=20, budget=48, decode_steps=60, window=8),       # T < B: free slots first
     "empty_start": lambda: small("empty_start", prompt_len=0, budget=24, decode_steps=50, n_residual=2, window=4),
     "ragged_multi_layer": lambda: small("ragged_multi_layer", n_layers=2, n_seqs=3, dtype="f16", head_dim=128,
@@ -101,7 +111,7 @@ def test_decode_from_oracle_state(case):
 # (case, workgroups per unit): the split step must give the oracle's decisions and outputs whatever the cut
 SPLIT_CASES = [("cfg1", 4), ("cfg1", 13), ("three_residual_f16", 2), ("alpha_half_bf16_gqa4", 3), ("gqa8_f32_d128", 2),
                ("fills_up", 2), ("gqa4_f16_many_tiles", 2), ("gqa8_bf16_d128", 3), ("empty_start", 3), ("ragged_multi_layer", 5), ("evict_only", 3), ("cfg0", 3),
-               ("residual_40_f16", 3), ("residual_20_f32_gqa4", 2)]
+               ("residual_40_f16", 3), ("residual_20_f32_gqa4", 2), ("gqa7_bf16_d128", 3), ("gqa3_f32_d64", 2)]
 
 
 @pytest.mark.parametrize("case,parts", SPLIT_CASES)
@@ -253,6 +263,10 @@ FULL_CASES = {
     "cfg4_slice": (lambda: synth.workload(4).sliced(n_layers=1, n_seqs=2, n_kv_heads=2, layer0=30, seq0=3, head0=6), 96),
     # the paper's recommended residual share (dense ratio 0.02 of B - B_p: 27 slots at B = 2700) on workload 2's shape
     "cfg2_slice_27_residual": (lambda: synth.workload(2).sliced(n_layers=1, n_kv_heads=2, layer0=11, head0=20, n_residual=27), 24),
+    # seven query heads per KV head (28 query and 4 KV heads, d = 128): prompt scores pooled over seven heads, then
+    # the decode step on the kernels compiled for eight
+    "gqa7_prompt_then_decode": (lambda: small("gqa7_full", dtype="bf16", q_per_kv=7, head_dim=128, n_kv_heads=4, n_seqs=2,
+                                              prompt_len=600, budget=96, window=32, n_residual=2, outliers=True), 40),
     # a batch of prompts between 0 and 5 tokens long (three of the eight are empty), then enough steps to fill
     # the slots and evict
     "ragged_with_empty_prompts": (lambda: small("ragged_empty", n_seqs=8, prompt_len=5, ragged=(0, 5), budget=12, window=8,
@@ -364,6 +378,26 @@ def test_random_shapes_prefill_then_decode(seed):
     cache.set_decode_parts(1)
     st = pu.run_decode_parity(wl, cache, units, 12, state_every=0, first_step=12)
     print(f"[done] random {seed}: parts {used} then 1, unit-steps={st0.unit_steps + st.unit_steps} evictions={st0.evictions + st.evictions} "
+          f"near_ties={st0.near_ties + st.near_ties} max|out err|={max(st0.max_out_err, st.max_out_err):.2e}", flush=True)
+    cache.close()
+
+
+@pytest.mark.parametrize("seed", list(range(12)))
+def test_random_shapes_other_group_sizes(seed):
+    """The same sweep with 3, 5, 6 and 7 query heads per KV head."""
+    wl = random_workload(100 + seed).sliced(q_per_kv=[3, 5, 6, 7][seed % 4])
+    bp, bc, br = wl.budgets()
+    print(f"[case] random {100 + seed}: {wl.dtype} d={wl.head_dim} G={wl.q_per_kv} B_r={br} T={wl.seq_lens()} B_p={bp} B_c={bc} "
+          f"W={wl.window} L={wl.n_layers} H={wl.n_kv_heads} alpha={wl.alpha}", flush=True)
+    if min(p for p in bp) < 1 or min(c for c in bc) < 0:
+        pytest.skip("drawn budget leaves no proximity slot")
+    cache, units = prefill_gpu_and_oracle(wl, gen_device="cpu")
+    pu.compare_all_state(wl, cache, units, pu.tol_for(wl.dtype), "after prefill")
+    cache.set_decode_parts(2 + seed % 3)
+    st0 = pu.run_decode_parity(wl, cache, units, 12, state_every=0)
+    cache.set_decode_parts(1)
+    st = pu.run_decode_parity(wl, cache, units, 12, state_every=0, first_step=12)
+    print(f"[done] random {100 + seed}: unit-steps={st0.unit_steps + st.unit_steps} evictions={st0.evictions + st.evictions} "
           f"near_ties={st0.near_ties + st.near_ties} max|out err|={max(st0.max_out_err, st.max_out_err):.2e}", flush=True)
     cache.close()
 
