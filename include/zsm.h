@@ -173,8 +173,9 @@ int zsm_prefill_compress(zsm_cache_t* cache, int32_t layer_begin, int32_t layer_
  * partial softmax sums and outputs meet in a scratch area inside the cache buffer; the
  * result does not depend on the cut beyond fp32 rounding of the output (scores, choices
  * and merged rows are formed in fp64 from the same per-slot values either way).
- * Limit: the per-slot values of one workgroup, (slots + 1) * G * 8 bytes, must fit the
- * 160 KB LDS together with ~24 KB of staging; a capacity too large for one workgroup is
+ * Positions are kept as int32: a unit may see at most 2^31 - 1 tokens in all.
+ * Limit: the per-slot values of one workgroup, (slots + 1) * G' * 8 bytes (G' = G rounded up
+ * to 1, 2, 4 or 8), must fit the 160 KB LDS together with ~24 KB of staging; a capacity too large for one workgroup is
  * split automatically where the launch is small enough to be split (at most 1024 units),
  * else ZSM_E_SHAPE.
  */

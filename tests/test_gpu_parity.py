@@ -66,6 +66,10 @@ DECODE_CASES = {
                                        budget=64, decode_steps=60, window=8),
     "gqa6_f32_d128": lambda: small("gqa6_f32_d128", q_per_kv=6, head_dim=128, n_residual=12, budget=60, prompt_len=200,
                                    alpha=0.5),
+    # a long run on a small budget: every slot is replaced dozens of times, the residual counts grow into the
+    # thousands (Eq. 6 with a large w), scores decay over many steps (Eq. 3)
+    "long_run_1500_steps": lambda: small("long_run", n_kv_heads=1, prompt_len=40, budget=24, n_residual=2, decode_steps=1500,
+                                         window=8, dtype="f16", outliers=True),
     "fills_up": lambda: small("fills_up", prompt_len=20, budget=48, decode_steps=60, window=8),       # T < B: free slots first
     "empty_start": lambda: small("empty_start", prompt_len=0, budget=24, decode_steps=50, n_residual=2, window=4),
     "ragged_multi_layer": lambda: small("ragged_multi_layer", n_layers=2, n_seqs=3, dtype="f16", head_dim=128,
