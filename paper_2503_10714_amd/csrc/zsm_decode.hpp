@@ -67,15 +67,20 @@ struct DecodeShape {
     static constexpr size_t QBYTES = QLDS ? sizeof(QE) * G * D : 0;
     // one LDS region serves the partial-dot staging and the queries of pass 1 and, after pass 2, the
     // waves' partial outputs
-    static constexpr size_t STAGE_A = sizeof(double) * NW * PART, STAGE_B = sizeof(float) * NW * G * D;
-    static constexpr size_t STAGE = STAGE_A + QBYTES > STAGE_B ? STAGE_A + QBYTES : STAGE_B;
+    // Normally every wave has a slot of its own there (out_slots = NW).  With eight query heads that is 16 KB, twice
+    // what pass 1 needs, and at B = 1024 what keeps a second workgroup out of a compute unit's LDS: such a launch
+    // runs with two slots, the waves handing their outputs over two at a time (NW / 2 rounds, a barrier each).
+    static constexpr size_t STAGE_A = sizeof(double) * NW * PART;
+    __host__ __device__ static constexpr size_t stage_bytes(int out_slots) {
+        return STAGE_A + QBYTES > sizeof(float) * out_slots * G * D ? STAGE_A + QBYTES : sizeof(float) * out_slots * G * D;
+    }
     static_assert(LPR >= 1 && LPR <= 64 && 64 % LPR == 0, "row must split over a wave");
 
     // dynamic LDS bytes when `nz` slots (the incoming token counted) keep their exp(logit - C) in LDS
-    __host__ __device__ static size_t lds_bytes(int nz) {
+    __host__ __device__ static size_t lds_bytes(int nz, int out_slots = NW) {
         size_t n = 0;
         n += sizeof(double) * G * (size_t)nz;          // et
-        n += STAGE;                                    // part and queries (pass 1) / accw (after pass 2)
+        n += stage_bytes(out_slots);                   // part and queries (pass 1) / accw (after pass 2)
         n += sizeof(double) * NW * G;                  // red64
         n += sizeof(unsigned long long) * NW;          // keyw
         n += sizeof(double) * NW;                      // dotw
@@ -731,7 +736,10 @@ __device__ __forceinline__ void decode_finish(const DecodeArgs& a, const CacheVi
 //   decode_combine_kernel, launched behind it, finishes every unit from there (the kernel
 //   boundary is what makes one workgroup's scratch visible to another: fences inside one
 //   kernel cost more here than the whole sweep of a small launch).
-template <typename T, int D, int G, int NW, bool SPLIT>
+//
+// AW: LDS slots for the waves' partial outputs after pass 2: one per wave, or fewer, the waves then handing
+// their outputs over AW at a time.
+template <typename T, int D, int G, int NW, bool SPLIT, int AW = NW>
 __global__ __launch_bounds__(NW * 64, G == 1 ? 4 : (NW == 12 ? 3 : 2)) void decode_kernel(DecodeArgs a) {
     using Sh = DecodeShape<T, D, G, NW>;
     constexpr int EPL = Sh::EPL, LPR = Sh::LPR, RPL = Sh::RPL, R = Sh::R, PART = Sh::PART, NT = Sh::NT, UT = Sh::UT;
@@ -773,8 +781,8 @@ __global__ __launch_bounds__(NW * 64, G == 1 ? 4 : (NW == 12 ? 3 : 2)) void deco
     double* part_s = et + (size_t)G * Bz;                         // [NW][PART], pass 1 only
     using QE = typename Sh::QE;
     QE* qlds = reinterpret_cast<QE*>(part_s + NW * PART);         // [G][D] (QLDS only), pass 1 only
-    float* accw = reinterpret_cast<float*>(part_s);               // [NW][G][D], after pass 2 (the memory of the two above)
-    double* red64 = reinterpret_cast<double*>(reinterpret_cast<unsigned char*>(part_s) + Sh::STAGE);   // [NW][G]
+    float* accw = reinterpret_cast<float*>(part_s);               // [AW][G][D], after pass 2 (the memory of the two above)
+    double* red64 = reinterpret_cast<double*>(reinterpret_cast<unsigned char*>(part_s) + Sh::stage_bytes(AW));   // [NW][G]
     unsigned long long* keyw = reinterpret_cast<unsigned long long*>(red64 + NW * G);   // [NW]
     double* dotw = reinterpret_cast<double*>(keyw + NW);          // [NW]
     int* misc = reinterpret_cast<int*>(dotw + NW);                // [4 + NW]
@@ -1020,22 +1028,29 @@ __global__ __launch_bounds__(NW * 64, G == 1 ? 4 : (NW == 12 ? 3 : 2)) void deco
     FinishPre<T, D, NW> pre;
     if (!SPLIT) pre.load(u, cv.cap, Br);
     // ---- combine the waves' partial outputs ----------------------------------------------
+    // (fewer slots than waves: waves r*AW .. r*AW + AW - 1 take round r; the first round stores, the later ones add)
 #pragma unroll
-    for (int g = 0; g < G; ++g) {
+    for (int round = 0; round < NW / AW; ++round) {
+        if (wave / AW == round) {
 #pragma unroll
-        for (int e = 0; e < EPL; ++e) {
-            float v = acc[g][e];
+            for (int g = 0; g < G; ++g) {
 #pragma unroll
-            for (int o = LPR; o < 64; o <<= 1) v += __shfl_xor(v, o, 64);
-            if (grp == 0) accw[(wave * G + g) * D + seg * EPL + e] = v;
+                for (int e = 0; e < EPL; ++e) {
+                    float v = acc[g][e];
+#pragma unroll
+                    for (int o = LPR; o < 64; o <<= 1) v += __shfl_xor(v, o, 64);
+                    float* slot = &accw[((wave - round * AW) * G + g) * D + seg * EPL + e];
+                    if (grp == 0) *slot = round == 0 ? v : *slot + v;
+                }
+            }
         }
+        __syncthreads();
     }
-    __syncthreads();
     if (!SPLIT) {
         for (int idx = tid; idx < Gr * D; idx += NT) {
             float o = 0.f;
 #pragma unroll
-            for (int x = 0; x < NW; ++x) o += accw[x * G * D + idx];
+            for (int x = 0; x < AW; ++x) o += accw[x * G * D + idx];
             a.out[(size_t)lu * Gr * D + idx] = o;
         }
         decode_finish<T, D, G, NW, 0>(a, cv, u, lu, ug, Bp, Br, B, Tseen, nocc, full, et, Bz, rL, pre, keyw, dotw, misc);
@@ -1049,7 +1064,7 @@ __global__ __launch_bounds__(NW * 64, G == 1 ? 4 : (NW == 12 ? 3 : 2)) void deco
     for (int idx = tid; idx < G * D; idx += NT) {
         float o = 0.f;
 #pragma unroll
-        for (int x = 0; x < NW; ++x) o += accw[x * G * D + idx];
+        for (int x = 0; x < AW; ++x) o += accw[x * G * D + idx];
         cv.sp_acc[(size_t)wg * G * D + idx] = o;
     }
     if (tid < G) {
@@ -1165,16 +1180,28 @@ constexpr size_t DECODE_LDS_MAX = 160 * 1024;   // LDS of one compute unit
 // B = 12000: 1.25 ms with 4 waves, 1.08 with 16).  Where two or more workgroups of four waves fit they stay: at
 // B = 6000 two of them stream as fast as sixteen waves do, and with three resident, as at four query heads and
 // B = 1024, larger workgroups lose to the serial stretches of a unit.
-template <typename T, int D, int G, bool SPLIT, int NWK>
+template <typename T, int D, int G, bool SPLIT, int NWK, int AWK = NWK>
 inline hipError_t launch_decode_nw(const DecodeArgs& a, hipStream_t stream);
 
 // waves a compute unit holds of this kernel by its registers (the launch bound's waves per SIMD, times four)
 template <typename T, int D, int G>
 constexpr int decode_cu_waves() { return G == 1 ? 16 : ((G == 4 && DecodeShape<T, D, G, DECODE_NW>::MFMA4) ? 12 : 8); }
 
+// LDS slots for the waves' partial outputs: one per wave, or two where that lets a second workgroup of four waves
+// into a compute unit (eight query heads: 16 KB against 8 KB of staging; measured at B = 1024, 4096 units:
+// 0.72 ms per step with one workgroup of eight waves per compute unit, 0.58 with two of four)
+template <typename T, int D, int G, int NWK>
+inline int decode_out_slots(int nz) {
+    if constexpr (G == 8 && NWK == 4) {
+        using Sh = DecodeShape<T, D, G, NWK>;
+        if (DECODE_LDS_MAX / Sh::lds_bytes(nz, 2) >= 2 && DECODE_LDS_MAX / Sh::lds_bytes(nz, NWK) < 2) return 2;
+    }
+    return NWK;
+}
+
 template <typename T, int D, int G, int NWK>
 inline int decode_resident_waves(int nz) {
-    const size_t lds = DecodeShape<T, D, G, NWK>::lds_bytes(nz);
+    const size_t lds = DecodeShape<T, D, G, NWK>::lds_bytes(nz, decode_out_slots<T, D, G, NWK>(nz));
     if (lds > DECODE_LDS_MAX) return 0;
     const int by_lds = (int)(DECODE_LDS_MAX / lds) * NWK, by_regs = decode_cu_waves<T, D, G>() / NWK * NWK;
     return by_lds < by_regs ? by_lds : by_regs;
@@ -1199,11 +1226,15 @@ inline hipError_t launch_decode_dgs(const DecodeArgs& a, hipStream_t stream) {
     return launch_decode_nw<T, D, G, SPLIT, DECODE_NW>(a, stream);
 }
 
-template <typename T, int D, int G, bool SPLIT, int NWK>
+template <typename T, int D, int G, bool SPLIT, int NWK, int AWK>
 inline hipError_t launch_decode_nw(const DecodeArgs& a, hipStream_t stream) {
     using Sh = DecodeShape<T, D, G, NWK>;
-    const size_t lds = Sh::lds_bytes(SPLIT ? a.part_rows + a.cv.Br + 1 : a.cv.cap + 1);
-    auto kern = decode_kernel<T, D, G, NWK, SPLIT>;
+    const int nz = SPLIT ? a.part_rows + a.cv.Br + 1 : a.cv.cap + 1;
+    if constexpr (G == 8 && NWK == 4 && !SPLIT && AWK == NWK) {
+        if (decode_out_slots<T, D, G, NWK>(nz) == 2) return launch_decode_nw<T, D, G, SPLIT, NWK, 2>(a, stream);
+    }
+    const size_t lds = Sh::lds_bytes(nz, AWK);
+    auto kern = decode_kernel<T, D, G, NWK, SPLIT, AWK>;
     // The attribute is per device; bit `dev` records that it has been set there.  Two host threads that
     // meet here for the first time may both set it (harmless: same value), neither reads a torn flag.
     static std::atomic<unsigned long long> attr_done{0ull};

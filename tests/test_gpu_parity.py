@@ -70,6 +70,13 @@ DECODE_CASES = {
     # thousands (Eq. 6 with a large w), scores decay over many steps (Eq. 3)
     "long_run_1500_steps": lambda: small("long_run", n_kv_heads=1, prompt_len=40, budget=24, n_residual=2, decode_steps=1500,
                                          window=8, dtype="f16", outliers=True),
+    # eight (seven) query heads and a budget whose per-slot values leave room for two workgroups per compute unit only
+    # if the waves stage their partial outputs in two LDS slots instead of four: the kernel variant that hands them
+    # over in two rounds
+    "gqa8_two_output_slots_bf16": lambda: small("gqa8_two_slots", dtype="bf16", q_per_kv=8, head_dim=128, n_kv_heads=2, n_residual=3,
+                                                prompt_len=1300, budget=1100, decode_steps=8, outliers=True),
+    "gqa7_two_output_slots_f16": lambda: small("gqa7_two_slots", dtype="f16", q_per_kv=7, head_dim=128, n_kv_heads=1,
+                                               prompt_len=1000, budget=1030, decode_steps=40, window=16),
     "fills_up": lambda: small("fills_up", prompt_len=20, budget=48, decode_steps=60, window=8),       # T < B: free slots first
     "empty_start": lambda: small("empty_start", prompt_len=0, budget=24, decode_steps=50, n_residual=2, window=4),
     "ragged_multi_layer": lambda: small("ragged_multi_layer", n_layers=2, n_seqs=3, dtype="f16", head_dim=128,
@@ -100,6 +107,11 @@ def test_decode_from_oracle_state(case):
     print(f"[case] {case} {wl.name} units={wl.n_units} B={wl.slot_capacity} steps={wl.decode_steps}", flush=True)
     units = oracle_states(wl)
     cache = pu.make_cache(wl, DEV)
+    if case.startswith("wide_") or "two_output_slots" in case:
+        # these cases are about the kernels that keep a whole unit in one workgroup (launches of so few units are
+        # cut over workgroups otherwise)
+        cache.set_decode_parts(1)
+        assert cache.decode_parts() == 1
     for l in range(wl.n_layers):
         cache.import_layer(l, **pu.pack_states(units[l], cache.cap, cache.B_r, wl.head_dim, cache.kv_dtype))
     pu.compare_all_state(wl, cache, units, pu.tol_for(wl.dtype), "after import")
@@ -115,7 +127,9 @@ def test_decode_from_oracle_state(case):
 # (case, workgroups per unit): the split step must give the oracle's decisions and outputs whatever the cut
 SPLIT_CASES = [("cfg1", 4), ("cfg1", 13), ("three_residual_f16", 2), ("alpha_half_bf16_gqa4", 3), ("gqa8_f32_d128", 2),
                ("fills_up", 2), ("gqa4_f16_many_tiles", 2), ("gqa8_bf16_d128", 3), ("empty_start", 3), ("ragged_multi_layer", 5), ("evict_only", 3), ("cfg0", 3),
-               ("residual_40_f16", 3), ("residual_20_f32_gqa4", 2), ("gqa7_bf16_d128", 3), ("gqa3_f32_d64", 2)]
+               ("residual_40_f16", 3), ("residual_20_f32_gqa4", 2), ("gqa7_bf16_d128", 3), ("gqa3_f32_d64", 2),
+               # large budgets cut as finely as a launch of one or two units is by default
+               ("wide_wg16_g1_b12000", 64), ("wide_wg12_gqa4_f16", 21), ("wide_wg8_gqa8_bf16", 11), ("gqa8_two_output_slots_bf16", 8)]
 
 
 @pytest.mark.parametrize("case,parts", SPLIT_CASES)
