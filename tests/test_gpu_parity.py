@@ -420,6 +420,39 @@ def test_random_shapes_other_group_sizes(seed):
     cache.close()
 
 
+@pytest.mark.parametrize("seed", list(range(16)))
+def test_random_large_shapes_one_workgroup_per_unit(seed):
+    """Seeded sweep over large budgets with one workgroup per unit forced: the kernels of 8, 12 and 16 waves that
+    run where the per-slot values leave room for one workgroup per compute unit, and (5 to 8 query heads, budgets
+    around 1024) the variant that stages the waves' outputs in two LDS slots."""
+    import random
+    from paper_2503_10714_amd import binding as zb
+    r = random.Random(9000 + seed)
+    dtype = r.choice(["f32", "f16", "bf16"]); d = r.choice([64, 128]); G = r.choice([1, 1, 2, 3, 4, 4, 5, 7, 8, 8])
+    n_res = r.choice([0, 1, 3, 12, 27])
+    bmax = min(19000, int(150000 / (8 * (G if G <= 2 else (4 if G <= 4 else 8)))))      # G' * (B + 1) * 8 bytes fill the LDS
+    budget = r.randint(max(300, bmax // 8), bmax)
+    if G >= 5 and r.random() < 0.4:
+        budget = r.randint(1000, 1160)
+    T = budget + r.randint(50, 300)
+    wl = synth.Workload(name=f"wide{seed}", n_layers=1, n_seqs=1, n_kv_heads=r.choice([1, 2]), q_per_kv=G, head_dim=d, dtype=dtype,
+                        prompt_len=T, budget=budget, decode_steps=6, window=r.choice([8, 32]), outliers=r.random() < 0.5,
+                        n_residual=n_res, seed=synth.MASTER_SEED + 9000 + seed)
+    print(f"[case] wide {seed}: {dtype} d={d} G={G} B_r={n_res} T={T} B={budget} H={wl.n_kv_heads}", flush=True)
+    cache, units = prefill_gpu_and_oracle(wl, gen_device="cpu")
+    pu.compare_all_state(wl, cache, units, pu.tol_for(wl.dtype), "after prefill")
+    cache.set_decode_parts(1)
+    try:
+        assert cache.decode_parts() == 1
+    except zb.ZsmError:
+        cache.close()
+        pytest.skip("one workgroup cannot hold this budget")
+    st = pu.run_decode_parity(wl, cache, units, 5, state_every=0)
+    print(f"[done] wide {seed}: evictions={st.evictions} near_ties={st.near_ties} max|out err|={st.max_out_err:.2e}", flush=True)
+    assert st.near_ties == 0
+    cache.close()
+
+
 def test_prefill_workspace_size():
     """The workspace holds the kept softmax numerators of as many units as fit 1 GiB (8 bytes per window row and
     key), never more, and none when the window covers half the prompt or more (those calls sweep K twice)."""
