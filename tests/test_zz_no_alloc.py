@@ -49,7 +49,7 @@ def _same_state(wl, ref, sta):
 
 
 def test_static_scratch_entry_point_matches_the_ordinary_one():
-    big = synth.Workload(name="noalloc_big", n_layers=2, n_seqs=2, n_kv_heads=3, q_per_kv=2, head_dim=128, dtype="f16",
+    big = synth.Workload(name="noalloc_big", n_layers=2, n_seqs=2, n_kv_heads=3, q_per_kv=3, head_dim=128, dtype="f16",
                          prompt_len=700, budget=301, decode_steps=6, window=16, outliers=True, n_residual=2)
     small = synth.Workload(name="noalloc_small", n_layers=1, n_seqs=1, n_kv_heads=2, q_per_kv=1, head_dim=64, dtype="f32",
                            prompt_len=150, budget=70, decode_steps=6, window=8, outliers=False)
