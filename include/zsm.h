@@ -55,12 +55,16 @@ enum zsm_flag {
     ZSM_FLAG_PREFILL_SPREAD = 2   /* zsm_prefill_compress met a logit beyond its range (see there) */
 };
 
+#define ZSM_MAX_Q_PER_KV 128
+
 typedef struct {
     int32_t n_layers;       /* L                                                        */
     int32_t n_seqs;         /* S: sequences in the batch                                */
     int32_t n_kv_heads;     /* H: KV heads per layer                                    */
-    int32_t q_per_kv;       /* G: query heads sharing one KV head, 1 to 8 (3 runs the   */
-                            /* kernels of 4, and 5 to 7 those of 8, at their cost)      */
+    int32_t q_per_kv;       /* G: query heads sharing one KV head, 1 to                 */
+                            /* ZSM_MAX_Q_PER_KV (3 runs the kernels of 4, 5 to 7 those  */
+                            /* of 8, at their cost; more than 8, multi-query models:    */
+                            /* the decode step sweeps the unit once per 8 heads)        */
     int32_t head_dim;       /* d: 64 or 128                                             */
     int32_t slot_capacity;  /* slot stride: max over sequences of B_r + B_c + B_p       */
     int32_t n_residual;     /* B_r (0 = pure eviction, Sec. 3.2)                        */
@@ -173,6 +177,11 @@ int zsm_prefill_compress(zsm_cache_t* cache, int32_t layer_begin, int32_t layer_
  * partial softmax sums and outputs meet in a scratch area inside the cache buffer; the
  * result does not depend on the cut beyond fp32 rounding of the output (scores, choices
  * and merged rows are formed in fp64 from the same per-slot values either way).
+ * More than 8 query heads per KV head: the step runs as ceil(G / 8) sweeps of the unit's slots, 8
+ * heads each, whose per-slot probabilities are pooled in the cache buffer's scratch section, and a
+ * finishing launch; such a step is never cut over workgroups (zsm_cache_set_decode_parts has no
+ * effect), so the limit below applies whatever the launch, with G' = 4 (the sweeps then take 4
+ * heads each where 8 do not fit).
  * Positions are kept as int32: a unit may see at most 2^31 - 1 tokens in all.
  * Limit: the per-slot values of one workgroup, (slots + 1) * G' * 8 bytes (G' = G rounded up
  * to 1, 2, 4 or 8), must fit the 160 KB LDS together with ~24 KB of staging; a capacity too large for one workgroup is

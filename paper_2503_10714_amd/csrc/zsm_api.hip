@@ -43,7 +43,7 @@ bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 
 bool config_ok(const zsm_config_t* c) {
     if (!c) return false;
     if (c->n_layers < 1 || c->n_seqs < 1 || c->n_kv_heads < 1) return false;
-    if (c->q_per_kv < 1 || c->q_per_kv > 8) return false;
+    if (c->q_per_kv < 1 || c->q_per_kv > ZSM_MAX_Q_PER_KV) return false;
     if (!(c->head_dim == 64 || c->head_dim == 128)) return false;
     if (c->n_residual < 0 || c->slot_capacity < c->n_residual + 1) return false;
     if (!(c->lambda >= 0.f && c->lambda <= 1.f) || !(c->alpha >= 0.f && c->alpha <= 1.f)) return false;
@@ -195,6 +195,14 @@ int run_state_check(zsm_cache_t* c, hipStream_t st, Launch launch, const char* w
 // must hold), or a negative status when no permitted cut fits the LDS.
 int choose_parts(const zsm_cache_t* cache, int n_units, int* part_rows) {
     const CacheView& v = cache->cv;
+    if (v.G > 8) {   // shares of eight heads, each one workgroup per unit: never cut over workgroups
+        *part_rows = 0;
+        auto lds_of = [&](int heads) {
+            return v.dtype == ZSM_F32 ? decode_lds_f32(v.D, heads, v.cap + 1)
+                                      : (v.dtype == ZSM_F16 ? decode_lds_f16(v.D, heads, v.cap + 1) : decode_lds_bf16(v.D, heads, v.cap + 1));
+        };
+        return lds_of(8) <= 160 * 1024 || lds_of(4) <= 160 * 1024 ? 1 : ZSM_E_SHAPE;   // shares of eight heads, else of four
+    }
     auto lds_of = [&](int nz) {
         switch (v.dtype) {
             case ZSM_F32: return decode_lds_f32(v.D, v.G, nz);
@@ -348,8 +356,36 @@ static int decode_step_impl(zsm_cache_t* cache, int32_t layer_begin, int32_t lay
     a.part_rows = part_rows;
     a.q = q; a.k_new = k_new; a.v_new = v_new; a.out = out;
     a.write_slot = write_slot; a.evicted_pos = evicted_pos; a.merged_slot = merged_slot;
+    a.pool = nullptr; a.q_heads = v.G; a.head0 = 0; a.heads = v.G;
     hipStream_t st = static_cast<hipStream_t>(stream);
     hipError_t e;
+    if (v.G > 8) {
+        // Groups of more than eight query heads: shares of eight, their per-slot sums pooled in the scratch section
+        // of the cache buffer (sized for sp_max_units units of eight heads: eight times as many pooled units), in
+        // launches of as many units as that holds.
+        const size_t es = esize(v.dtype);
+        const int per_launch = v.sp_max_units * 8;
+        for (int u0 = 0; u0 < n_units; u0 += per_launch) {
+            DecodeArgs b = a;
+            b.unit0 = a.unit0 + u0;
+            b.n_units = n_units - u0 < per_launch ? n_units - u0 : per_launch;
+            b.pool = v.sp_E;
+            b.q = static_cast<const char*>(q) + (size_t)u0 * v.G * v.D * es;
+            b.k_new = static_cast<const char*>(k_new) + (size_t)u0 * v.D * es;
+            b.v_new = static_cast<const char*>(v_new) + (size_t)u0 * v.D * es;
+            b.out = out + (size_t)u0 * v.G * v.D;
+            b.write_slot = write_slot ? write_slot + u0 : nullptr;
+            b.evicted_pos = evicted_pos ? evicted_pos + u0 : nullptr;
+            b.merged_slot = merged_slot ? merged_slot + u0 : nullptr;
+            switch (v.dtype) {
+                case ZSM_F32: e = launch_decode_pooled_f32(b, st); break;
+                case ZSM_F16: e = launch_decode_pooled_f16(b, st); break;
+                default: e = launch_decode_pooled_bf16(b, st); break;
+            }
+            if (e != hipSuccess) return hip_fail(e, "zsm_decode_step launch (pooled heads)");
+        }
+        return ZSM_OK;
+    }
     switch (v.dtype) {
         case ZSM_F32: e = launch_decode_f32(a, st); break;
         case ZSM_F16: e = launch_decode_f16(a, st); break;

@@ -43,6 +43,10 @@ struct DecodeArgs {
     int32_t* merged_slot;
     int32_t parts;      // workgroups per unit (1: the whole unit in one workgroup)
     int32_t part_rows;  // parts > 1: token rows the LDS of one part holds (a whole number of wave tiles)
+    // Groups of more than eight query heads (decode_kernel's POOL): a launch covers `heads` of the unit's
+    // `q_heads` query heads, from `head0` on
+    double* pool;       // [n_units][cap + 1]: per slot (the incoming token last), the sum over the heads so far of e / L
+    int32_t q_heads, head0, heads;
 };
 
 template <typename T, int D, int G, int NW>
@@ -739,13 +743,18 @@ __device__ __forceinline__ void decode_finish(const DecodeArgs& a, const CacheVi
 //
 // AW: LDS slots for the waves' partial outputs after pass 2: one per wave, or fewer, the waves then handing
 // their outputs over AW at a time.
-template <typename T, int D, int G, int NW, bool SPLIT, int AW = NW>
+// POOL: the launch handles a share of at most G (eight, or four where eight heads' per-slot values do not fit the
+//   LDS) of a unit's query heads (groups larger than eight: a.heads heads from a.head0 on).  It writes their outputs and adds, per slot, the sum over its heads of e / L to
+//   a.pool (the first share stores); the cache is not touched.  decode_pool_finish_kernel, launched behind the
+//   last share, divides by the number of heads (the head mean of Eq. 3's grouped-query form) and runs D3-D6.
+template <typename T, int D, int G, int NW, bool SPLIT, int AW = NW, bool POOL = false>
 __global__ __launch_bounds__(NW * 64, G == 1 ? 4 : (NW == 12 ? 3 : 2)) void decode_kernel(DecodeArgs a) {
+    static_assert(!POOL || (!SPLIT && (G == 8 || G == 4)), "shares of a large group run the eight- or four-head kernel, one workgroup per unit");
     using Sh = DecodeShape<T, D, G, NW>;
     constexpr int EPL = Sh::EPL, LPR = Sh::LPR, RPL = Sh::RPL, R = Sh::R, PART = Sh::PART, NT = Sh::NT, UT = Sh::UT;
     constexpr bool QLDS = Sh::QLDS;
     const CacheView& cv = a.cv;
-    const int Gr = real_heads<G>(cv);
+    const int Gr = POOL ? a.heads : real_heads<G>(cv);
     const int lu = SPLIT ? (int)blockIdx.x / a.parts : (int)blockIdx.x;
     const int part = SPLIT ? (int)blockIdx.x % a.parts : 0;
     const int ug = a.unit0 + lu;
@@ -802,7 +811,8 @@ __global__ __launch_bounds__(NW * 64, G == 1 ? 4 : (NW == 12 ? 3 : 2)) void deco
         if constexpr (MF) tile_load_mfma4<T, UT, D, EPL>(bufA, Kt, wave * R, cv.cap_tok, lane);
         else tile_load<T, UT, D, EPL, LPR, RPL>(bufA, Kt, wave * R, cv.cap_tok, klane);
     }
-    const T* qp = reinterpret_cast<const T*>(a.q) + (size_t)lu * Gr * D;
+    const size_t head_off = POOL ? (size_t)lu * a.q_heads + a.head0 : (size_t)lu * Gr;   // this launch's first head in q and out
+    const T* qp = reinterpret_cast<const T*>(a.q) + head_off * D;
     const T* knew = reinterpret_cast<const T*>(a.k_new) + (size_t)lu * D;
     const T* vnew = reinterpret_cast<const T*>(a.v_new) + (size_t)lu * D;
     const long long Tseen = cv.n_seen[ug];
@@ -1026,7 +1036,7 @@ __global__ __launch_bounds__(NW * 64, G == 1 ? 4 : (NW == 12 ? 3 : 2)) void deco
     // the values do not fit the register budget and the spill makes every wave wait for them.)
     UnitRefs<T> u{Kt, Vt, Kr, Vr, s, pos, w, knew, vnew};
     FinishPre<T, D, NW> pre;
-    if (!SPLIT) pre.load(u, cv.cap, Br);
+    if (!SPLIT && !POOL) pre.load(u, cv.cap, Br);
     // ---- combine the waves' partial outputs ----------------------------------------------
     // (fewer slots than waves: waves r*AW .. r*AW + AW - 1 take round r; the first round stores, the later ones add)
 #pragma unroll
@@ -1051,9 +1061,20 @@ __global__ __launch_bounds__(NW * 64, G == 1 ? 4 : (NW == 12 ? 3 : 2)) void deco
             float o = 0.f;
 #pragma unroll
             for (int x = 0; x < AW; ++x) o += accw[x * G * D + idx];
-            a.out[(size_t)lu * Gr * D + idx] = o;
+            a.out[head_off * D + idx] = o;
         }
-        decode_finish<T, D, G, NW, 0>(a, cv, u, lu, ug, Bp, Br, B, Tseen, nocc, full, et, Bz, rL, pre, keyw, dotw, misc);
+        if constexpr (POOL) {
+            // slot j's exponentials sit at et[g][j], the incoming token's at et[g][B] (one workgroup per unit)
+            double* pool = a.pool + (size_t)lu * (cv.cap + 1);
+            for (int j = tid; j <= B; j += NT) {
+                double pm = 0.0;
+#pragma unroll
+                for (int g = 0; g < G; ++g) pm += et[(size_t)g * Bz + j] * rL[g];   // 1/L of the heads past the last is 0
+                pool[j] = a.head0 == 0 ? pm : pool[j] + pm;
+            }
+        } else {
+            decode_finish<T, D, G, NW, 0>(a, cv, u, lu, ug, Bp, Br, B, Tseen, nocc, full, et, Bz, rL, pre, keyw, dotw, misc);
+        }
         return;
     }
 
@@ -1169,6 +1190,43 @@ __global__ __launch_bounds__(NW * 64) void decode_combine_kernel(DecodeArgs a) {
     decode_finish<T, D, G, NW, G>(a, cv, u, lu, ug, Bp, Br, B, Tseen, nocc, full, Eu, BzG, rL, pre, keyw, dotw, misc);
 }
 
+// Last kernel of a step over groups of more than eight query heads, one workgroup per unit: the per-slot sums the
+// shares left in a.pool become the head mean (sum / G, as the appendix's grouped-query adaptation pools the heads),
+// then D3-D6 as for a single head whose probabilities are those means.
+template <typename T, int D, int NW>
+__global__ __launch_bounds__(NW * 64) void decode_pool_finish_kernel(DecodeArgs a) {
+    constexpr int NT = NW * 64;
+    const CacheView& cv = a.cv;
+    const int lu = blockIdx.x;
+    const int ug = a.unit0 + lu;
+    const int b = (ug / cv.H) % cv.S;
+    const int tid = threadIdx.x;
+    const int Br = cv.Br;
+    __shared__ unsigned long long keyw[NW];
+    __shared__ double dotw[NW];
+    __shared__ int misc[4 + NW];
+    T* Kt = reinterpret_cast<T*>(cv.Kt) + (size_t)ug * cv.cap_tok * D;
+    T* Vt = reinterpret_cast<T*>(cv.Vt) + (size_t)ug * cv.cap_tok * D;
+    UnitRefs<T> u{Kt, Vt, cv.Kr + (size_t)ug * Br * D, cv.Vr + (size_t)ug * Br * D, cv.s + (size_t)ug * cv.cap,
+                  cv.pos + (size_t)ug * cv.cap, cv.w + (size_t)ug * cv.cap,
+                  reinterpret_cast<const T*>(a.k_new) + (size_t)lu * D, reinterpret_cast<const T*>(a.v_new) + (size_t)lu * D};
+    FinishPre<T, D, NW> pre;
+    pre.load(u, cv.cap, Br);
+    const int Bp = cv.Bp[b], Bc = cv.Bc[b];
+    const int ntok = Bp + Bc, B = ntok + Br;
+    const long long Tseen = cv.n_seen[ug];
+    const int nocc = cv.n_occ[ug];
+    const bool full = nocc == ntok;
+    if (tid == 0) { misc[0] = -1; misc[2] = 0x7fffffff; }
+    double* pool = a.pool + (size_t)lu * (cv.cap + 1);
+    const double heads = (double)a.q_heads;
+    for (int j = tid; j <= B; j += NT) pool[j] = pool[j] / heads;
+    __threadfence_block();
+    __syncthreads();
+    const double one[1] = {1.0};
+    decode_finish<T, D, 1, NW, 0>(a, cv, u, lu, ug, Bp, Br, B, Tseen, nocc, full, pool, cv.cap + 1, one, pre, keyw, dotw, misc);
+}
+
 // Host side: pick the instantiation for (D, G) and launch.
 constexpr int DECODE_NW = 4;
 constexpr size_t DECODE_LDS_MAX = 160 * 1024;   // LDS of one compute unit
@@ -1276,6 +1334,59 @@ inline hipError_t launch_decode_t(const DecodeArgs& a, hipStream_t stream) {
     return hipErrorInvalidValue;
 }
 
+// A step over groups of more than eight query heads: one launch per share of GS heads (the eight-head kernel, or
+// the four-head kernel where the per-slot values of eight heads do not fit the LDS), then the finishing kernel.
+// a.q_heads, a.pool, a.n_units, a.unit0 and the tensors are set by the caller.
+template <typename T, int D, int GS>
+inline hipError_t launch_decode_pooled_share(DecodeArgs a, hipStream_t stream) {
+    using Sh = DecodeShape<T, D, GS, DECODE_NW>;
+    const size_t lds = Sh::lds_bytes(a.cv.cap + 1);
+    auto kern = decode_kernel<T, D, GS, DECODE_NW, false, DECODE_NW, true>;
+    static std::atomic<unsigned long long> attr_done{0ull};
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    const unsigned long long bit = 1ull << (dev & 63);
+    if (!(attr_done.load(std::memory_order_acquire) & bit)) {
+        e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+        if (e != hipSuccess) return e;
+        attr_done.fetch_or(bit, std::memory_order_release);
+    }
+    a.parts = 1;
+    a.part_rows = 0;
+    for (int h0 = 0; h0 < a.q_heads; h0 += GS) {
+        a.head0 = h0;
+        a.heads = a.q_heads - h0 < GS ? a.q_heads - h0 : GS;
+        hipLaunchKernelGGL(kern, dim3(a.n_units), dim3(DECODE_NW * 64), lds, stream, a);
+    }
+    hipLaunchKernelGGL((decode_pool_finish_kernel<T, D, DECODE_NW>), dim3(a.n_units), dim3(DECODE_NW * 64), 0, stream, a);
+    return hipGetLastError();
+}
+
+// heads per share of a pooled step: 8, or 4 where only that fits one workgroup's LDS (0: neither does)
+template <typename T, int D>
+inline int decode_pool_share_heads(int nz) {
+    if (DecodeShape<T, D, 8, DECODE_NW>::lds_bytes(nz) <= DECODE_LDS_MAX) return 8;
+    if (DecodeShape<T, D, 4, DECODE_NW>::lds_bytes(nz) <= DECODE_LDS_MAX) return 4;
+    return 0;
+}
+
+template <typename T, int D>
+inline hipError_t launch_decode_pooled_d(const DecodeArgs& a, hipStream_t stream) {
+    switch (decode_pool_share_heads<T, D>(a.cv.cap + 1)) {
+        case 8: return launch_decode_pooled_share<T, D, 8>(a, stream);
+        case 4: return launch_decode_pooled_share<T, D, 4>(a, stream);
+        default: return hipErrorInvalidValue;
+    }
+}
+
+template <typename T>
+inline hipError_t launch_decode_pooled_t(const DecodeArgs& a, hipStream_t stream) {
+    if (a.cv.D == 64) return launch_decode_pooled_d<T, 64>(a, stream);
+    if (a.cv.D == 128) return launch_decode_pooled_d<T, 128>(a, stream);
+    return hipErrorInvalidValue;
+}
+
 // LDS bytes of a launch that keeps `nz` per-slot values per query head in LDS
 template <typename T>
 inline size_t decode_lds_t(int D, int Gr, int nz) {
@@ -1291,6 +1402,9 @@ inline size_t decode_lds_t(int D, int Gr, int nz) {
 hipError_t launch_decode_f32(const DecodeArgs& a, hipStream_t stream);
 hipError_t launch_decode_f16(const DecodeArgs& a, hipStream_t stream);
 hipError_t launch_decode_bf16(const DecodeArgs& a, hipStream_t stream);
+hipError_t launch_decode_pooled_f32(const DecodeArgs& a, hipStream_t stream);
+hipError_t launch_decode_pooled_f16(const DecodeArgs& a, hipStream_t stream);
+hipError_t launch_decode_pooled_bf16(const DecodeArgs& a, hipStream_t stream);
 size_t decode_lds_f32(int D, int G, int nz);
 size_t decode_lds_f16(int D, int G, int nz);
 size_t decode_lds_bf16(int D, int G, int nz);

@@ -70,6 +70,18 @@ DECODE_CASES = {
     # thousands (Eq. 6 with a large w), scores decay over many steps (Eq. 3)
     "long_run_1500_steps": lambda: small("long_run", n_kv_heads=1, prompt_len=40, budget=24, n_residual=2, decode_steps=1500,
                                          window=8, dtype="f16", outliers=True),
+    # more than eight query heads per KV head (multi-query models): the step sweeps the unit once per eight heads and
+    # pools their per-slot probabilities; 12 = 8 + 4, 16 = 8 + 8 while the cache still fills up (masked tiles),
+    # 71 = 8 x 8 + 7 on one KV head of d = 64 (the multi-query model among the paper's three core models)
+    "mqa12_f16_d64": lambda: small("mqa12_f16_d64", dtype="f16", q_per_kv=12, n_kv_heads=2, n_residual=2, prompt_len=300,
+                                   budget=90, outliers=True),
+    "mqa16_f32_d128_fills_up": lambda: small("mqa16_fills_up", q_per_kv=16, head_dim=128, n_kv_heads=1, prompt_len=30, budget=64,
+                                             decode_steps=60, window=8),
+    "mqa71_bf16_d64": lambda: small("mqa71_bf16_d64", dtype="bf16", q_per_kv=71, n_kv_heads=1, n_seqs=2, n_residual=3,
+                                    prompt_len=400, budget=120, decode_steps=30, outliers=True),
+    # a budget at which eight heads' per-slot values do not fit the LDS: shares of four heads (13 = 4 + 4 + 4 + 1)
+    "mqa13_f16_b2700_shares_of_four": lambda: small("mqa13_b2700", dtype="f16", q_per_kv=13, head_dim=128, n_kv_heads=1, n_residual=2,
+                                                    prompt_len=2900, budget=2700, decode_steps=6, outliers=True),
     # eight (seven) query heads and a budget whose per-slot values leave room for two workgroups per compute unit only
     # if the waves stage their partial outputs in two LDS slots instead of four: the kernel variant that hands them
     # over in two rounds
@@ -285,6 +297,9 @@ FULL_CASES = {
     # the decode step on the kernels compiled for eight
     "gqa7_prompt_then_decode": (lambda: small("gqa7_full", dtype="bf16", q_per_kv=7, head_dim=128, n_kv_heads=4, n_seqs=2,
                                               prompt_len=600, budget=96, window=32, n_residual=2, outliers=True), 40),
+    # 71 query heads on one KV head: prompt scores pooled over 71 heads, then the pooled decode step
+    "mqa71_prompt_then_decode": (lambda: small("mqa71_full", dtype="f16", q_per_kv=71, n_kv_heads=1, n_layers=2,
+                                               prompt_len=500, budget=80, window=32, n_residual=2, outliers=True), 32),
     # a batch of prompts between 0 and 5 tokens long (three of the eight are empty), then enough steps to fill
     # the slots and evict
     "ragged_with_empty_prompts": (lambda: small("ragged_empty", n_seqs=8, prompt_len=5, ragged=(0, 5), budget=12, window=8,
@@ -417,6 +432,24 @@ def test_random_shapes_other_group_sizes(seed):
     st = pu.run_decode_parity(wl, cache, units, 12, state_every=0, first_step=12)
     print(f"[done] random {100 + seed}: unit-steps={st0.unit_steps + st.unit_steps} evictions={st0.evictions + st.evictions} "
           f"near_ties={st0.near_ties + st.near_ties} max|out err|={max(st0.max_out_err, st.max_out_err):.2e}", flush=True)
+    cache.close()
+
+
+@pytest.mark.parametrize("seed", list(range(8)))
+def test_random_shapes_large_groups(seed):
+    """The same sweep with more than eight query heads per KV head (the pooled decode step)."""
+    wl = random_workload(200 + seed).sliced(q_per_kv=[9, 12, 16, 20, 33, 40, 71, 128][seed])
+    bp, bc, br = wl.budgets()
+    print(f"[case] random {200 + seed}: {wl.dtype} d={wl.head_dim} G={wl.q_per_kv} B_r={br} T={wl.seq_lens()} B_p={bp} B_c={bc} "
+          f"W={wl.window} L={wl.n_layers} H={wl.n_kv_heads} alpha={wl.alpha}", flush=True)
+    if min(p for p in bp) < 1 or min(c for c in bc) < 0:
+        pytest.skip("drawn budget leaves no proximity slot")
+    cache, units = prefill_gpu_and_oracle(wl, gen_device="cpu")
+    pu.compare_all_state(wl, cache, units, pu.tol_for(wl.dtype), "after prefill")
+    assert cache.decode_parts() == 1
+    st = pu.run_decode_parity(wl, cache, units, 24, state_every=0)
+    print(f"[done] random {200 + seed}: unit-steps={st.unit_steps} evictions={st.evictions} near_ties={st.near_ties} "
+          f"max|out err|={st.max_out_err:.2e}", flush=True)
     cache.close()
 
 
