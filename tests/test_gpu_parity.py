@@ -79,6 +79,9 @@ DECODE_CASES = {
                                              decode_steps=60, window=8),
     "mqa71_bf16_d64": lambda: small("mqa71_bf16_d64", dtype="bf16", q_per_kv=71, n_kv_heads=1, n_seqs=2, n_residual=3,
                                     prompt_len=400, budget=120, decode_steps=30, outliers=True),
+    # more units than the pooled sums of one launch have room for (8 x 1024): the step goes out as two launches per share
+    "mqa9_8256_units": lambda: small("mqa9_many_units", q_per_kv=9, n_seqs=129, n_kv_heads=64, prompt_len=0, budget=6, n_residual=1,
+                                     decode_steps=9, window=4),
     # a budget at which eight heads' per-slot values do not fit the LDS: shares of four heads (13 = 4 + 4 + 4 + 1)
     "mqa13_f16_b2700_shares_of_four": lambda: small("mqa13_b2700", dtype="f16", q_per_kv=13, head_dim=128, n_kv_heads=1, n_residual=2,
                                                     prompt_len=2900, budget=2700, decode_steps=6, outliers=True),
