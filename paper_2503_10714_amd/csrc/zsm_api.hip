@@ -68,14 +68,32 @@ struct Layout {
 // Scratch of a split decode launch of n_wgs workgroups over n_units units: offsets from a
 // 256-byte aligned base, and the total.
 struct SplitScratch { size_t L, acc, E, total; };
-SplitScratch split_scratch(size_t n_wgs, size_t n_units, size_t G, size_t D, size_t cap) {
+// (e_slices: arrays of cap + 1 doubles per unit in E; G of them for a split launch, one per share of heads for a
+// step over more than eight query heads)
+SplitScratch split_scratch(size_t n_wgs, size_t n_units, size_t G, size_t D, size_t cap, size_t e_slices = 0) {
     SplitScratch x{};
     size_t o = 0;
     x.L = o; o += up256(sizeof(double) * n_wgs * G);
     x.acc = o; o += up256(sizeof(float) * n_wgs * G * D);
-    x.E = o; o += up256(sizeof(double) * n_units * G * (cap + 1));
+    x.E = o; o += up256(sizeof(double) * n_units * (e_slices > G ? e_slices : G) * (cap + 1));
     x.total = o;
     return x;
+}
+
+// heads per workgroup of a step over more than eight query heads per KV head: 8, 4, or 0 where neither fits the LDS
+int pool_share_heads(int dtype, int D, int cap) {
+    switch (dtype) {
+        case ZSM_F32: return decode_pool_share_heads_f32(D, cap + 1);
+        case ZSM_F16: return decode_pool_share_heads_f16(D, cap + 1);
+        default: return decode_pool_share_heads_bf16(D, cap + 1);
+    }
+}
+
+// slices of pooled per-slot sums a unit needs (0: at most eight query heads, no pooled step)
+size_t pool_slices(const zsm_config_t& c) {
+    if (c.q_per_kv <= 8) return 0;
+    const int gs = pool_share_heads(c.kv_dtype, c.head_dim, c.slot_capacity);
+    return gs > 0 ? (size_t)(c.q_per_kv + gs - 1) / gs : 0;
 }
 
 Layout make_layout(const zsm_config_t& c) {
@@ -98,7 +116,8 @@ Layout make_layout(const zsm_config_t& c) {
     l.Vt = o; o += up256(esize(c.kv_dtype) * units * (cap - Br) * D);
     l.sp_max_units = (int)(units < (size_t)SP_MAX_UNITS ? units : (size_t)SP_MAX_UNITS);
     l.sp_max_wgs = l.sp_max_units * SP_MAX_PARTS < SP_MAX_WGS ? l.sp_max_units * SP_MAX_PARTS : SP_MAX_WGS;
-    const SplitScratch sp = split_scratch(l.sp_max_wgs, l.sp_max_units, decode_compiled_heads(c.q_per_kv), D, cap);
+    const SplitScratch sp = split_scratch(l.sp_max_wgs, l.sp_max_units, decode_compiled_heads(c.q_per_kv), D, cap,
+                                          pool_slices(c));
     l.sp_L = o + sp.L; l.sp_acc = o + sp.acc; l.sp_E = o + sp.E;
     o += sp.total;
     l.total = o;
@@ -193,15 +212,13 @@ int run_state_check(zsm_cache_t* c, hipStream_t st, Launch launch, const char* w
 
 // Workgroups per unit for a decode launch of n_units units (and the token rows one part's LDS
 // must hold), or a negative status when no permitted cut fits the LDS.
+int pool_share_heads(const CacheView& v) { return pool_share_heads(v.dtype, v.D, v.cap); }
+
 int choose_parts(const zsm_cache_t* cache, int n_units, int* part_rows) {
     const CacheView& v = cache->cv;
     if (v.G > 8) {   // shares of eight heads, each one workgroup per unit: never cut over workgroups
         *part_rows = 0;
-        auto lds_of = [&](int heads) {
-            return v.dtype == ZSM_F32 ? decode_lds_f32(v.D, heads, v.cap + 1)
-                                      : (v.dtype == ZSM_F16 ? decode_lds_f16(v.D, heads, v.cap + 1) : decode_lds_bf16(v.D, heads, v.cap + 1));
-        };
-        return lds_of(8) <= 160 * 1024 || lds_of(4) <= 160 * 1024 ? 1 : ZSM_E_SHAPE;   // shares of eight heads, else of four
+        return pool_share_heads(v) > 0 ? 1 : ZSM_E_SHAPE;   // shares of eight heads, else of four
     }
     auto lds_of = [&](int nz) {
         switch (v.dtype) {
@@ -356,15 +373,17 @@ static int decode_step_impl(zsm_cache_t* cache, int32_t layer_begin, int32_t lay
     a.part_rows = part_rows;
     a.q = q; a.k_new = k_new; a.v_new = v_new; a.out = out;
     a.write_slot = write_slot; a.evicted_pos = evicted_pos; a.merged_slot = merged_slot;
-    a.pool = nullptr; a.q_heads = v.G; a.head0 = 0; a.heads = v.G;
+    a.pool = nullptr; a.q_heads = v.G; a.n_shares = 1;
     hipStream_t st = static_cast<hipStream_t>(stream);
     hipError_t e;
     if (v.G > 8) {
-        // Groups of more than eight query heads: shares of eight, their per-slot sums pooled in the scratch section
-        // of the cache buffer (sized for sp_max_units units of eight heads: eight times as many pooled units), in
-        // launches of as many units as that holds.
+        // Groups of more than eight query heads: one workgroup per unit and share of eight (or four) heads, the
+        // shares' per-slot sums in the scratch section of the cache buffer, in launches of as many units as that
+        // holds.
         const size_t es = esize(v.dtype);
-        const int per_launch = v.sp_max_units * 8;
+        const int gs = pool_share_heads(v);   // > 0: choose_parts has checked
+        a.n_shares = (v.G + gs - 1) / gs;
+        const int per_launch = v.sp_max_units;   // the scratch holds n_shares slices for each of that many units
         for (int u0 = 0; u0 < n_units; u0 += per_launch) {
             DecodeArgs b = a;
             b.unit0 = a.unit0 + u0;

@@ -43,10 +43,10 @@ struct DecodeArgs {
     int32_t* merged_slot;
     int32_t parts;      // workgroups per unit (1: the whole unit in one workgroup)
     int32_t part_rows;  // parts > 1: token rows the LDS of one part holds (a whole number of wave tiles)
-    // Groups of more than eight query heads (decode_kernel's POOL): a launch covers `heads` of the unit's
-    // `q_heads` query heads, from `head0` on
-    double* pool;       // [n_units][cap + 1]: per slot (the incoming token last), the sum over the heads so far of e / L
-    int32_t q_heads, head0, heads;
+    // Groups of more than eight query heads (decode_kernel's POOL): the unit's q_heads query heads are dealt to
+    // n_shares workgroups, G (the kernel's compiled group size) each
+    double* pool;       // [n_units][n_shares][cap + 1]: per share and slot (the incoming token last), the sum over the share's heads of e / L
+    int32_t q_heads, n_shares;
 };
 
 template <typename T, int D, int G, int NW>
@@ -743,10 +743,11 @@ __device__ __forceinline__ void decode_finish(const DecodeArgs& a, const CacheVi
 //
 // AW: LDS slots for the waves' partial outputs after pass 2: one per wave, or fewer, the waves then handing
 // their outputs over AW at a time.
-// POOL: the launch handles a share of at most G (eight, or four where eight heads' per-slot values do not fit the
-//   LDS) of a unit's query heads (groups larger than eight: a.heads heads from a.head0 on).  It writes their outputs and adds, per slot, the sum over its heads of e / L to
-//   a.pool (the first share stores); the cache is not touched.  decode_pool_finish_kernel, launched behind the
-//   last share, divides by the number of heads (the head mean of Eq. 3's grouped-query form) and runs D3-D6.
+// POOL: groups of more than eight query heads.  a.n_shares workgroups per unit, each with a share of G (eight, or
+//   four where eight heads' per-slot values do not fit the LDS) of the unit's a.q_heads query heads.  A workgroup
+//   writes its heads' outputs and leaves, per slot, the sum over its heads of e / L in its slice of a.pool; the
+//   cache is not touched.  decode_pool_finish_kernel, launched behind it, adds the shares up in order, divides by
+//   the number of heads (the head mean of Eq. 3's grouped-query form) and runs D3-D6.
 template <typename T, int D, int G, int NW, bool SPLIT, int AW = NW, bool POOL = false>
 __global__ __launch_bounds__(NW * 64, G == 1 ? 4 : (NW == 12 ? 3 : 2)) void decode_kernel(DecodeArgs a) {
     static_assert(!POOL || (!SPLIT && (G == 8 || G == 4)), "shares of a large group run the eight- or four-head kernel, one workgroup per unit");
@@ -754,8 +755,9 @@ __global__ __launch_bounds__(NW * 64, G == 1 ? 4 : (NW == 12 ? 3 : 2)) void deco
     constexpr int EPL = Sh::EPL, LPR = Sh::LPR, RPL = Sh::RPL, R = Sh::R, PART = Sh::PART, NT = Sh::NT, UT = Sh::UT;
     constexpr bool QLDS = Sh::QLDS;
     const CacheView& cv = a.cv;
-    const int Gr = POOL ? a.heads : real_heads<G>(cv);
-    const int lu = SPLIT ? (int)blockIdx.x / a.parts : (int)blockIdx.x;
+    const int share = POOL ? (int)blockIdx.x % a.n_shares : 0;
+    const int Gr = POOL ? (a.q_heads - share * G < G ? a.q_heads - share * G : G) : real_heads<G>(cv);
+    const int lu = SPLIT ? (int)blockIdx.x / a.parts : (POOL ? (int)blockIdx.x / a.n_shares : (int)blockIdx.x);
     const int part = SPLIT ? (int)blockIdx.x % a.parts : 0;
     const int ug = a.unit0 + lu;
     const int b = (ug / cv.H) % cv.S;
@@ -811,7 +813,7 @@ __global__ __launch_bounds__(NW * 64, G == 1 ? 4 : (NW == 12 ? 3 : 2)) void deco
         if constexpr (MF) tile_load_mfma4<T, UT, D, EPL>(bufA, Kt, wave * R, cv.cap_tok, lane);
         else tile_load<T, UT, D, EPL, LPR, RPL>(bufA, Kt, wave * R, cv.cap_tok, klane);
     }
-    const size_t head_off = POOL ? (size_t)lu * a.q_heads + a.head0 : (size_t)lu * Gr;   // this launch's first head in q and out
+    const size_t head_off = POOL ? (size_t)lu * a.q_heads + share * G : (size_t)lu * Gr;   // this workgroup's first head in q and out
     const T* qp = reinterpret_cast<const T*>(a.q) + head_off * D;
     const T* knew = reinterpret_cast<const T*>(a.k_new) + (size_t)lu * D;
     const T* vnew = reinterpret_cast<const T*>(a.v_new) + (size_t)lu * D;
@@ -1065,12 +1067,12 @@ __global__ __launch_bounds__(NW * 64, G == 1 ? 4 : (NW == 12 ? 3 : 2)) void deco
         }
         if constexpr (POOL) {
             // slot j's exponentials sit at et[g][j], the incoming token's at et[g][B] (one workgroup per unit)
-            double* pool = a.pool + (size_t)lu * (cv.cap + 1);
+            double* pool = a.pool + ((size_t)lu * a.n_shares + share) * (cv.cap + 1);
             for (int j = tid; j <= B; j += NT) {
                 double pm = 0.0;
 #pragma unroll
                 for (int g = 0; g < G; ++g) pm += et[(size_t)g * Bz + j] * rL[g];   // 1/L of the heads past the last is 0
-                pool[j] = a.head0 == 0 ? pm : pool[j] + pm;
+                pool[j] = pm;
             }
         } else {
             decode_finish<T, D, G, NW, 0>(a, cv, u, lu, ug, Bp, Br, B, Tseen, nocc, full, et, Bz, rL, pre, keyw, dotw, misc);
@@ -1190,8 +1192,8 @@ __global__ __launch_bounds__(NW * 64) void decode_combine_kernel(DecodeArgs a) {
     decode_finish<T, D, G, NW, G>(a, cv, u, lu, ug, Bp, Br, B, Tseen, nocc, full, Eu, BzG, rL, pre, keyw, dotw, misc);
 }
 
-// Last kernel of a step over groups of more than eight query heads, one workgroup per unit: the per-slot sums the
-// shares left in a.pool become the head mean (sum / G, as the appendix's grouped-query adaptation pools the heads),
+// Second kernel of a step over groups of more than eight query heads, one workgroup per unit: the per-slot sums the
+// shares left in a.pool are added up in the order of the heads and become the head mean (sum / G, as the appendix's grouped-query adaptation pools the heads),
 // then D3-D6 as for a single head whose probabilities are those means.
 template <typename T, int D, int NW>
 __global__ __launch_bounds__(NW * 64) void decode_pool_finish_kernel(DecodeArgs a) {
@@ -1218,9 +1220,13 @@ __global__ __launch_bounds__(NW * 64) void decode_pool_finish_kernel(DecodeArgs 
     const int nocc = cv.n_occ[ug];
     const bool full = nocc == ntok;
     if (tid == 0) { misc[0] = -1; misc[2] = 0x7fffffff; }
-    double* pool = a.pool + (size_t)lu * (cv.cap + 1);
+    double* pool = a.pool + (size_t)lu * a.n_shares * (cv.cap + 1);   // the sums end up in the first share's slice
     const double heads = (double)a.q_heads;
-    for (int j = tid; j <= B; j += NT) pool[j] = pool[j] / heads;
+    for (int j = tid; j <= B; j += NT) {
+        double t = pool[j];
+        for (int sh = 1; sh < a.n_shares; ++sh) t += pool[(size_t)sh * (cv.cap + 1) + j];
+        pool[j] = t / heads;
+    }
     __threadfence_block();
     __syncthreads();
     const double one[1] = {1.0};
@@ -1334,9 +1340,9 @@ inline hipError_t launch_decode_t(const DecodeArgs& a, hipStream_t stream) {
     return hipErrorInvalidValue;
 }
 
-// A step over groups of more than eight query heads: one launch per share of GS heads (the eight-head kernel, or
-// the four-head kernel where the per-slot values of eight heads do not fit the LDS), then the finishing kernel.
-// a.q_heads, a.pool, a.n_units, a.unit0 and the tensors are set by the caller.
+// A step over groups of more than eight query heads: one workgroup per unit and share of GS heads (the eight-head
+// kernel, or the four-head kernel where the per-slot values of eight heads do not fit the LDS), then the finishing
+// kernel.  a.q_heads, a.n_shares (= ceil(q_heads / GS)), a.pool, a.n_units, a.unit0 and the tensors are set by the caller.
 template <typename T, int D, int GS>
 inline hipError_t launch_decode_pooled_share(DecodeArgs a, hipStream_t stream) {
     using Sh = DecodeShape<T, D, GS, DECODE_NW>;
@@ -1354,11 +1360,7 @@ inline hipError_t launch_decode_pooled_share(DecodeArgs a, hipStream_t stream) {
     }
     a.parts = 1;
     a.part_rows = 0;
-    for (int h0 = 0; h0 < a.q_heads; h0 += GS) {
-        a.head0 = h0;
-        a.heads = a.q_heads - h0 < GS ? a.q_heads - h0 : GS;
-        hipLaunchKernelGGL(kern, dim3(a.n_units), dim3(DECODE_NW * 64), lds, stream, a);
-    }
+    hipLaunchKernelGGL(kern, dim3(a.n_units * a.n_shares), dim3(DECODE_NW * 64), lds, stream, a);
     hipLaunchKernelGGL((decode_pool_finish_kernel<T, D, DECODE_NW>), dim3(a.n_units), dim3(DECODE_NW * 64), 0, stream, a);
     return hipGetLastError();
 }
@@ -1378,6 +1380,11 @@ inline hipError_t launch_decode_pooled_d(const DecodeArgs& a, hipStream_t stream
         case 4: return launch_decode_pooled_share<T, D, 4>(a, stream);
         default: return hipErrorInvalidValue;
     }
+}
+
+template <typename T>
+inline int decode_pool_share_heads_t(int D, int nz) {
+    return D == 64 ? decode_pool_share_heads<T, 64>(nz) : (D == 128 ? decode_pool_share_heads<T, 128>(nz) : 0);
 }
 
 template <typename T>
@@ -1405,6 +1412,9 @@ hipError_t launch_decode_bf16(const DecodeArgs& a, hipStream_t stream);
 hipError_t launch_decode_pooled_f32(const DecodeArgs& a, hipStream_t stream);
 hipError_t launch_decode_pooled_f16(const DecodeArgs& a, hipStream_t stream);
 hipError_t launch_decode_pooled_bf16(const DecodeArgs& a, hipStream_t stream);
+int decode_pool_share_heads_f32(int D, int nz);
+int decode_pool_share_heads_f16(int D, int nz);
+int decode_pool_share_heads_bf16(int D, int nz);
 size_t decode_lds_f32(int D, int G, int nz);
 size_t decode_lds_f16(int D, int G, int nz);
 size_t decode_lds_bf16(int D, int G, int nz);

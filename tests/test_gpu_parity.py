@@ -79,7 +79,7 @@ DECODE_CASES = {
                                              decode_steps=60, window=8),
     "mqa71_bf16_d64": lambda: small("mqa71_bf16_d64", dtype="bf16", q_per_kv=71, n_kv_heads=1, n_seqs=2, n_residual=3,
                                     prompt_len=400, budget=120, decode_steps=30, outliers=True),
-    # more units than the pooled sums of one launch have room for (8 x 1024): the step goes out as two launches per share
+    # more units than the pooled sums have room for (1024): the step goes out as nine launches of the shares and of the finish
     "mqa9_8256_units": lambda: small("mqa9_many_units", q_per_kv=9, n_seqs=129, n_kv_heads=64, prompt_len=0, budget=6, n_residual=1,
                                      decode_steps=9, window=4),
     # a budget at which eight heads' per-slot values do not fit the LDS: shares of four heads (13 = 4 + 4 + 4 + 1)
