@@ -34,7 +34,7 @@ def ulp_close(a, b):
     return np.abs(a32.view(np.int32).astype(np.int64) - b32.view(np.int32).astype(np.int64)) <= 1
 
 
-@pytest.mark.parametrize("G,B_r,W", [(1, 1, 4), (2, 3, 6), (4, 0, 5), (1, 2, 24)])
+@pytest.mark.parametrize("G,B_r,W", [(1, 1, 4), (2, 3, 6), (4, 0, 5), (1, 2, 24), (7, 1, 6), (12, 2, 5)])
 def test_batch_matches_the_numpy_oracle_step_by_step(G, B_r, W):
     n, d, T_max, n_steps = 5, 16, 40, 30
     Q, K, V, dq, dk, dv = make_inputs(100 + G + B_r, n, G, d, T_max, n_steps)
