@@ -65,7 +65,14 @@ def test_static_scratch_entry_point_matches_the_ordinary_one():
     # a launch that is not split needs no scratch and goes through as well
     sta_s.set_decode_parts(1); ref_s.set_decode_parts(1)
     _step_both(small, ref_s, sta_s, small.decode_steps)
-    for c in (ref_b, sta_b, ref_s, sta_s):
+    # so does a step over more than eight query heads per KV head (its pooled sums live in the cache buffer)
+    mqa = synth.Workload(name="noalloc_mqa", n_layers=1, n_seqs=2, n_kv_heads=1, q_per_kv=12, head_dim=64, dtype="bf16",
+                         prompt_len=200, budget=60, decode_steps=4, window=8, outliers=True, n_residual=1)
+    ref_m, sta_m = _twins(mqa, 0)
+    for step in range(mqa.decode_steps):
+        _step_both(mqa, ref_m, sta_m, step)
+    _same_state(mqa, ref_m, sta_m)
+    for c in (ref_b, sta_b, ref_s, sta_s, ref_m, sta_m):
         c.close()
 
 
