@@ -755,9 +755,14 @@ __global__ __launch_bounds__(NW * 64, G == 1 ? 4 : (NW == 12 ? 3 : 2)) void deco
     constexpr int EPL = Sh::EPL, LPR = Sh::LPR, RPL = Sh::RPL, R = Sh::R, PART = Sh::PART, NT = Sh::NT, UT = Sh::UT;
     constexpr bool QLDS = Sh::QLDS;
     const CacheView& cv = a.cv;
-    const int share = POOL ? (int)blockIdx.x % a.n_shares : 0;
+    // POOL: workgroup x of the grid is dispatched to XCD x % 8; the shares of one unit are given numbers that agree
+    // modulo 8 and lie 8 apart, so that they run at about the same time on one XCD and meet in its L2 (the unit's K
+    // and V come from memory once instead of once per share)
+    const int pool_r = (int)blockIdx.x >> 3;
+    const int share = POOL ? pool_r % a.n_shares : 0;
     const int Gr = POOL ? (a.q_heads - share * G < G ? a.q_heads - share * G : G) : real_heads<G>(cv);
-    const int lu = SPLIT ? (int)blockIdx.x / a.parts : (POOL ? (int)blockIdx.x / a.n_shares : (int)blockIdx.x);
+    const int lu = SPLIT ? (int)blockIdx.x / a.parts : (POOL ? (pool_r / a.n_shares) * 8 + ((int)blockIdx.x & 7) : (int)blockIdx.x);
+    if (POOL && lu >= a.n_units) return;   // the grid is rounded up to whole groups of eight units
     const int part = SPLIT ? (int)blockIdx.x % a.parts : 0;
     const int ug = a.unit0 + lu;
     const int b = (ug / cv.H) % cv.S;
@@ -1360,7 +1365,7 @@ inline hipError_t launch_decode_pooled_share(DecodeArgs a, hipStream_t stream) {
     }
     a.parts = 1;
     a.part_rows = 0;
-    hipLaunchKernelGGL(kern, dim3(a.n_units * a.n_shares), dim3(DECODE_NW * 64), lds, stream, a);
+    hipLaunchKernelGGL(kern, dim3((a.n_units + 7) / 8 * 8 * a.n_shares), dim3(DECODE_NW * 64), lds, stream, a);
     hipLaunchKernelGGL((decode_pool_finish_kernel<T, D, DECODE_NW>), dim3(a.n_units), dim3(DECODE_NW * 64), 0, stream, a);
     return hipGetLastError();
 }
