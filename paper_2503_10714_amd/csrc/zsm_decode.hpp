@@ -1370,12 +1370,24 @@ inline hipError_t launch_decode_pooled_share(DecodeArgs a, hipStream_t stream) {
     return hipGetLastError();
 }
 
-// heads per share of a pooled step: 8, or 4 where only that fits one workgroup's LDS (0: neither does)
+// waves of the four-wave kernel for GS heads that a compute unit holds at `nz` per-slot values (0: one workgroup does not fit)
+template <typename T, int D, int GS>
+inline int decode_pool_resident_waves(int nz) {
+    const size_t lds = DecodeShape<T, D, GS, DECODE_NW>::lds_bytes(nz);
+    if (lds > DECODE_LDS_MAX) return 0;
+    const int by_lds = (int)(DECODE_LDS_MAX / lds) * DECODE_NW, by_regs = decode_cu_waves<T, D, GS>();
+    return by_lds < by_regs ? by_lds : by_regs;
+}
+
+// Heads per share of a pooled step: 8, or 4 where that keeps more waves resident on a compute unit (the per-slot
+// values of 8 heads leave room for one workgroup from B of about 1000 on, those of 4 for two or three; measured
+// on 512 units of 71 heads, d = 64: 0.43 against 0.49 ms at B = 1024, where both have two workgroups resident, 0.85
+// against 0.64 at B = 1500; d = 128, 256 units: 0.42 against 0.33 at B = 1024).  0: neither fits.
 template <typename T, int D>
 inline int decode_pool_share_heads(int nz) {
-    if (DecodeShape<T, D, 8, DECODE_NW>::lds_bytes(nz) <= DECODE_LDS_MAX) return 8;
-    if (DecodeShape<T, D, 4, DECODE_NW>::lds_bytes(nz) <= DECODE_LDS_MAX) return 4;
-    return 0;
+    const int w8 = decode_pool_resident_waves<T, D, 8>(nz), w4 = decode_pool_resident_waves<T, D, 4>(nz);
+    if (w8 == 0 && w4 == 0) return 0;
+    return w4 > w8 ? 4 : 8;
 }
 
 template <typename T, int D>

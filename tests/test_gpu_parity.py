@@ -82,6 +82,9 @@ DECODE_CASES = {
     # more units than the pooled sums have room for (1024): the step goes out as nine launches of the shares and of the finish
     "mqa9_8256_units": lambda: small("mqa9_many_units", q_per_kv=9, n_seqs=129, n_kv_heads=64, prompt_len=0, budget=6, n_residual=1,
                                      decode_steps=9, window=4),
+    # shares of four heads chosen because more of them stay resident (16-bit keys, d = 128, B = 1024), 12 = 4 + 4 + 4
+    "mqa12_bf16_d128_b1024": lambda: small("mqa12_b1024", dtype="bf16", q_per_kv=12, head_dim=128, n_kv_heads=1, n_residual=1,
+                                           prompt_len=1200, budget=1024, decode_steps=8, outliers=True),
     # a budget at which eight heads' per-slot values do not fit the LDS: shares of four heads (13 = 4 + 4 + 4 + 1)
     "mqa13_f16_b2700_shares_of_four": lambda: small("mqa13_b2700", dtype="f16", q_per_kv=13, head_dim=128, n_kv_heads=1, n_residual=2,
                                                     prompt_len=2900, budget=2700, decode_steps=6, outliers=True),
