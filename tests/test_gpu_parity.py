@@ -100,6 +100,10 @@ DECODE_CASES = {
     "ragged_multi_layer": lambda: small("ragged_multi_layer", n_layers=2, n_seqs=3, dtype="f16", head_dim=128,
                                         prompt_len=300, ragged=(40, 300), budget_ratio=0.2, budget=60, decode_steps=30),
     "tiny_budget": lambda: small("tiny_budget", budget=3, prompt_len=50, decode_steps=30),            # B_p = 1, B_c = 1, B_r = 1
+    # the smallest caches there are: one slot in all (every step drops the previous token), one token slot and one residual slot
+    "one_slot_cache": lambda: small("one_slot", budget=1, prox=1, n_residual=0, prompt_len=10, decode_steps=12, window=4),
+    "one_token_one_residual": lambda: small("one_one", budget=2, prox=1, n_residual=1, prompt_len=10, decode_steps=12, window=4,
+                                            dtype="f16", head_dim=128),
     "no_context": lambda: small("no_context", prompt_len=60, budget=9, prox=8, decode_steps=30, window=8),     # B_c = 0
     # 4001 slots x 8 query heads x 8 bytes do not fit one workgroup's LDS: the step is cut over workgroups by itself
     "huge_capacity_gqa8": lambda: small("huge_capacity_gqa8", n_kv_heads=1, q_per_kv=8, head_dim=128, dtype="f16",
