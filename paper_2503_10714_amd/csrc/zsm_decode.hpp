@@ -1252,6 +1252,22 @@ constexpr size_t DECODE_LDS_MAX = 160 * 1024;   // LDS of one compute unit
 template <typename T, int D, int G, bool SPLIT, int NWK, int AWK = NWK>
 inline hipError_t launch_decode_nw(const DecodeArgs& a, hipStream_t stream);
 
+// Lets a kernel use a compute unit's whole LDS as dynamic shared memory.  The attribute is per device; bit `dev` of
+// `done` (one flag per kernel) records that it has been set there.  Two host threads that meet here for the first
+// time may both set it (harmless: same value), neither reads a torn flag.
+inline hipError_t allow_whole_lds(const void* kern, std::atomic<unsigned long long>& done) {
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    const unsigned long long bit = 1ull << (dev & 63);
+    if (!(done.load(std::memory_order_acquire) & bit)) {
+        e = hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+        if (e != hipSuccess) return e;
+        done.fetch_or(bit, std::memory_order_release);
+    }
+    return hipSuccess;
+}
+
 // waves a compute unit holds of this kernel by its registers (the launch bound's waves per SIMD, times four)
 template <typename T, int D, int G>
 constexpr int decode_cu_waves() { return G == 1 ? 16 : ((G == 4 && DecodeShape<T, D, G, DECODE_NW>::MFMA4) ? 12 : 8); }
@@ -1304,18 +1320,9 @@ inline hipError_t launch_decode_nw(const DecodeArgs& a, hipStream_t stream) {
     }
     const size_t lds = Sh::lds_bytes(nz, AWK);
     auto kern = decode_kernel<T, D, G, NWK, SPLIT, AWK>;
-    // The attribute is per device; bit `dev` records that it has been set there.  Two host threads that
-    // meet here for the first time may both set it (harmless: same value), neither reads a torn flag.
     static std::atomic<unsigned long long> attr_done{0ull};
-    int dev = 0;
-    hipError_t e = hipGetDevice(&dev);
+    const hipError_t e = allow_whole_lds(reinterpret_cast<const void*>(kern), attr_done);
     if (e != hipSuccess) return e;
-    const unsigned long long bit = 1ull << (dev & 63);
-    if (!(attr_done.load(std::memory_order_acquire) & bit)) {
-        e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
-        if (e != hipSuccess) return e;
-        attr_done.fetch_or(bit, std::memory_order_release);
-    }
     hipLaunchKernelGGL(kern, dim3(a.n_units * (SPLIT ? a.parts : 1)), dim3(NWK * 64), lds, stream, a);
     if (SPLIT) hipLaunchKernelGGL((decode_combine_kernel<T, D, G, DECODE_NW>), dim3(a.n_units), dim3(DECODE_NW * 64), 0, stream, a);
     return hipGetLastError();
@@ -1354,15 +1361,8 @@ inline hipError_t launch_decode_pooled_share(DecodeArgs a, hipStream_t stream) {
     const size_t lds = Sh::lds_bytes(a.cv.cap + 1);
     auto kern = decode_kernel<T, D, GS, DECODE_NW, false, DECODE_NW, true>;
     static std::atomic<unsigned long long> attr_done{0ull};
-    int dev = 0;
-    hipError_t e = hipGetDevice(&dev);
+    const hipError_t e = allow_whole_lds(reinterpret_cast<const void*>(kern), attr_done);
     if (e != hipSuccess) return e;
-    const unsigned long long bit = 1ull << (dev & 63);
-    if (!(attr_done.load(std::memory_order_acquire) & bit)) {
-        e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
-        if (e != hipSuccess) return e;
-        attr_done.fetch_or(bit, std::memory_order_release);
-    }
     a.parts = 1;
     a.part_rows = 0;
     hipLaunchKernelGGL(kern, dim3((a.n_units + 7) / 8 * 8 * a.n_shares), dim3(DECODE_NW * 64), lds, stream, a);
