@@ -854,13 +854,14 @@ def test_resynchronisation_after_a_permitted_flip(monkeypatch):
     cache.close()
 
 
-def test_decode_steps_replayed_from_a_hip_graph():
-    """Per-layer decode calls (split over workgroups) captured once in a HIP graph and replayed with new inputs:
-    every replay must give what the same calls give eagerly on a twin cache (the calls only enqueue kernels: no
-    allocation, no memset, no synchronisation)."""
+@pytest.mark.parametrize("heads", [1, 12])
+def test_decode_steps_replayed_from_a_hip_graph(heads):
+    """Per-layer decode calls (split over workgroups; with 12 query heads per KV head: the pooled step's two kernels)
+    captured once in a HIP graph and replayed with new inputs: every replay must give what the same calls give
+    eagerly on a twin cache (the calls only enqueue kernels: no allocation, no memset, no synchronisation)."""
     from paper_2503_10714_amd import binding as zb
-    wl = small("graph", n_layers=3, n_kv_heads=4, dtype="f16", head_dim=128, prompt_len=700, budget=300, decode_steps=6,
-               window=16, outliers=True)
+    wl = small("graph", n_layers=3, n_kv_heads=4, q_per_kv=heads, dtype="f16", head_dim=128, prompt_len=700, budget=300,
+               decode_steps=6, window=16, outliers=True)
     units = oracle_states(wl)
     caches = [pu.make_cache(wl, DEV) for _ in range(2)]
     for c in caches:
