@@ -11,6 +11,12 @@
 // write of the incoming token, all from the per-slot values kept in LDS plus 12 bytes of
 // metadata per slot.
 //
+// Launch shapes: one workgroup per unit (4 waves; 8, 12 or 16 where the per-slot values of one workgroup fill a
+// compute unit's LDS); several workgroups per unit plus decode_combine_kernel for launches of few units (SPLIT);
+// for more than eight query heads per KV head, one workgroup per unit and share of eight or four heads plus
+// decode_pool_finish_kernel (POOL).  Group sizes are compiled for 1, 2, 4 and 8 query heads; 3 and 5..7 run the
+// next one with the surplus heads masked.
+//
 // Precision.  Everything that feeds a stored score or a decision (logits, exp, L, Eq. 5's
 // dot products, Eq. 6's mean) is evaluated in fp64 and rounded once to the fp32 storage
 // type; products of two fp16/bf16/fp32 values are exact in fp64, so the logits are the
