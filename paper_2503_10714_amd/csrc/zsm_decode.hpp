@@ -492,7 +492,10 @@ struct FinishPre {
     static constexpr int NT = NW * 64;
     int pj[DECODE_MCH];      // positions and scores of slots k*NT + tid
     float sj[DECODE_MCH];
-    double ej[GE > 0 ? DECODE_MCH : 1][GE > 0 ? GE : 1];   // GE = G: their exp(logit - C) too (values that live in global memory)
+    // GE = G: their exp(logit - C) too (values that live in global memory); of the first MCHE slots only where the
+    // eight heads' values of all twelve would take 192 registers and leave one wave per SIMD
+    static constexpr int MCHE = GE >= 8 ? DECODE_MCH / 2 : DECODE_MCH;
+    double ej[GE > 0 ? MCHE : 1][GE > 0 ? GE : 1];
     int wres;                // fusion count of residual slot tid (tid < B_r), else 1
     T kn, vn;                // channel tid of the incoming token (tid < D)
     float kr0, vr0;          // B_r = 1: channel tid of the only residual slot
@@ -536,7 +539,7 @@ struct FinishPre {
         vec = (cap & 3) == 0;   // every unit's score and position rows then start on a 16-byte boundary
         if (GE > 0) {
 #pragma unroll
-            for (int k = 0; k < DECODE_MCH; ++k) {
+            for (int k = 0; k < (GE > 0 ? MCHE : 1); ++k) {
                 const int j = slot_of(k);
 #pragma unroll
                 for (int g = 0; g < (GE > 0 ? GE : 1); ++g) ej[k][g] = j < cap ? et[(size_t)g * Bz + j] : 0.0;
@@ -603,7 +606,8 @@ __device__ __forceinline__ void decode_finish(const DecodeArgs& a, const CacheVi
                     double pm = 0.0;
 #pragma unroll
                     for (int g = 0; g < G; ++g)
-                        pm += ((GE > 0 && base == 0) ? pre.ej[GE > 0 ? k : 0][GE > 0 ? g : 0] : et[(size_t)g * Bz + j]) * rL[g];
+                        pm += ((GE > 0 && base == 0 && k < FinishPre<T, D, NW, GE>::MCHE) ? pre.ej[(GE > 0 && k < FinishPre<T, D, NW, GE>::MCHE) ? k : 0][GE > 0 ? g : 0]
+                                                                                         : et[(size_t)g * Bz + j]) * rL[g];
                     pm = head_mean<G>(pm, Gr);
                     const float sn = (float)(lam * (double)pre.sj[k] + pm);
                     sn4[c4] = sn;
@@ -1121,7 +1125,7 @@ __global__ __launch_bounds__(NW * 64, G == 1 ? 4 : (NW == 12 ? 3 : 2)) void deco
 // from the per-slot values the parts left in scratch.  Latency-bound (a few dependent memory
 // round trips), so everything whose address is known up front is requested up front.
 template <typename T, int D, int G, int NW>
-__global__ __launch_bounds__(NW * 64) void decode_combine_kernel(DecodeArgs a) {
+__global__ __launch_bounds__(NW * 64, G >= 8 ? 2 : 1) void decode_combine_kernel(DecodeArgs a) {
     constexpr int NT = NW * 64;
     constexpr int MAXP = 64;   // parts per unit (the host never asks for more)
     const CacheView& cv = a.cv;
